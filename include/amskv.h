@@ -1,0 +1,173 @@
+/*
+ * amskv.h -- C ABI of the AMS-KV hot path for AMD MI355X (gfx950).
+ *
+ * AMS-KV (arxiv 2511.16047) is a per-layer KV-cache policy for next-scale-prediction
+ * visual autoregressive transformers: an image is generated as S scales of h_s x w_s
+ * tokens (Section 3.1, Eq. 1-2); the tokens of scale s attend to every cached earlier
+ * scale and, bidirectionally, to their own scale.  Each layer keeps the first few
+ * "condensed" scales for good, a rolling window of "local" scales just before the
+ * current one, and drops the "intermediate" ones (Section 4.1, Section 4.3, Algorithm 2);
+ * layers whose adjacent-scale keys are dissimilar (Eq. 3) are "cache-demanding" and keep
+ * more (Section 4.2).
+ *
+ * This library owns only host-side metadata.  All device memory -- the inputs, the
+ * outputs and the cache arena -- is allocated by the caller and passed as plain device
+ * pointers.  Every call that touches device memory enqueues its kernels on the
+ * hipStream_t passed as `stream` (NULL = the null stream) and returns without waiting,
+ * except where stated.  No call allocates or frees device memory.
+ *
+ * Tensor layouts (all row-major, contiguous):
+ *   Q, K, V, O of scale s : [B][H][T_s][D],  T_s = side_h[s]*side_w[s], tokens of a scale
+ *                           in row-major grid order
+ *   cache of layer l      : K[B][H][cap_l][D] followed by V[B][H][cap_l][D] inside the
+ *                           arena; the kept scales sit back to back in ascending scale
+ *                           order (AMSKV_LAYOUT_COMPACT) or at offsets fixed at create
+ *                           time (AMSKV_LAYOUT_PLANNED); amskv_cache_layout reports them
+ * Element type: float (dtype 0) or bfloat16 (dtype 1), the same for every tensor.
+ *
+ * Every function returns an amskv_status (0 = ok, negative = error) unless stated.
+ * On error nothing has been enqueued and the cache state is unchanged.
+ */
+#ifndef AMSKV_H
+#define AMSKV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  AMSKV_OK = 0,
+  AMSKV_ERR_INVALID_ARG = -1,     /* null pointer, bad size, unsupported head_dim/dtype      */
+  AMSKV_ERR_ORDER = -2,           /* scales not appended in order / attend on a stale scale  */
+  AMSKV_ERR_EVICTED = -3,         /* the call needs a scale that is not resident             */
+  AMSKV_ERR_ARENA_TOO_SMALL = -4, /* arena_bytes < amskv_cache_required_bytes                 */
+  AMSKV_ERR_HIP = -5,             /* a HIP runtime call failed (launch, copy, sync)          */
+  AMSKV_ERR_NO_DEVICE_MEMORY = -6 /* device work asked of a plan-only cache (arena == NULL)  */
+} amskv_status;
+
+enum { AMSKV_DTYPE_F32 = 0, AMSKV_DTYPE_BF16 = 1 };
+enum { AMSKV_LAYOUT_COMPACT = 0, AMSKV_LAYOUT_PLANNED = 1 };
+enum { AMSKV_MAX_SCALES = 16 };
+
+typedef struct amskv_cache amskv_cache; /* opaque, host memory, owned by the library */
+
+/* The scale schedule (Section 3.1/3.2): n_scales grids of side_h[s] x side_w[s] tokens,
+ * generated in this order.  `batch` is the literal batch B (a caller that doubles the
+ * batch for classifier-free guidance passes the doubled value). */
+typedef struct {
+  int32_t n_scales;       /* 1 .. AMSKV_MAX_SCALES                       */
+  const int32_t* side_h;  /* host, [n_scales], each >= 1                  */
+  const int32_t* side_w;  /* host, [n_scales], each >= 1                  */
+  int32_t batch;          /* B >= 1                                       */
+  int32_t dtype;          /* AMSKV_DTYPE_F32 or AMSKV_DTYPE_BF16          */
+} amskv_schedule;
+
+/* Per-layer policy in scale units (Section 4.3; Algorithm 2 with budgets counted in whole
+ * scales): after scale s is appended the layer holds scales {0..n_condensed-1}, the
+ * `window` scales before s, and s, clipped to [0, s].  keep_all != 0 keeps every scale
+ * (a cache-demanding layer with an unlimited budget, and the vanilla baseline). */
+typedef struct {
+  int32_t n_condensed;    /* >= 0 */
+  int32_t window;         /* >= 0 */
+  int32_t keep_all;       /* 0 / 1 */
+} amskv_layer_policy;
+
+typedef struct {
+  int32_t n_layers;                 /* must equal `layers` of the create call            */
+  const amskv_layer_policy* layer;  /* host, [n_layers]                                   */
+  float softmax_scale;              /* 0 => 1/sqrt(head_dim)                              */
+  int32_t layout;                   /* AMSKV_LAYOUT_COMPACT or AMSKV_LAYOUT_PLANNED       */
+} amskv_policy;
+
+/* Bytes the arena must have for this configuration: for every layer the K and V regions
+ * sized for the largest kept set the policy ever reaches (Section 4.3: capacity is fixed
+ * per layer), plus a small reduction workspace for amskv_interscale_similarity.
+ * Host only. */
+int32_t amskv_cache_required_bytes(int32_t layers, int32_t heads, int32_t head_dim,
+                                   const amskv_schedule* schedule, const amskv_policy* policy,
+                                   uint64_t* bytes_out);
+
+/* Create the cache (problem statement of Section 4.3: one independent cache per layer,
+ * governed by the policy).  arena_dev: device pointer, 256-byte aligned, at least
+ * required_bytes long, owned by the caller and kept alive until destroy; it need not be
+ * initialised.  arena_dev == NULL creates a plan-only cache: append calls with NULL K/V
+ * advance the metadata (layout, bytes held, eviction lists) without touching a GPU, and
+ * device calls return AMSKV_ERR_NO_DEVICE_MEMORY.  head_dim must be 64 or 128.
+ * The schedule and policy structs are copied.  Host only. */
+int32_t amskv_cache_create(int32_t layers, int32_t heads, int32_t head_dim,
+                           const amskv_schedule* schedule, const amskv_policy* policy,
+                           void* arena_dev, uint64_t arena_bytes, amskv_cache** out);
+
+/* Append scale s to layer `layer` (Algorithm 1's append + rolling step, Algorithm 2's
+ * eviction at scale granularity): scales that fall outside the policy are evicted, the
+ * surviving scales are slid down so the kept set stays contiguous (COMPACT layout), and
+ * K_dev/V_dev ([B][H][T_s][D], device) are copied to their slot.  Scales must arrive in
+ * order 0,1,2,... per layer (else AMSKV_ERR_ORDER).  The host metadata is updated before
+ * the call returns, the device work is asynchronous on `stream`; K_dev/V_dev must stay
+ * valid until it has run.  K_dev == V_dev == NULL updates metadata only. */
+int32_t amskv_append_scale(amskv_cache* cache, int32_t layer, int32_t s,
+                           const void* K_dev, const void* V_dev, void* stream);
+
+/* Self-attention of generation step s in layer `layer` (Section 3.1: scale s attends to
+ * the cached scales and to itself, no mask inside the step):
+ *   O[b,h,i,:] = sum_j softmax_j(Q[b,h,i,:].K~[b,h,j,:] * softmax_scale) V~[b,h,j,:]
+ * with K~,V~ the concatenation of the resident scales of the layer (scale s included).
+ * s must be the scale appended last to this layer (else AMSKV_ERR_ORDER).
+ * Q_dev, O_dev: device, [B][H][T_s][D].  bf16: fp32 accumulation and softmax, P rounded
+ * to bf16 before the PV product, O rounded to bf16.  Asynchronous on `stream`. */
+int32_t amskv_attend(amskv_cache* cache, int32_t layer, int32_t s,
+                     const void* Q_dev, void* O_dev, void* stream);
+
+/* Inter-scale similarity of Eq. 3 between scale s and scale s-1 resized bilinearly
+ * (half-pixel centres, edge clamp) to the grid of scale s, computed from the cache.
+ * Both scales must be resident (else AMSKV_ERR_EVICTED); s >= 1.
+ *   cosK_host[h]   mean over (batch, token) of the cosine between k_s[t] and k^_{s-1}[t]
+ *   cosV_host[h]   the same for the values, or NULL to skip
+ *   sums_host[h*3+{0,1,2}]  sum k.k^, sum |k|^2, sum |k^|^2 over (batch, token, channel)
+ *                  of the keys, or NULL; Eq. 3's score is -sqrt(s1 + s2 - 2 s0)
+ * Outputs are host arrays of `heads` (resp. 3*heads) floats.  fp32 arithmetic, fixed
+ * reduction order (deterministic).  Waits for `stream` before returning. */
+int32_t amskv_interscale_similarity(amskv_cache* cache, int32_t layer, int32_t s,
+                                    float* cosK_host, float* cosV_host, float* sums_host,
+                                    void* stream);
+
+/* Resident segments of a layer, ascending scale id: n_seg entries written to each
+ * caller array of at least AMSKV_MAX_SCALES elements.  tok_offset is the position of the
+ * segment inside the [cap_l] token axis of the layer's K and V regions.  Host only. */
+int32_t amskv_cache_layout(const amskv_cache* cache, int32_t layer, int32_t* n_seg,
+                           int32_t* scale_id, int64_t* tok_offset, int32_t* tok_len);
+
+/* Scales dropped by the most recent append to this layer (ascending), for inspection. */
+int32_t amskv_cache_last_evicted(const amskv_cache* cache, int32_t layer, int32_t* n_evicted,
+                                 int32_t* scale_id);
+
+/* K+V bytes resident in a layer: 2 * elem * B * H * D * sum of T_k over resident scales
+ * (Eq. 4's accounting with its constant written as 2*elem).  include_current == 0 leaves
+ * out the newest scale (Algorithm 1 never stores a scale larger than C_max, so the
+ * paper's end-of-generation figure excludes it).  Negative status on error.  Host only. */
+int64_t amskv_cache_bytes_held(const amskv_cache* cache, int32_t layer, int32_t include_current);
+
+/* Token capacity cap_l of a layer's K (and V) region, or a negative status. */
+int64_t amskv_cache_capacity_tokens(const amskv_cache* cache, int32_t layer);
+
+/* Copy the resident scales of a layer, ascending and back to back, into
+ * K_out_dev/V_out_dev ([B][H][T_kept][D], device, caller-owned; either may be NULL).
+ * For bit-exact checks of slot selection, eviction and compaction.  Asynchronous. */
+int32_t amskv_cache_export(const amskv_cache* cache, int32_t layer,
+                           void* K_out_dev, void* V_out_dev, void* stream);
+
+/* Forget every appended scale of every layer (metadata only; the arena is not cleared). */
+int32_t amskv_cache_reset(amskv_cache* cache);
+
+/* Free the host metadata.  The arena stays the caller's. */
+void amskv_cache_destroy(amskv_cache* cache);
+
+/* Static text for a status code. */
+const char* amskv_status_string(int32_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AMSKV_H */

@@ -140,13 +140,14 @@ def kv_mem_saving_eq4(tokens: Sequence[int], batch: int, heads: int, head_dim: i
 # --------------------------------------------------------------------------- mask + attention
 def allow_mask(tokens: Sequence[int], policy: Policy) -> np.ndarray:
     """Explicit T x T boolean mask over the whole sequence: allow[q, k]."""
-    sc = scale_of_token(tokens)
-    n = sc.shape[0]
+    st = scale_starts(tokens)
+    n = sum(int(t) for t in tokens)
     allow = np.zeros((n, n), dtype=bool)
-    for q in range(n):
+    for q_scale in range(len(tokens)):
         for k_scale in range(len(tokens)):
-            if visible(policy, int(sc[q]), k_scale):
-                allow[q, sc == k_scale] = True
+            if visible(policy, q_scale, k_scale):
+                allow[st[q_scale]: st[q_scale] + int(tokens[q_scale]),
+                      st[k_scale]: st[k_scale] + int(tokens[k_scale])] = True
     return allow
 
 
@@ -177,17 +178,30 @@ def attend_step(q_scales: Sequence[np.ndarray], k_scales: Sequence[np.ndarray],
                 s: int, softmax_scale: float | None = None) -> np.ndarray:
     """Output rows of generation step s, [..., T_s, D] (fp64).
 
-    Builds the whole-sequence tensors and mask up to scale s (later scales cannot be
-    seen by scale s, so leaving them out changes nothing) and slices the rows of s.
+    Builds the whole-sequence K, V and mask up to scale s (later scales cannot be seen by
+    scale s, so leaving them out changes nothing) and evaluates the rows of scale s.
     """
     toks = list(tokens[: s + 1])
-    q_all = np.concatenate([np.asarray(x, dtype=np.float64) for x in q_scales[: s + 1]], axis=-2)
     k_all = np.concatenate([np.asarray(x, dtype=np.float64) for x in k_scales[: s + 1]], axis=-2)
     v_all = np.concatenate([np.asarray(x, dtype=np.float64) for x in v_scales[: s + 1]], axis=-2)
     allow = allow_mask(toks, policy)
-    o = masked_attention(q_all, k_all, v_all, allow, softmax_scale)
     st = scale_starts(toks)[s]
-    return o[..., st: st + toks[s], :]
+    # only the query rows of scale s are wanted: take those rows of Q and of the mask
+    return masked_attention(np.asarray(q_scales[s], dtype=np.float64), k_all, v_all,
+                            allow[st: st + toks[s], :], softmax_scale)
+
+
+def attend_all_steps(q_scales: Sequence[np.ndarray], k_scales: Sequence[np.ndarray],
+                     v_scales: Sequence[np.ndarray], tokens: Sequence[int], policy: Policy,
+                     softmax_scale: float | None = None) -> List[np.ndarray]:
+    """Every generation step at once: one masked attention over the whole sequence, then the
+    rows of each scale.  Same numbers as attend_step(s) for every s."""
+    q_all = np.concatenate([np.asarray(x, dtype=np.float64) for x in q_scales], axis=-2)
+    k_all = np.concatenate([np.asarray(x, dtype=np.float64) for x in k_scales], axis=-2)
+    v_all = np.concatenate([np.asarray(x, dtype=np.float64) for x in v_scales], axis=-2)
+    o = masked_attention(q_all, k_all, v_all, allow_mask(tokens, policy), softmax_scale)
+    st = scale_starts(tokens)
+    return [o[..., st[s]: st[s] + int(tokens[s]), :] for s in range(len(tokens))]
 
 
 # --------------------------------------------------------------------------- cache contents

@@ -1,0 +1,130 @@
+// Bandwidth-bound cache kernels: evict + compact + append (Algorithm 1's append and rolling
+// step, Algorithm 2's eviction, at scale granularity) and the read-back export.
+// All traffic is 16-byte vector loads/stores, consecutive lanes on consecutive chunks.
+#include "amskv_internal.hpp"
+
+namespace amskv {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kUnroll = 4;  // 16-byte chunks in flight per thread and pass
+
+__device__ __forceinline__ void wait_all_vector_loads() {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
+// One workgroup owns one (b,h) row of one tensor (blockIdx.y: 0 = K, 1 = V).
+//
+// Phase 1 slides the surviving segments toward offset 0.  The moved chunks, taken in
+// ascending address order, have strictly increasing source and destination addresses with
+// dst < src, so a pass that first loads all of its chunks, waits for the data, meets at a
+// barrier and only then stores can never overwrite a chunk that a later pass still has to
+// read: a store to address X can only alias the source of an EARLIER chunk.
+// Phase 2 copies the new scale into its slot; that slot may overlap the old position of a
+// moved segment, so it starts after the last pass's barrier.
+__global__ __launch_bounds__(kThreads) void append_kernel(char* __restrict__ kc, char* __restrict__ vc,
+                                                          const char* __restrict__ k_new,
+                                                          const char* __restrict__ v_new, int row_bytes,
+                                                          long long cap_tokens, MoveList mv, int t_new,
+                                                          int dst_new) {
+  const int tid = threadIdx.x;
+  const long long bh = blockIdx.x;
+  char* base = (blockIdx.y ? vc : kc) + bh * cap_tokens * row_bytes;
+  const char* src_new = (blockIdx.y ? v_new : k_new) + bh * (long long)t_new * row_bytes;
+  const int cpr = row_bytes >> 4;  // chunks per token row
+
+  int total = 0;
+  for (int i = 0; i < mv.n; ++i) total += mv.len[i] * cpr;
+
+  for (int c0 = 0; c0 < total; c0 += kThreads * kUnroll) {
+    uint4 buf[kUnroll];
+    long long dst_byte[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int c = c0 + u * kThreads + tid;
+      dst_byte[u] = -1;
+      if (c < total) {
+        int rem = c, src_tok = 0, dst_tok = 0;
+        for (int i = 0; i < mv.n; ++i) {
+          const int n = mv.len[i] * cpr;
+          if (rem < n) {
+            src_tok = mv.src[i];
+            dst_tok = mv.dst[i];
+            break;
+          }
+          rem -= n;
+        }
+        const long long so = (long long)src_tok * row_bytes + ((long long)rem << 4);
+        dst_byte[u] = (long long)dst_tok * row_bytes + ((long long)rem << 4);
+        buf[u] = *reinterpret_cast<const uint4*>(base + so);
+      }
+    }
+    wait_all_vector_loads();
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+      if (dst_byte[u] >= 0) *reinterpret_cast<uint4*>(base + dst_byte[u]) = buf[u];
+  }
+  if (total > 0) {
+    wait_all_vector_loads();
+    __syncthreads();
+  }
+
+  const int n_new = t_new * cpr;
+  char* dst = base + (long long)dst_new * row_bytes;
+  for (int c0 = 0; c0 < n_new; c0 += kThreads * kUnroll) {
+    uint4 buf[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int c = c0 + u * kThreads + tid;
+      if (c < n_new) buf[u] = *reinterpret_cast<const uint4*>(src_new + ((long long)c << 4));
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int c = c0 + u * kThreads + tid;
+      if (c < n_new) *reinterpret_cast<uint4*>(dst + ((long long)c << 4)) = buf[u];
+    }
+  }
+}
+
+// Gather the resident segments, ascending and back to back, into [BH][T_kept][row].
+__global__ __launch_bounds__(kThreads) void export_kernel(const char* __restrict__ kc,
+                                                          const char* __restrict__ vc, char* __restrict__ k_out,
+                                                          char* __restrict__ v_out, int row_bytes,
+                                                          long long cap_tokens, SegTable seg) {
+  const long long bh = blockIdx.x;
+  const char* base = (blockIdx.y ? vc : kc) + bh * cap_tokens * row_bytes;
+  char* out = blockIdx.y ? v_out : k_out;
+  if (!out) return;
+  out += bh * (long long)seg.total * row_bytes;
+  const int cpr = row_bytes >> 4;
+  const int n = seg.total * cpr;
+  for (int c = threadIdx.x; c < n; c += kThreads) {
+    const int tok = c / cpr, piece = c - tok * cpr;
+    int delta = 0;
+    for (int i = 0; i < seg.n; ++i)
+      if (tok >= seg.virt_start[i]) delta = seg.phys_off[i] - seg.virt_start[i];
+    const long long so = (long long)(tok + delta) * row_bytes + (piece << 4);
+    *reinterpret_cast<uint4*>(out + ((long long)c << 4)) = *reinterpret_cast<const uint4*>(base + so);
+  }
+}
+
+}  // namespace
+
+hipError_t launch_append(void* kc, void* vc, const void* k_new, const void* v_new, int bh, int row_bytes,
+                         int64_t cap_tokens, const MoveList& mv, int t_new, int dst_new, hipStream_t st) {
+  dim3 grid(bh, 2), block(kThreads);
+  hipLaunchKernelGGL(append_kernel, grid, block, 0, st, (char*)kc, (char*)vc, (const char*)k_new,
+                     (const char*)v_new, row_bytes, (long long)cap_tokens, mv, t_new, dst_new);
+  return hipGetLastError();
+}
+
+hipError_t launch_export(const void* kc, const void* vc, void* k_out, void* v_out, int bh, int row_bytes,
+                         int64_t cap_tokens, const SegTable& seg, hipStream_t st) {
+  dim3 grid(bh, 2), block(kThreads);
+  hipLaunchKernelGGL(export_kernel, grid, block, 0, st, (const char*)kc, (const char*)vc, (char*)k_out,
+                     (char*)v_out, row_bytes, (long long)cap_tokens, seg);
+  return hipGetLastError();
+}
+
+}  // namespace amskv

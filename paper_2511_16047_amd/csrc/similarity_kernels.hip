@@ -1,0 +1,165 @@
+// Inter-scale similarity (Eq. 3): scale s-1 is resized bilinearly to the grid of scale s on
+// the fly (never materialised) and compared with scale s, straight from the cache.
+// Bandwidth-bound: each token row is read with 16-byte loads by consecutive lanes.
+// Reduction order is fixed (lane tree -> workgroup tree -> sequential over batch), so the
+// result is deterministic from run to run.
+#include "amskv_internal.hpp"
+
+namespace amskv {
+namespace {
+
+constexpr int kThreads = 256;
+
+template <bool BF16>
+struct Chunk;  // one 16-byte piece of a token row, widened to fp32
+
+template <>
+struct Chunk<true> {
+  static constexpr int N = 8;
+  float v[8];
+  __device__ __forceinline__ void load(const char* p) {
+    const uint4 r = *reinterpret_cast<const uint4*>(p);
+    const unsigned w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[2 * i] = __uint_as_float(w[i] << 16);
+      v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+  }
+};
+
+template <>
+struct Chunk<false> {
+  static constexpr int N = 4;
+  float v[4];
+  __device__ __forceinline__ void load(const char* p) {
+    const float4 r = *reinterpret_cast<const float4*>(p);
+    v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w;
+  }
+};
+
+// Source coordinate of the bilinear resize with half-pixel centres, clamped to the grid.
+__device__ __forceinline__ void taps(int dst, int n_in, int n_out, int& i0, int& i1, float& lam) {
+  float src = ((float)dst + 0.5f) * ((float)n_in / (float)n_out) - 0.5f;
+  src = fminf(fmaxf(src, 0.f), (float)(n_in - 1));
+  const float f = floorf(src);
+  i0 = (int)f;
+  i1 = min(i0 + 1, n_in - 1);
+  lam = src - f;
+}
+
+// grid: (B*H, tensors); one workgroup per (b,h) of one tensor (0 = keys, 1 = values).
+// partial[(tensor*BH + bh)*4 + {0,1,2,3}] = sum_t cos_t, sum a.b, sum |a|^2, sum |b|^2.
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void similarity_partial_kernel(
+    const char* __restrict__ kc, const char* __restrict__ vc, int row_bytes, long long cap_tokens,
+    int off_cur, int off_prev, int h_cur, int w_cur, int h_prev, int w_prev, float* __restrict__ partial) {
+  const long long bh = blockIdx.x;
+  const char* base = (blockIdx.y ? vc : kc) + bh * cap_tokens * row_bytes;
+  const char* cur = base + (long long)off_cur * row_bytes;
+  const char* prev = base + (long long)off_prev * row_bytes;
+  const int lpt = row_bytes >> 4;          // lanes per token: 8, 16 or 32
+  const int sub = threadIdx.x % lpt;       // which 16-byte piece of the row
+  const int slot = threadIdx.x / lpt;
+  const int tok_per_pass = kThreads / lpt;
+  const int t_cur = h_cur * w_cur;
+
+  float acc_cos = 0.f, acc_ab = 0.f, acc_aa = 0.f, acc_bb = 0.f;
+  for (int t0 = 0; t0 < t_cur; t0 += tok_per_pass) {
+    const int t = t0 + slot;
+    float ab = 0.f, aa = 0.f, bb = 0.f;
+    if (t < t_cur) {
+      const int i = t / w_cur, j = t - i * w_cur;
+      int r0, r1, c0, c1;
+      float lr, lc;
+      taps(i, h_prev, h_cur, r0, r1, lr);
+      taps(j, w_prev, w_cur, c0, c1, lc);
+      Chunk<BF16> a, p00, p01, p10, p11;
+      a.load(cur + (long long)t * row_bytes + (sub << 4));
+      p00.load(prev + (long long)(r0 * w_prev + c0) * row_bytes + (sub << 4));
+      p01.load(prev + (long long)(r0 * w_prev + c1) * row_bytes + (sub << 4));
+      p10.load(prev + (long long)(r1 * w_prev + c0) * row_bytes + (sub << 4));
+      p11.load(prev + (long long)(r1 * w_prev + c1) * row_bytes + (sub << 4));
+#pragma unroll
+      for (int e = 0; e < Chunk<BF16>::N; ++e) {
+        const float left = p00.v[e] * (1.f - lr) + p10.v[e] * lr;    // rows first,
+        const float right = p01.v[e] * (1.f - lr) + p11.v[e] * lr;
+        const float b = left * (1.f - lc) + right * lc;              // then columns
+        ab += a.v[e] * b;
+        aa += a.v[e] * a.v[e];
+        bb += b * b;
+      }
+    }
+    // sum over the lanes that share a token (lpt is a power of two <= 32)
+    for (int m = 1; m < lpt; m <<= 1) {
+      ab += __shfl_xor(ab, m, 64);
+      aa += __shfl_xor(aa, m, 64);
+      bb += __shfl_xor(bb, m, 64);
+    }
+    if (sub == 0 && t < t_cur) {
+      acc_cos += ab / fmaxf(sqrtf(aa) * sqrtf(bb), 1e-12f);
+      acc_ab += ab;
+      acc_aa += aa;
+      acc_bb += bb;
+    }
+  }
+
+  __shared__ float red[4][kThreads];
+  red[0][threadIdx.x] = acc_cos;
+  red[1][threadIdx.x] = acc_ab;
+  red[2][threadIdx.x] = acc_aa;
+  red[3][threadIdx.x] = acc_bb;
+  __syncthreads();
+  for (int m = kThreads / 2; m > 0; m >>= 1) {
+    if (threadIdx.x < m)
+      for (int q = 0; q < 4; ++q) red[q][threadIdx.x] += red[q][threadIdx.x + m];
+    __syncthreads();
+  }
+  if (threadIdx.x < 4)
+    partial[((long long)blockIdx.y * gridDim.x + bh) * 4 + threadIdx.x] = red[threadIdx.x][0];
+}
+
+// totals[(tensor*H + h)*4 + q] = sum over b (ascending) of partial[(tensor*B*H + b*H + h)*4 + q].
+__global__ void similarity_total_kernel(const float* __restrict__ partial, int batch, int heads, int tensors,
+                                        float* __restrict__ totals) {
+  const int id = blockIdx.x * blockDim.x + threadIdx.x;
+  if (id >= tensors * heads * 4) return;
+  const int q = id & 3, h = (id >> 2) % heads, tn = (id >> 2) / heads;
+  // compensated (Kahan) sum in ascending batch order: small fp32 error, fixed order
+  float s = 0.f, comp = 0.f;
+  for (int b = 0; b < batch; ++b) {
+    const float x = partial[(((long long)tn * batch + b) * heads + h) * 4 + q];
+    const float y = x - comp;
+    const float t = s + y;
+    comp = (t - s) - y;
+    s = t;
+  }
+  totals[id] = s;
+}
+
+}  // namespace
+
+hipError_t launch_similarity(const void* kc, const void* vc, int batch, int heads, int head_dim, int dtype,
+                             int64_t cap_tokens, int off_cur, int off_prev, int h_cur, int w_cur, int h_prev,
+                             int w_prev, float* partial_ws, float* out_dev, hipStream_t st) {
+  const int tensors = vc ? 2 : 1;
+  const int bh = batch * heads;
+  dim3 grid(bh, tensors), block(kThreads);
+  if (dtype == AMSKV_DTYPE_BF16) {
+    hipLaunchKernelGGL(similarity_partial_kernel<true>, grid, block, 0, st, (const char*)kc, (const char*)vc,
+                       head_dim * 2, (long long)cap_tokens, off_cur, off_prev, h_cur, w_cur, h_prev, w_prev,
+                       partial_ws);
+  } else {
+    hipLaunchKernelGGL(similarity_partial_kernel<false>, grid, block, 0, st, (const char*)kc, (const char*)vc,
+                       head_dim * 4, (long long)cap_tokens, off_cur, off_prev, h_cur, w_cur, h_prev, w_prev,
+                       partial_ws);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int n = tensors * heads * 4;
+  hipLaunchKernelGGL(similarity_total_kernel, dim3((n + 63) / 64), dim3(64), 0, st, (const float*)partial_ws,
+                     batch, heads, tensors, out_dev);
+  return hipGetLastError();
+}
+
+}  // namespace amskv

@@ -1,0 +1,152 @@
+"""Host logic of the library (policy -> kept set, offsets, eviction lists, bytes held, status
+codes) against the oracle, through the C ABI on a plan-only cache: no GPU needed."""
+import itertools
+import os
+import re
+
+import pytest
+
+import paper_2511_16047_amd as amskv
+from oracle import amskv_oracle as orc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+VAR = (1, 2, 3, 4, 5, 6, 8, 10, 13, 16)
+INF = (1, 2, 4, 6, 8, 12, 16, 20, 24, 32, 40, 48, 64)
+
+
+def test_library_exports_every_declared_symbol():
+    lib = amskv.load_library()
+    text = open(os.path.join(ROOT, "include", "amskv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(amskv_[a-z_]+)\s*\(", text))
+    assert names == set(amskv.binding.EXPORTED)
+    for n in sorted(names):
+        assert hasattr(lib, n), n
+
+
+def _plan_cache(sides, policies, layout=amskv.AMSKV_LAYOUT_COMPACT, B=2, H=3, D=64, dtype=amskv.AMSKV_DTYPE_BF16):
+    return amskv.amskv_cache_create(len(policies), H, D, sides, sides, B, dtype, policies, 0.0, layout)
+
+
+@pytest.mark.parametrize("sides", [VAR, INF, (1, 2, 3), (2, 2, 5, 3)])
+def test_compact_layout_matches_oracle(sides):
+    tokens = [s * s for s in sides]
+    pols = [(c, w, False) for c, w in itertools.product(range(5), range(5))] + [(0, 0, True), (2, 1, True)]
+    B, H, D = 2, 3, 64
+    h = _plan_cache(sides, pols, B=B, H=H, D=D)
+    try:
+        for l, pol in enumerate(pols):
+            assert amskv.amskv_cache_capacity_tokens(h, l) == orc.cache_capacity(tokens, pol)
+        for s in range(len(sides)):
+            for l, pol in enumerate(pols):
+                amskv.amskv_append_scale(h, l, s)
+                kept = orc.kept_scales(pol, s)
+                offs = orc.segment_offsets(tokens, pol, s)
+                assert amskv.amskv_cache_layout(h, l) == [(k, o, tokens[k]) for k, o in zip(kept, offs)]
+                assert amskv.amskv_cache_last_evicted(h, l) == orc.evicted_scales(pol, s)
+                for inc in (True, False):
+                    assert amskv.amskv_cache_bytes_held(h, l, inc) == orc.bytes_held(tokens, pol, s, B, H, D, 2, inc)
+    finally:
+        amskv.amskv_cache_destroy(h)
+
+
+@pytest.mark.parametrize("sides", [VAR, INF])
+def test_planned_layout_is_overlap_free_fixed_and_tight(sides):
+    tokens = [s * s for s in sides]
+    pols = [(c, w, False) for c, w in itertools.product(range(4), range(5))] + [(0, 0, True)]
+    h = _plan_cache(sides, pols, layout=amskv.AMSKV_LAYOUT_PLANNED)
+    try:
+        slot = [dict() for _ in pols]
+        for s in range(len(sides)):
+            for l, pol in enumerate(pols):
+                amskv.amskv_append_scale(h, l, s)
+                lay = amskv.amskv_cache_layout(h, l)
+                assert [k for k, _, _ in lay] == orc.kept_scales(pol, s)
+                cap = amskv.amskv_cache_capacity_tokens(h, l)
+                spans = sorted((o, o + n) for _, o, n in lay)
+                for (a0, a1), (b0, b1) in zip(spans, spans[1:]):
+                    assert a1 <= b0
+                assert spans[-1][1] <= cap
+                for k, o, n in lay:
+                    assert n == tokens[k]
+                    assert slot[l].setdefault(k, o) == o     # a scale never moves
+        for l, pol in enumerate(pols):
+            # no data movement, and no more memory than the compacting layout needs
+            assert amskv.amskv_cache_capacity_tokens(h, l) == orc.cache_capacity(tokens, pol)
+    finally:
+        amskv.amskv_cache_destroy(h)
+
+
+def test_required_bytes_closed_form():
+    B, H, D = 4, 5, 64
+    pols = [(2, 2, False), (0, 0, True)]
+    need = amskv.amskv_cache_required_bytes(2, H, D, VAR, VAR, B, amskv.AMSKV_DTYPE_BF16, pols)
+    kv = sum(2 * B * H * cap * D * 2 for cap in (530, 680))
+    ws = (2 * B * H * 4 + 2 * H * 4) * 4
+    assert kv + ws <= need <= kv + ws + 5 * 256
+    need32 = amskv.amskv_cache_required_bytes(2, H, D, VAR, VAR, B, amskv.AMSKV_DTYPE_F32, pols)
+    assert need32 >= 2 * kv
+
+
+def test_status_codes():
+    E = amskv.AmskvError
+    pol = [(2, 1, False)]
+    with pytest.raises(E) as e:
+        amskv.amskv_cache_create(1, 4, 48, VAR, VAR, 1, 1, pol)           # head_dim
+    assert e.value.status == amskv.AMSKV_ERR_INVALID_ARG
+    with pytest.raises(E) as e:
+        amskv.amskv_cache_create(2, 4, 64, VAR, VAR, 1, 1, pol)           # layers != n_layers
+    assert e.value.status == amskv.AMSKV_ERR_INVALID_ARG
+    with pytest.raises(E) as e:
+        amskv.amskv_cache_create(1, 4, 64, (1, 0, 3), (1, 2, 3), 1, 1, pol)  # empty scale
+    assert e.value.status == amskv.AMSKV_ERR_INVALID_ARG
+    with pytest.raises(E) as e:
+        amskv.amskv_cache_create(1, 4, 64, VAR, VAR, 1, 7, pol)           # dtype
+    assert e.value.status == amskv.AMSKV_ERR_INVALID_ARG
+    with pytest.raises(E) as e:
+        amskv.amskv_cache_create(1, 4, 64, VAR, VAR, 1, 1, [(-1, 1, False)])
+    assert e.value.status == amskv.AMSKV_ERR_INVALID_ARG
+    with pytest.raises(E) as e:
+        amskv.amskv_cache_create(1, 4, 64, tuple(range(1, 19)), tuple(range(1, 19)), 1, 1, pol)  # > 16 scales
+    assert e.value.status == amskv.AMSKV_ERR_INVALID_ARG
+
+    lib = amskv.load_library()
+    import ctypes as C
+    sc, po, keep = amskv.binding._structs(VAR, VAR, 1, 1, pol, 0.0, 0)
+    out = C.c_void_p(None)
+    # a non-null (never dereferenced) arena that is too small / misaligned
+    assert lib.amskv_cache_create(1, 4, 64, C.byref(sc), C.byref(po), C.c_void_p(4096), 1024, C.byref(out)) == amskv.AMSKV_ERR_ARENA_TOO_SMALL
+    assert lib.amskv_cache_create(1, 4, 64, C.byref(sc), C.byref(po), C.c_void_p(4100), 1 << 40, C.byref(out)) == amskv.AMSKV_ERR_INVALID_ARG
+    assert out.value is None
+
+    h = amskv.amskv_cache_create(1, 4, 64, VAR, VAR, 1, 1, pol)
+    try:
+        with pytest.raises(E) as e:
+            amskv.amskv_append_scale(h, 0, 1)                              # scale 1 before scale 0
+        assert e.value.status == amskv.AMSKV_ERR_ORDER
+        with pytest.raises(E) as e:
+            amskv.amskv_append_scale(h, 3, 0)                              # no such layer
+        assert e.value.status == amskv.AMSKV_ERR_INVALID_ARG
+        assert lib.amskv_attend(h, 0, 0, C.c_void_p(256), C.c_void_p(256), None) == amskv.AMSKV_ERR_ORDER  # nothing appended
+        for s in range(5):
+            amskv.amskv_append_scale(h, 0, s)
+        with pytest.raises(E) as e:
+            amskv.amskv_append_scale(h, 0, 4)                              # twice
+        assert e.value.status == amskv.AMSKV_ERR_ORDER
+        assert lib.amskv_attend(h, 0, 3, C.c_void_p(256), C.c_void_p(256), None) == amskv.AMSKV_ERR_ORDER  # stale scale
+        assert lib.amskv_attend(h, 0, 4, C.c_void_p(256), C.c_void_p(256), None) == amskv.AMSKV_ERR_NO_DEVICE_MEMORY
+        assert lib.amskv_append_scale(h, 0, 5, C.c_void_p(256), C.c_void_p(256), None) == amskv.AMSKV_ERR_NO_DEVICE_MEMORY
+        assert lib.amskv_append_scale(h, 0, 5, C.c_void_p(256), None, None) == amskv.AMSKV_ERR_INVALID_ARG
+        f = (C.c_float * 4)()
+        # window 1 at step 4 holds {0,1,3,4}: scale 2 is gone, scale 5 not there yet
+        assert lib.amskv_interscale_similarity(h, 0, 3, f, None, None, None) == amskv.AMSKV_ERR_EVICTED
+        assert lib.amskv_interscale_similarity(h, 0, 5, f, None, None, None) == amskv.AMSKV_ERR_ORDER
+        assert lib.amskv_interscale_similarity(h, 0, 0, f, None, None, None) == amskv.AMSKV_ERR_INVALID_ARG
+        assert lib.amskv_interscale_similarity(h, 0, 4, f, None, None, None) == amskv.AMSKV_ERR_NO_DEVICE_MEMORY
+        amskv.amskv_cache_reset(h)
+        assert amskv.amskv_cache_layout(h, 0) == []
+        amskv.amskv_append_scale(h, 0, 0)
+        assert amskv.amskv_cache_layout(h, 0) == [(0, 0, 1)]
+    finally:
+        amskv.amskv_cache_destroy(h)
+    assert amskv.status_string(0) == "ok" and "order" in amskv.status_string(-2)

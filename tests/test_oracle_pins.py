@@ -130,6 +130,16 @@ def test_policy_attention_equals_library_attention_on_gathered_scales(pol):
         np.testing.assert_allclose(got, want, rtol=0, atol=1e-12)
 
 
+def test_all_steps_equals_step_by_step():
+    sides = (1, 2, 3, 4, 5)
+    t = [s * s for s in sides]
+    q, k, v = _rand_scales(sides, 2, 2, 8, 31)
+    for pol in [(2, 1, False), (0, 0, True), (1, 0, False)]:
+        every = orc.attend_all_steps(q, k, v, t, pol)
+        for s in range(len(sides)):
+            np.testing.assert_allclose(every[s], orc.attend_step(q, k, v, t, pol, s), rtol=0, atol=1e-13)
+
+
 def test_softmax_scale_override_and_default():
     sides = (1, 2, 3)
     t = [1, 4, 9]
