@@ -1,0 +1,279 @@
+#!/usr/bin/env python3
+"""Benchmark of the AMS-KV hot path on one MI355X.
+
+One "step" is one whole pass of the hot path over one image batch of synthetic input, already
+resident in HBM: for every scale s and every layer l, amskv_append_scale (policy -> kept set,
+evict + compact + append) then amskv_attend; at the probe scale, amskv_interscale_similarity for
+every layer; bytes-held accounting at the end.  Default workload: VAR-d30 shape (30 layers,
+30 heads x 64, ten scales = 680 tokens), bf16, batch 256, cache-demanding layers chosen by the
+similarity call (mean cosine < 0.5 -> keep all scales), the rest {0,1} + window 2.
+
+Prints ONE JSON line.  `value` is attention TFLOP/s over the whole step (FLOPs of the kept keys
+only, 4*B*H*T_q*T_kv*D per launch; the time includes append/evict and similarity).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+PROBE_SCALE = 5                # first step at which {0,1}+window 2 evicts a scale
+COS_THRESHOLD = 0.5
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (summaries under profiles/); None until measured for the workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def kept_tokens(tokens, pol, s):
+    c, w, keep_all = pol
+    return sum(tokens[k] for k in range(s + 1) if keep_all or k < c or s - k <= w)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="var_d30", choices=["var_d30", "var_d16", "var_d24", "infinity_2b"])
+    ap.add_argument("--batch", type=int, default=0, help="0 = the configuration's batch")
+    ap.add_argument("--mode", default="amskv", choices=["amskv", "vanilla"])
+    ap.add_argument("--layout", default="compact", choices=["compact", "planned"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--per-scale", action="store_true", help="print a per-scale timing table to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus %d is not supported (every (layer, batch, head) "
+              "unit is independent, so more GPUs would shard the batch with no exchange)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import amskv_inputs as inp
+    import paper_2511_16047_amd as amskv
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    amskv.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    fn = {"var_d30": inp.config3, "var_d16": inp.config2, "var_d24": inp.config5, "infinity_2b": inp.config4}[args.workload]
+    w = fn(args.batch) if args.batch else fn()
+    if args.workload != "var_d30":
+        w.name += "_b%d" % w.batch
+    B, H, D, L = w.batch, w.heads, w.head_dim, w.layers
+    tokens = w.tokens
+    S = len(tokens)
+    eb = 2
+    layout = amskv.AMSKV_LAYOUT_PLANNED if args.layout == "planned" else amskv.AMSKV_LAYOUT_COMPACT
+
+    # ---------------- synthetic inputs, resident in HBM
+    t0 = time.time()
+    Q, K, V = [], [], []
+    if args.workload == "var_d30":
+        rhos = inp.layer_rhos(L, inp.layer_seed(3, 999))
+    for l in range(L):
+        if args.workload == "var_d30":
+            q, k, v = inp.correlated_qkv(w.sides, B, H, D, "bf16", inp.layer_seed(w.config_id, l), rhos[l], device=dev)
+        elif args.workload == "var_d16":
+            q, k, v = inp.correlated_qkv(w.sides, B, H, D, "bf16", inp.layer_seed(w.config_id, l), 0.8, device=dev)
+        else:
+            q, k, v = inp.iid_qkv(w.sides, B, H, D, "bf16", inp.layer_seed(w.config_id, l), device=dev)
+        Q.append(q); K.append(k); V.append(v)
+    O = [torch.empty(B, H, t, D, dtype=torch.bfloat16, device=dev) for t in tokens]
+    torch.cuda.synchronize()
+    log("inputs: %.1f GB in %.1f s" % (3 * L * B * H * sum(tokens) * D * eb / 1e9, time.time() - t0))
+
+    # ---------------- policy: cache-demanding layers from the similarity call (VAR-d30 configuration)
+    base_pol = list(w.policies)
+    cos_layer = None
+    if args.mode == "vanilla":
+        pols = [(0, 0, True)] * L
+    elif args.workload == "var_d30":
+        need = amskv.amskv_cache_required_bytes(1, H, D, w.sides, w.sides, B, 1, [(0, 0, True)])
+        arena = torch.empty(need, dtype=torch.uint8, device=dev)
+        prof = amskv.amskv_cache_create(1, H, D, w.sides, w.sides, B, 1, [(0, 0, True)], arena=arena)
+        cos_layer = []
+        for l in range(L):
+            amskv.amskv_cache_reset(prof)
+            for s in range(PROBE_SCALE + 1):
+                amskv.amskv_append_scale(prof, 0, s, K[l][s], V[l][s])
+            ck, _, _ = amskv.amskv_interscale_similarity(prof, 0, PROBE_SCALE, H, want_v=False, want_sums=False)
+            cos_layer.append(sum(ck) / H)
+        amskv.amskv_cache_destroy(prof)
+        del arena
+        pols = [(0, 0, True) if c < COS_THRESHOLD else base_pol[l] for l, c in enumerate(cos_layer)]
+        log("mean cosine per layer:", " ".join("%.2f" % c for c in cos_layer))
+        log("cache-demanding layers:", [l for l, p in enumerate(pols) if p[2]])
+    else:
+        pols = base_pol
+
+    need = amskv.amskv_cache_required_bytes(L, H, D, w.sides, w.sides, B, 1, pols, 0.0, layout)
+    arena = torch.empty(need, dtype=torch.uint8, device=dev)
+    cache = amskv.amskv_cache_create(L, H, D, w.sides, w.sides, B, 1, pols, 0.0, layout, arena=arena)
+    probe_layers = list(range(L))
+    probe = PROBE_SCALE if S > PROBE_SCALE else S - 1
+
+    def one_step(timers=None):
+        amskv.amskv_cache_reset(cache)
+        for s in range(S):
+            for l in range(L):
+                if timers is None:
+                    amskv.amskv_append_scale(cache, l, s, K[l][s], V[l][s])
+                    amskv.amskv_attend(cache, l, s, Q[l][s], O[s])
+                else:
+                    e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+                    e[0].record()
+                    amskv.amskv_append_scale(cache, l, s, K[l][s], V[l][s])
+                    e[1].record()
+                    amskv.amskv_attend(cache, l, s, Q[l][s], O[s])
+                    e[2].record()
+                    timers.append((l, s, e))
+            if s == probe and probe >= 1:
+                for l in probe_layers:
+                    amskv.amskv_interscale_similarity(cache, l, s, H, want_v=False, want_sums=False)
+
+    # ---------------- timed region
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    flops = sum(4.0 * B * H * tokens[s] * kept_tokens(tokens, pols[l], s) * D for l in range(L) for s in range(S))
+    held = sum(amskv.amskv_cache_bytes_held(cache, l, True) for l in range(L))
+    held_paper = sum(amskv.amskv_cache_bytes_held(cache, l, False) for l in range(L))
+    vanilla_held = 2 * eb * B * H * D * sum(tokens) * L
+    arena_bytes = need
+
+    # ---------------- instrumented pass: HIP events around every launch, on the launch stream
+    timers = []
+    one_step(timers)
+    torch.cuda.synchronize()
+    dom_rows = 128                    # launches with T_q > 128 use the 256-row variant (the dominant kernel)
+    dom_t = dom_bytes = dom_flops = 0.0
+    dom_n = 0
+    att_t = app_t = att_bytes = app_bytes = 0.0
+    per_scale = [[0.0, 0.0, 0.0, 0.0] for _ in range(S)]
+    for l, s, e in timers:
+        ta, tt = e[0].elapsed_time(e[1]) * 1e-3, e[1].elapsed_time(e[2]) * 1e-3
+        tkv = kept_tokens(tokens, pols[l], s)
+        by = (2 * tokens[s] + 2 * tkv) * D * eb * B * H
+        fl = 4.0 * B * H * tokens[s] * tkv * D
+        # append: moved tokens (COMPACT) read+written, new scale read+written, K and V
+        prev = [k for k in range(s) if pols[l][2] or k < pols[l][0] or (s - 1) - k <= pols[l][1]]
+        now = [k for k in prev if pols[l][2] or k < pols[l][0] or s - k <= pols[l][1]]
+        moved = 0
+        if layout == amskv.AMSKV_LAYOUT_COMPACT and len(now) != len(prev):
+            first_gone = min(k for k in prev if k not in now)
+            moved = sum(tokens[k] for k in now if k > first_gone)
+        aby = 2 * (2 * moved + 2 * tokens[s]) * D * eb * B * H
+        att_t += tt; app_t += ta; att_bytes += by; app_bytes += aby
+        per_scale[s][0] += ta; per_scale[s][1] += tt; per_scale[s][2] += fl; per_scale[s][3] += by
+        if tokens[s] > dom_rows:
+            dom_t += tt; dom_bytes += by; dom_flops += fl; dom_n += 1
+    if dom_n == 0:
+        dom_t, dom_bytes, dom_flops, dom_n = att_t, att_bytes, flops, len(timers)
+    if args.per_scale:
+        log("scale  T_q  append_ms attend_ms  TFLOP/s   GB/s(attend)")
+        for s in range(S):
+            a, t, fl, by = per_scale[s]
+            log("%5d %4d %9.3f %9.3f %8.1f %8.1f" % (s, tokens[s], a * 1e3, t * 1e3, fl / t / 1e12, by / t / 1e9))
+        log("attend total %.2f ms, append total %.2f ms, append GB/s %.1f" % (att_t * 1e3, app_t * 1e3, app_bytes / max(app_t, 1e-9) / 1e9))
+
+    dom_name = "attend_bf16_kernel<%d,2>" % D
+    ai = dom_flops / dom_bytes
+    hbm_bound = ai < PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+    if hbm_bound:
+        roof = {"bound": "hbm", "achieved": dom_bytes / dom_t / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s"}
+    else:
+        roof = {"bound": "mfma", "achieved": dom_flops / dom_t / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((dom_name, w.name, args.mode))
+    roof.update({"kernel": dom_name, "launches": dom_n, "avg_launch_ms": dom_t / dom_n * 1e3,
+                 "algorithmic_bytes_per_launch": dom_bytes / dom_n, "flops_per_launch": dom_flops / dom_n,
+                 "arithmetic_intensity": ai, "tflops": dom_flops / dom_t / 1e12,
+                 "frac_of_bf16_mfma_peak": dom_flops / dom_t / 1e12 / PEAK_BF16_TFLOPS,
+                 "frac_of_min_roof": (dom_flops / dom_t) / min(PEAK_BF16_TFLOPS * 1e12, ai * PEAK_HBM_GBS * 1e9)})
+
+    out = {
+        "metric": "AMS-KV attention TFLOP/s + ms per image at VAR-d30 b=256; KV bytes held",
+        "value": flops / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "mode": args.mode, "layout": args.layout, "layers": L, "heads": H,
+                   "head_dim": D, "batch": B, "tokens": sum(tokens), "scales": S,
+                   "cache_demanding_layers": sum(1 for p in pols if p[2]), "probe_scale": probe},
+        "ms_per_image": ms_per_step / B,
+        "kv_bytes_held": held, "kv_bytes_held_excluding_current_scale": held_paper,
+        "kv_bytes_vanilla": vanilla_held, "kv_reduction": 1.0 - held / vanilla_held,
+        "arena_bytes": arena_bytes, "attention_flops_per_step": flops,
+        "attend_ms_per_step": att_t * 1e3, "append_ms_per_step": app_t * 1e3,
+        "append_gbs": app_bytes / max(app_t, 1e-9) / 1e9,
+        "roofline": roof,
+        "paper_context": {"kv_reduction_up_to": 0.8483, "self_attention_latency_reduction": 0.6048,
+                          "var_d30_b256": "44.94 GB KV, 23.88 img/s whole model", "hardware": "NVIDIA A100-80GB, FlashAttention-2"},
+    }
+
+    # ---------------- the oracle, timed on the host cores, on a bounded sample of the same workload
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, pols, K, V, Q, tokens, H, D)
+    print(json.dumps(out), flush=True)
+    amskv.amskv_cache_destroy(cache)
+
+
+def cpu_baseline(w, pols, K, V, Q, tokens, H, D):
+    """The oracle as it stands, on (layer 0, the first few batch rows, all heads, all scales)."""
+    import numpy as np
+    from oracle import amskv_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    S = len(tokens)
+    l = 0
+    done_flops, elapsed, nb = 0.0, 0.0, 0
+    budget = 12.0
+    b = 0
+    while elapsed < budget and b < w.batch:
+        nb_now = 1 if b == 0 else min(max(1, int(nb * (budget - elapsed) / max(elapsed, 1e-3))), 8, w.batch - b)
+        q = [x[b:b + nb_now].double().cpu().numpy() for x in Q[l]]
+        k = [x[b:b + nb_now].double().cpu().numpy() for x in K[l]]
+        v = [x[b:b + nb_now].double().cpu().numpy() for x in V[l]]
+        t0 = time.perf_counter()
+        orc.attend_all_steps(q, k, v, tokens, pols[l])
+        for s in range(S):
+            orc.cache_contents(k, pols[l], s)
+            orc.cache_contents(v, pols[l], s)
+        if S > PROBE_SCALE:
+            sd = (w.sides[PROBE_SCALE],) * 2, (w.sides[PROBE_SCALE - 1],) * 2
+            orc.interscale_similarity(k[PROBE_SCALE], k[PROBE_SCALE - 1], sd[0], sd[1])
+        elapsed += time.perf_counter() - t0
+        done_flops += sum(4.0 * nb_now * H * tokens[s] * kept_tokens(tokens, pols[l], s) * D for s in range(S))
+        b += nb_now
+        nb += nb_now
+    return {"value": done_flops / elapsed / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+            "sample": "layer 0, batch rows 0..%d, all %d heads, all %d scales (attention over the explicit mask, "
+                      "cache contents, probe-scale similarity); %.1f s" % (nb - 1, H, S, elapsed)}
+
+
+if __name__ == "__main__":
+    main()

@@ -61,6 +61,10 @@ def load_library() -> C.CDLL:
         return _lib
     if not os.path.exists(LIB_PATH):
         raise RuntimeError("libamskv.so is not built (%s); run `python -m paper_2511_16047_amd.build`" % LIB_PATH)
+    # PyTorch owns the device memory and the streams handed to the library, so both must talk
+    # to the same HIP runtime instance: torch bundles its own libamdhip64 and must load first,
+    # then the library's dependency on that soname resolves to the copy already in the process.
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     vp, i32, i64, u64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64
     ps, pp = C.POINTER(_Schedule), C.POINTER(_Policy)
