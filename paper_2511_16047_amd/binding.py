@@ -11,7 +11,8 @@ import os
 from typing import List, Optional, Sequence, Tuple
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libamskv.so")
+# AMSKV_LIBRARY points at another build of the same library (e.g. a tuning variant)
+LIB_PATH = os.environ.get("AMSKV_LIBRARY") or os.path.join(HERE, "libamskv.so")
 
 AMSKV_OK = 0
 AMSKV_ERR_INVALID_ARG = -1

@@ -19,7 +19,7 @@ LIB = os.path.join(HERE, "libamskv.so")
 OBJ = os.path.join(HERE, "_build")
 
 SOURCES = ["amskv_api.cpp", "cache_kernels.hip", "similarity_kernels.hip", "attend_f32.hip", "attend_bf16.hip"]
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip", "-Wno-inline-asm",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 

@@ -1,7 +1,8 @@
 // bf16 per-scale attention over the resident segments (Section 3.1: the queries of scale s
 // attend to the cached scales and to their own scale; no mask inside a step), written for
-// gfx950: 64-lane wavefronts, v_mfma_f32_32x32x16_bf16, LDS-staged K/V tiles, transposing LDS
-// reads for the V operand, online softmax with fp32 statistics.
+// gfx950: 64-lane wavefronts, v_mfma_f32_32x32x16_bf16, K/V tiles streamed HBM -> LDS with
+// direct-to-LDS loads through a multi-stage ring, transposing LDS reads for the V operand,
+// online softmax with fp32 statistics.
 //
 // Formulation.  One workgroup of four waves owns all (<= 128*NQ) query rows of a (b,h) tile, so
 // K~ and V~ stream from HBM once per tile.  Each wave owns 32*NQ query rows and keeps their Q
@@ -19,8 +20,14 @@
 // 4 consecutive head-dim elements of key (i/4) at column group (i%4), and receives the four keys'
 // values of column i -- exactly a 4x16 -> 16x4 transpose, so V stays row-major in LDS.
 //
-// LDS rows are XOR-swizzled at 16-byte granularity (chunk ^= row & 7) so that the 16-byte K
-// fragment reads of 32 consecutive rows spread over all banks.
+// Memory pipeline.  The kernel is HBM-bound at VAR shapes (arithmetic intensity
+// T_q*T_kv/(T_q+T_kv) flop/byte, below the chip's ridge), so the tile loop keeps kStages-1 tiles
+// in flight: global_load_lds_dwordx4 writes 64 lanes x 16 bytes straight into LDS with no
+// register staging, and the wave only waits (s_waitcnt vmcnt) for the tile it is about to use.
+// A direct-to-LDS load puts lane i's 16 bytes at base + 16*i, so the XOR swizzle that keeps the
+// fragment reads conflict-free (chunk ^= row & 7) is applied on the global side: the lane that
+// fills LDS chunk position c' of row r fetches global chunk c' ^ (r & 7).  Rows past the end of
+// K~ re-read the last valid row (finite data) and their scores are set to -inf.
 #include "amskv_internal.hpp"
 
 namespace amskv {
@@ -28,36 +35,100 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int kThreads = 256;
-constexpr int kWaves = 4;
 constexpr int kTileKeys = 64;
+// the online softmax lets the running max lag by up to this many powers of two before the
+// accumulators are rescaled; probabilities then stay below 2^kMaxLag, far inside fp32/bf16 range
+constexpr float kMaxLag = 6.0f;
 
 #define AMSKV_LDS __attribute__((address_space(3)))
+#define AMSKV_GLOBAL __attribute__((address_space(1)))
 
 __device__ __forceinline__ bf16x4 lds_read_tr16(const char* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((AMSKV_LDS bf16x4*)(p));
 }
 
-template <int D, int NQ>
-__global__ __launch_bounds__(kThreads) void attend_bf16_kernel(const __bf16* __restrict__ q,
+// One wave-wide direct-to-LDS load: lane i's 16 bytes at `g` land at lds_wave_base + 16*i.
+// Written as inline assembly on purpose: the ring's reuse distance is enforced by the explicit
+// vmcnt waits and barriers in the tile loop, whereas the compiler, seeing an LDS write in
+// flight, would drain every outstanding load before each LDS read and serialise the pipeline.
+// lds_wave_base must be wave-uniform (it goes through M0).
+__device__ __forceinline__ void lds_dma16(const char* g, char* lds_wave_base) {
+  const unsigned m0v = (unsigned)(size_t)(AMSKV_LDS char*)lds_wave_base;
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(m0v) : "memory", "m0");
+}
+
+// Asynchronous 16-byte global load into registers, also outside the compiler's bookkeeping so
+// that it does not drain the direct-to-LDS loads issued after it; the value may only be used
+// after a wait_vmcnt that covers it, followed by pin().
+__device__ __forceinline__ void global_load16_async(bf16x8& dst, const void* g) {
+  asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(dst) : "v"(g) : "memory");
+}
+// Zero-instruction fence for one register value: later uses cannot be scheduled above it.
+__device__ __forceinline__ void pin(bf16x8& x) { asm volatile("" : "+v"(x)); }
+
+// v_max3_f32 written out: the compiler's fmaxf first canonicalises every operand (one extra
+// v_max per element under IEEE rules), which alone costs more than the whole reduction
+__device__ __forceinline__ float max3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+template <int D, int kWaves>
+struct TileLoader {
+  static constexpr int RB = D * 2;
+  static constexpr int CPR = D / 8;
+  static constexpr int kRowsPerLoad = 64 / CPR;                       // rows covered by one wave-wide load
+  static constexpr int kLoadsPerWave = kTileKeys / kRowsPerLoad / kWaves;  // per tensor
+  static constexpr int kVmPerTile = 2 * kLoadsPerWave;                // vector-memory ops per thread and tile
+
+  // Issue the loads of tile rows j0..j0+63 of the virtual concatenation into one ring slot.
+  __device__ static __forceinline__ void issue(const char* kb, const char* vb, char* lds_k, char* lds_v, int j0,
+                                               int t_kv, const SegTable& seg, int wave, int lane) {
+#pragma unroll
+    for (int i = 0; i < kLoadsPerWave; ++i) {
+      const int blk = wave * kLoadsPerWave + i;        // which 1 KB block of the tile
+      const int row = blk * kRowsPerLoad + lane / CPR;
+      const int cpos = lane % CPR;
+      const int j = min(j0 + row, t_kv - 1);
+      int delta = 0;
+      for (int g = 0; g < seg.n; ++g)
+        if (j >= seg.virt_start[g]) delta = seg.phys_off[g] - seg.virt_start[g];
+      const long long off = (long long)(j + delta) * RB + 16 * (cpos ^ (row & 7));
+      lds_dma16(kb + off, lds_k + blk * 1024);
+      lds_dma16(vb + off, lds_v + blk * 1024);
+    }
+  }
+};
+
+template <int D, int NQ, int kWaves, int kStages, int kMinWavesPerSimd>
+__global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_kernel(const __bf16* __restrict__ q,
                                                                __bf16* __restrict__ o,
                                                                const char* __restrict__ kc,
                                                                const char* __restrict__ vc, int t_q,
                                                                long long cap_tokens, SegTable seg,
                                                                float scale_log2e) {
+  using Loader = TileLoader<D, kWaves>;
   constexpr int RB = D * 2;       // bytes per token row
-  constexpr int CPR = D / 8;      // 16-byte chunks per row
   constexpr int KS = D / 16;      // K-steps of the first product
   constexpr int DB = D / 32;      // 32-row blocks of O^T
   constexpr int BM = kWaves * 32 * NQ;
+  constexpr int kTileBytes = kTileKeys * RB;
+  constexpr int VM = Loader::kVmPerTile;
 
-  __shared__ __align__(16) char lds_k[kTileKeys * RB];
-  __shared__ __align__(16) char lds_v[kTileKeys * RB];
+  __shared__ __align__(1024) char lds_k[kStages * kTileBytes];
+  __shared__ __align__(1024) char lds_v[kStages * kTileBytes];
 
   const int tid = threadIdx.x;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
   const int r = lane & 31;        // column (query) / row (key or head-dim) index inside a block
   const int h = lane >> 5;        // which half of the K-step this lane feeds
@@ -65,24 +136,25 @@ __global__ __launch_bounds__(kThreads) void attend_bf16_kernel(const __bf16* __r
   const int q_base = blockIdx.y * BM + wave * (32 * NQ);
   const bool wave_active = q_base < t_q;
   const int t_kv = seg.total;
+  const int n_tiles = (t_kv + kTileKeys - 1) / kTileKeys;
   const char* kb = kc + bh * cap_tokens * RB;
   const char* vb = vc + bh * cap_tokens * RB;
 
-  // Q fragments: B operand of S^T = K Q^T; lane (r,h) holds Q[row r][16t + 8h .. +8)
+  // ---- prologue: the Q fragments, then kStages-1 tiles; all of it stays in flight until the
+  // first wait of the tile loop (loads complete in issue order, so that wait covers Q as well).
+  // Q fragments: B operand of S^T = K Q^T; lane (r,h) holds Q[row r][16t + 8h .. +8).  Query rows
+  // past T_q re-read the last row; their results are never stored.
   bf16x8 qf[NQ][KS];
 #pragma unroll
   for (int n = 0; n < NQ; ++n) {
-    const int row = q_base + 32 * n + r;
+    const int row = min(q_base + 32 * n + r, t_q - 1);
 #pragma unroll
-    for (int t = 0; t < KS; ++t) {
-      if (row < t_q) {
-        qf[n][t] = *reinterpret_cast<const bf16x8*>(q + (bh * t_q + row) * D + 16 * t + 8 * h);
-      } else {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) qf[n][t][e] = (__bf16)0.f;
-      }
-    }
+    for (int t = 0; t < KS; ++t) global_load16_async(qf[n][t], q + (bh * t_q + row) * D + 16 * t + 8 * h);
   }
+#pragma unroll
+  for (int st = 0; st < kStages - 1; ++st)
+    if (st < n_tiles)
+      Loader::issue(kb, vb, lds_k + st * kTileBytes, lds_v + st * kTileBytes, st * kTileKeys, t_kv, seg, wave, lane);
 
   f32x16 oacc[NQ][DB];
 #pragma unroll
@@ -102,28 +174,30 @@ __global__ __launch_bounds__(kThreads) void attend_bf16_kernel(const __bf16* __r
   const int tr_key = 4 * h + ((lane & 15) >> 2);               // + K-step base (+8 for the second read)
   const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);  // + 32*db
 
-  for (int j0 = 0; j0 < t_kv; j0 += kTileKeys) {
-    __syncthreads();
-    // stage K and V rows j0 .. j0+63 of the virtual concatenation; rows past the end are zero
+  for (int it = 0; it < n_tiles; ++it) {
+    // wait for tile `it`; the younger tiles (at most kStages-2 of them) may stay in flight
+    const int ahead = min(kStages - 2, n_tiles - 1 - it);
+    if (ahead >= 2) wait_vmcnt<2 * VM>();
+    else if (ahead == 1) wait_vmcnt<VM>();
+    else wait_vmcnt<0>();
+    __syncthreads();  // every wave's part of tile `it` has landed; every wave is done with tile it-1
 #pragma unroll
-    for (int id = tid; id < kTileKeys * CPR; id += kThreads) {
-      const int row = id / CPR, c = id % CPR;
-      const int j = j0 + row;
-      uint4 kk = make_uint4(0, 0, 0, 0), vv = kk;
-      if (j < t_kv) {
-        int delta = 0;
-        for (int i = 0; i < seg.n; ++i)
-          if (j >= seg.virt_start[i]) delta = seg.phys_off[i] - seg.virt_start[i];
-        const long long off = (long long)(j + delta) * RB + 16 * c;
-        kk = *reinterpret_cast<const uint4*>(kb + off);
-        vv = *reinterpret_cast<const uint4*>(vb + off);
-      }
-      const int lo = row * RB + 16 * (c ^ (row & 7));
-      *reinterpret_cast<uint4*>(lds_k + lo) = kk;
-      *reinterpret_cast<uint4*>(lds_v + lo) = vv;
+    for (int n = 0; n < NQ; ++n)
+#pragma unroll
+      for (int t = 0; t < KS; ++t) pin(qf[n][t]);
+#if defined(XP_NODMA)
+    if (false) {
+#else
+    if (it + kStages - 1 < n_tiles) {
+#endif
+      const int nx = it + kStages - 1, slot = nx % kStages;
+      Loader::issue(kb, vb, lds_k + slot * kTileBytes, lds_v + slot * kTileBytes, nx * kTileKeys, t_kv, seg, wave,
+                    lane);
     }
-    __syncthreads();
     if (!wave_active) continue;
+    const int j0 = it * kTileKeys;
+    const char* tk = lds_k + (it % kStages) * kTileBytes;
+    const char* tv = lds_v + (it % kStages) * kTileBytes;
 
     // ---- S^T = K Q^T for two 32-key blocks
     f32x16 sacc[NQ][2];
@@ -138,7 +212,7 @@ __global__ __launch_bounds__(kThreads) void attend_bf16_kernel(const __bf16* __r
       const int row = 32 * kbk + r;
 #pragma unroll
       for (int t = 0; t < KS; ++t) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(lds_k + row * RB + 16 * ((2 * t + h) ^ (row & 7)));
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(tk + row * RB + 16 * ((2 * t + h) ^ (row & 7)));
 #pragma unroll
         for (int n = 0; n < NQ; ++n)
           sacc[n][kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[n][t], sacc[n][kbk], 0, 0, 0);
@@ -159,33 +233,55 @@ __global__ __launch_bounds__(kThreads) void attend_bf16_kernel(const __bf16* __r
 
     // ---- online softmax; probabilities packed as B operands of the second product
     bf16x8 pf[NQ][2][2];
+#if defined(XP_NOSOFTMAX)
+#pragma unroll
+    for (int n = 0; n < NQ; ++n)
+#pragma unroll
+      for (int kbk = 0; kbk < 2; ++kbk)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) pf[n][kbk][v >> 3][v & 7] = (__bf16)sacc[n][kbk][v];
+#else
 #pragma unroll
     for (int n = 0; n < NQ; ++n) {
-      float mx = -INFINITY;
+      // in-lane max of this lane's 32 scores (16 x v_max3), then one exchange between the halves
+      float mx = max3(sacc[n][0][0], sacc[n][0][1], sacc[n][0][2]);
+#pragma unroll
+      for (int v = 3; v < 15; v += 2) mx = max3(mx, sacc[n][0][v], sacc[n][0][v + 1]);
+      mx = max3(mx, sacc[n][0][15], sacc[n][1][0]);
+#pragma unroll
+      for (int v = 1; v < 15; v += 2) mx = max3(mx, sacc[n][1][v], sacc[n][1][v + 1]);
+      const float other = __shfl_xor(max3(mx, sacc[n][1][15], sacc[n][1][15]), 32, 64);
+      mx = max3(mx, sacc[n][1][15], other);
+      const bool lag = (mx - run_max[n]) * scale_log2e > kMaxLag;
+      if (__builtin_amdgcn_ballot_w64(lag) != 0) {   // wave-uniform branch
+        const float new_max = fmaxf(run_max[n], mx);
+        const float alpha = __builtin_amdgcn_exp2f((run_max[n] - new_max) * scale_log2e);
+        run_max[n] = new_max;
+        run_sum[n] *= alpha;
+#pragma unroll
+        for (int d = 0; d < DB; ++d)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) oacc[n][d][v] *= alpha;
+      }
+      // p = 2^(s*c - m*c), rounded to bf16 in pairs; the row sum is taken over the ROUNDED values
+      // (the same weights the second product uses) with one v_dot2c_f32_bf16 per pair
+      const float mc = run_max[n] * scale_log2e;
+      const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+      float sum = run_sum[n];
 #pragma unroll
       for (int kbk = 0; kbk < 2; ++kbk)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, sacc[n][kbk][v]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float new_max = fmaxf(run_max[n], mx);
-      const float alpha = __builtin_amdgcn_exp2f((run_max[n] - new_max) * scale_log2e);
-      const float mc = new_max * scale_log2e;
-      float sum = 0.f;
-#pragma unroll
-      for (int kbk = 0; kbk < 2; ++kbk)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(sacc[n][kbk][v], scale_log2e, -mc));
-          sum += p;
-          pf[n][kbk][v >> 3][v & 7] = (__bf16)p;
+        for (int v = 0; v < 16; v += 2) {
+          bf16x2 pk;
+          pk[0] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[n][kbk][v], scale_log2e, -mc));
+          pk[1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[n][kbk][v + 1], scale_log2e, -mc));
+          sum = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, sum, false);
+          pf[n][kbk][v >> 3][v & 7] = pk[0];
+          pf[n][kbk][v >> 3][(v & 7) + 1] = pk[1];
         }
-      run_sum[n] = run_sum[n] * alpha + sum;
-      run_max[n] = new_max;
-#pragma unroll
-      for (int d = 0; d < DB; ++d)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) oacc[n][d][v] *= alpha;
+      run_sum[n] = sum;
     }
+#endif
 
     // ---- O^T += V^T P^T
 #pragma unroll
@@ -197,8 +293,8 @@ __global__ __launch_bounds__(kThreads) void attend_bf16_kernel(const __bf16* __r
 #pragma unroll
         for (int d = 0; d < DB; ++d) {
           const int col = 32 * d + tr_col;
-          const bf16x4 lo = lds_read_tr16(lds_v + key0 * RB + 16 * ((col >> 3) ^ (key0 & 7)) + 2 * (col & 7));
-          const bf16x4 hi = lds_read_tr16(lds_v + key1 * RB + 16 * ((col >> 3) ^ (key1 & 7)) + 2 * (col & 7));
+          const bf16x4 lo = lds_read_tr16(tv + key0 * RB + 16 * ((col >> 3) ^ (key0 & 7)) + 2 * (col & 7));
+          const bf16x4 hi = lds_read_tr16(tv + key1 * RB + 16 * ((col >> 3) ^ (key1 & 7)) + 2 * (col & 7));
           bf16x8 a;
           a[0] = lo[0]; a[1] = lo[1]; a[2] = lo[2]; a[3] = lo[3];
           a[4] = hi[0]; a[5] = hi[1]; a[6] = hi[2]; a[7] = hi[3];
@@ -231,12 +327,13 @@ __global__ __launch_bounds__(kThreads) void attend_bf16_kernel(const __bf16* __r
   }
 }
 
-template <int D, int NQ>
+template <int D, int NQ, int kWaves, int kStages, int kMinWavesPerSimd>
 hipError_t launch(const void* q, void* o, const void* kc, const void* vc, int bh, int t_q, int64_t cap_tokens,
                   const SegTable& seg, float c, hipStream_t st) {
   constexpr int BM = kWaves * 32 * NQ;
-  dim3 grid(bh, (t_q + BM - 1) / BM), block(kThreads);
-  hipLaunchKernelGGL((attend_bf16_kernel<D, NQ>), grid, block, 0, st, (const __bf16*)q, (__bf16*)o,
+  dim3 grid(bh, (t_q + BM - 1) / BM), block(64 * kWaves);
+  static_assert(kStages >= 2 && kStages <= 4, "the tile wait handles at most two younger tiles in flight");
+  hipLaunchKernelGGL((attend_bf16_kernel<D, NQ, kWaves, kStages, kMinWavesPerSimd>), grid, block, 0, st, (const __bf16*)q, (__bf16*)o,
                      (const char*)kc, (const char*)vc, t_q, (long long)cap_tokens, seg, c);
   return hipGetLastError();
 }
@@ -249,10 +346,13 @@ hipError_t launch_attend_bf16(const void* q, void* o, const void* kc, const void
   const float c = softmax_scale * 1.4426950408889634f;
   const bool wide = t_q > 128;  // 256 query rows per workgroup keeps K/V single-pass up to T_q = 256
   if (head_dim == 64)
-    return wide ? launch<64, 2>(q, o, kc, vc, bh, t_q, cap_tokens, seg, c, st)
-                : launch<64, 1>(q, o, kc, vc, bh, t_q, cap_tokens, seg, c, st);
-  return wide ? launch<128, 2>(q, o, kc, vc, bh, t_q, cap_tokens, seg, c, st)
-              : launch<128, 1>(q, o, kc, vc, bh, t_q, cap_tokens, seg, c, st);
+    // eight waves of 32 rows: ~110 registers per lane, so two workgroups (16 waves) share a CU
+    // and one wave's softmax overlaps another's matrix products
+    return wide ? launch<64, 1, 8, 3, 4>(q, o, kc, vc, bh, t_q, cap_tokens, seg, c, st)
+                : launch<64, 1, 4, 3, 3>(q, o, kc, vc, bh, t_q, cap_tokens, seg, c, st);
+  // head dim 128: 16 KB tiles; two stages keep two workgroups per CU inside 160 KB of LDS
+  return wide ? launch<128, 2, 4, 2, 1>(q, o, kc, vc, bh, t_q, cap_tokens, seg, c, st)
+              : launch<128, 1, 4, 2, 1>(q, o, kc, vc, bh, t_q, cap_tokens, seg, c, st);
 }
 
 }  // namespace amskv
