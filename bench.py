@@ -30,7 +30,11 @@ COS_THRESHOLD = 0.5
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (summaries under profiles/); None until measured for the workload.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # profiles/var_d30_b256_hbm_traffic.txt: (FETCH_SIZE*2.0000 + WRITE_SIZE*1.0000) KiB per launch, mean over
+    # the dominant kernel's launches of one step
+    ("attend_bf16_kernel<64,1,8,64,4>", "var_d30_bf16_b256", "amskv"): 1425818771,
+}
 
 
 def log(*a):
@@ -53,6 +57,9 @@ def main():
     ap.add_argument("--layout", default="compact", choices=["compact", "planned"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-scale", action="store_true", help="print a per-scale timing table to stderr")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 4 GiB device copy five times (reference dispatch of known size for "
+                         "scaling the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus %d is not supported (every (layer, batch, head) "
@@ -69,6 +76,14 @@ def main():
     amskv.load_library()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.copy_calibration:
+        a = torch.ones(1 << 30, dtype=torch.int32, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(5):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": 4 << 30, "copy_bytes_written": 4 << 30, "repeats": 5}))
+        return
 
     fn = {"var_d30": inp.config3, "var_d16": inp.config2, "var_d24": inp.config5, "infinity_2b": inp.config4}[args.workload]
     w = fn(args.batch) if args.batch else fn()
@@ -198,7 +213,7 @@ def main():
             log("%5d %4d %9.3f %9.3f %8.1f %8.1f" % (s, tokens[s], a * 1e3, t * 1e3, fl / t / 1e12, by / t / 1e9))
         log("attend total %.2f ms, append total %.2f ms, append GB/s %.1f" % (att_t * 1e3, app_t * 1e3, app_bytes / max(app_t, 1e-9) / 1e9))
 
-    dom_name = "attend_bf16_kernel<%d,2>" % D
+    dom_name = "attend_bf16_kernel<%d,%s>" % (D, "1,8,64,4" if D == 64 else "2,4,32,1")
     ai = dom_flops / dom_bytes
     hbm_bound = ai < PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
     if hbm_bound:

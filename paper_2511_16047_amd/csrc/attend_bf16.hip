@@ -2,15 +2,16 @@
 // attend to the cached scales and to their own scale; no mask inside a step), written for
 // gfx950: 64-lane wavefronts, v_mfma_f32_32x32x16_bf16, K/V tiles streamed HBM -> LDS with
 // direct-to-LDS loads through a multi-stage ring, transposing LDS reads for the V operand,
-// online softmax with fp32 statistics.
+// online softmax with fp32 statistics, and a software pipeline that overlaps the softmax of one
+// 32-key block with the second matrix product of the block before it.
 //
-// Formulation.  One workgroup of four waves owns all (<= 128*NQ) query rows of a (b,h) tile, so
-// K~ and V~ stream from HBM once per tile.  Each wave owns 32*NQ query rows and keeps their Q
-// fragments in registers for the whole kernel.  Per 64-key tile it computes the TRANSPOSED
-// score block S^T = K Q^T (M = keys, N = queries): in the 32x32 accumulator layout every lane
-// then holds 16 keys of ONE query (column = lane%32), so the row max / row sum of the softmax
-// are in-lane reductions plus a single exchange between the two lane halves, and the
-// probabilities are already in the register layout the second product needs as its B operand:
+// Formulation.  One workgroup owns all (<= 32*NQ*kWaves) query rows of a (b,h) tile, so K~ and
+// V~ stream from HBM once per tile.  Each wave owns 32*NQ query rows and keeps their Q fragments
+// in registers for the whole kernel.  Per 32-key block it computes the TRANSPOSED score block
+// S^T = K Q^T (M = keys, N = queries): in the 32x32 accumulator layout every lane then holds 16
+// keys of ONE query (column = lane%32), so the row max / row sum of the softmax are in-lane
+// reductions plus a single exchange between the two lane halves, and the probabilities are
+// already in the register layout the second product needs as its B operand:
 // O^T += V^T P^T (M = head dim, K = keys, N = queries).  P never touches LDS.
 //
 // The accumulator row held in slot v of lane l is 8*(v/4) + 4*(l/32) + v%4, so the 8 values a
@@ -20,14 +21,21 @@
 // 4 consecutive head-dim elements of key (i/4) at column group (i%4), and receives the four keys'
 // values of column i -- exactly a 4x16 -> 16x4 transpose, so V stays row-major in LDS.
 //
-// Memory pipeline.  The kernel is HBM-bound at VAR shapes (arithmetic intensity
-// T_q*T_kv/(T_q+T_kv) flop/byte, below the chip's ridge), so the tile loop keeps kStages-1 tiles
-// in flight: global_load_lds_dwordx4 writes 64 lanes x 16 bytes straight into LDS with no
-// register staging, and the wave only waits (s_waitcnt vmcnt) for the tile it is about to use.
-// A direct-to-LDS load puts lane i's 16 bytes at base + 16*i, so the XOR swizzle that keeps the
-// fragment reads conflict-free (chunk ^= row & 7) is applied on the global side: the lane that
-// fills LDS chunk position c' of row r fetches global chunk c' ^ (r & 7).  Rows past the end of
-// K~ re-read the last valid row (finite data) and their scores are set to -inf.
+// Pipeline.  Block g's softmax runs on the vector ALUs, block g-1's O^T += V^T P^T on the matrix
+// cores; they share no data (the probabilities of g-1 were packed one iteration earlier), so
+// they sit in one basic block and the scheduler interleaves them.  The accumulator rescale that
+// a larger running max requires is applied after that, and only when some query of the wave
+// needs it: the running max may lag the true max by up to 2^kMaxLag.
+//
+// Memory.  The kernel is HBM-bound at VAR shapes (arithmetic intensity T_q*T_kv/(T_q+T_kv)
+// flop/byte, below the chip's ridge), so the tile loop keeps two tiles in flight:
+// global_load_lds_dwordx4 writes 64 lanes x 16 bytes straight into LDS with no register staging,
+// and the wave only waits (s_waitcnt vmcnt) for the tile it is about to use.  A direct-to-LDS load
+// puts lane i's 16 bytes at base + 16*i, so the XOR swizzle that keeps the 16-byte fragment reads
+// conflict-free (chunk ^= row & 7) is applied on the global side: the lane that fills LDS chunk
+// position c' of row r fetches global chunk c' ^ (r & 7).  Rows past the end of K~ re-read the
+// last valid row (finite data) and their scores are set to -inf.  The ring has four slots: tile
+// t-1 (its last block's V is still being multiplied), t (in use), t+1 and t+2 (in flight).
 #include "amskv_internal.hpp"
 
 namespace amskv {
@@ -38,13 +46,12 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int kTileKeys = 64;
+constexpr int kStages = 4;
 // the online softmax lets the running max lag by up to this many powers of two before the
 // accumulators are rescaled; probabilities then stay below 2^kMaxLag, far inside fp32/bf16 range
 constexpr float kMaxLag = 6.0f;
 
 #define AMSKV_LDS __attribute__((address_space(3)))
-#define AMSKV_GLOBAL __attribute__((address_space(1)))
 
 __device__ __forceinline__ bf16x4 lds_read_tr16(const char* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((AMSKV_LDS bf16x4*)(p));
@@ -82,20 +89,21 @@ __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int D, int kWaves>
+template <int D, int kWaves, int kTileKeys>
 struct TileLoader {
   static constexpr int RB = D * 2;
   static constexpr int CPR = D / 8;
-  static constexpr int kRowsPerLoad = 64 / CPR;                       // rows covered by one wave-wide load
+  static constexpr int kRowsPerLoad = 64 / CPR;                            // rows covered by one wave-wide load
   static constexpr int kLoadsPerWave = kTileKeys / kRowsPerLoad / kWaves;  // per tensor
-  static constexpr int kVmPerTile = 2 * kLoadsPerWave;                // vector-memory ops per thread and tile
+  static constexpr int kVmPerTile = 2 * kLoadsPerWave;                     // vector-memory ops per thread and tile
+  static_assert(kLoadsPerWave >= 1 && kLoadsPerWave * kRowsPerLoad * kWaves == kTileKeys, "tile/wave split");
 
-  // Issue the loads of tile rows j0..j0+63 of the virtual concatenation into one ring slot.
+  // Issue the loads of tile rows j0..j0+kTileKeys-1 of the virtual concatenation into one ring slot.
   __device__ static __forceinline__ void issue(const char* kb, const char* vb, char* lds_k, char* lds_v, int j0,
                                                int t_kv, const SegTable& seg, int wave, int lane) {
 #pragma unroll
     for (int i = 0; i < kLoadsPerWave; ++i) {
-      const int blk = wave * kLoadsPerWave + i;        // which 1 KB block of the tile
+      const int blk = wave * kLoadsPerWave + i;  // which 1 KB block of the tile
       const int row = blk * kRowsPerLoad + lane / CPR;
       const int cpos = lane % CPR;
       const int j = min(j0 + row, t_kv - 1);
@@ -109,19 +117,17 @@ struct TileLoader {
   }
 };
 
-template <int D, int NQ, int kWaves, int kStages, int kMinWavesPerSimd>
-__global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_kernel(const __bf16* __restrict__ q,
-                                                               __bf16* __restrict__ o,
-                                                               const char* __restrict__ kc,
-                                                               const char* __restrict__ vc, int t_q,
-                                                               long long cap_tokens, SegTable seg,
-                                                               float scale_log2e) {
-  using Loader = TileLoader<D, kWaves>;
-  constexpr int RB = D * 2;       // bytes per token row
-  constexpr int KS = D / 16;      // K-steps of the first product
-  constexpr int DB = D / 32;      // 32-row blocks of O^T
+template <int D, int NQ, int kWaves, int kTileKeys, int kMinWavesPerSimd>
+__global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_kernel(
+    const __bf16* __restrict__ q, __bf16* __restrict__ o, const char* __restrict__ kc, const char* __restrict__ vc,
+    int t_q, long long cap_tokens, SegTable seg, float scale_log2e) {
+  using Loader = TileLoader<D, kWaves, kTileKeys>;
+  constexpr int RB = D * 2;   // bytes per token row
+  constexpr int KS = D / 16;  // K-steps of the first product
+  constexpr int DB = D / 32;  // 32-row blocks of O^T
   constexpr int BM = kWaves * 32 * NQ;
   constexpr int kTileBytes = kTileKeys * RB;
+  constexpr int kBlocksPerTile = kTileKeys / 32;
   constexpr int VM = Loader::kVmPerTile;
 
   __shared__ __align__(1024) char lds_k[kStages * kTileBytes];
@@ -130,18 +136,19 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lane = tid & 63;
-  const int r = lane & 31;        // column (query) / row (key or head-dim) index inside a block
-  const int h = lane >> 5;        // which half of the K-step this lane feeds
+  const int r = lane & 31;  // column (query) / row (key or head-dim) index inside a block
+  const int h = lane >> 5;  // which half of the K-step this lane feeds
   const long long bh = blockIdx.x;
   const int q_base = blockIdx.y * BM + wave * (32 * NQ);
   const bool wave_active = q_base < t_q;
   const int t_kv = seg.total;
   const int n_tiles = (t_kv + kTileKeys - 1) / kTileKeys;
+  const int n_blocks = (t_kv + 31) / 32;
   const char* kb = kc + bh * cap_tokens * RB;
   const char* vb = vc + bh * cap_tokens * RB;
 
-  // ---- prologue: the Q fragments, then kStages-1 tiles; all of it stays in flight until the
-  // first wait of the tile loop (loads complete in issue order, so that wait covers Q as well).
+  // ---- prologue: the Q fragments, then two tiles; all of it stays in flight until the first
+  // wait of the tile loop (loads complete in issue order, so that wait covers Q as well).
   // Q fragments: B operand of S^T = K Q^T; lane (r,h) holds Q[row r][16t + 8h .. +8).  Query rows
   // past T_q re-read the last row; their results are never stored.
   bf16x8 qf[NQ][KS];
@@ -152,7 +159,7 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
     for (int t = 0; t < KS; ++t) global_load16_async(qf[n][t], q + (bh * t_q + row) * D + 16 * t + 8 * h);
   }
 #pragma unroll
-  for (int st = 0; st < kStages - 1; ++st)
+  for (int st = 0; st < 2; ++st)
     if (st < n_tiles)
       Loader::issue(kb, vb, lds_k + st * kTileBytes, lds_v + st * kTileBytes, st * kTileKeys, t_kv, seg, wave, lane);
 
@@ -164,148 +171,181 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
 #pragma unroll
       for (int v = 0; v < 16; ++v) oacc[n][d][v] = 0.f;
   float run_max[NQ], run_sum[NQ];
+  bf16x8 pf[NQ][2];  // probabilities of the previous block, two K-steps of 16 keys
 #pragma unroll
   for (int n = 0; n < NQ; ++n) {
     run_max[n] = -INFINITY;
     run_sum[n] = 0.f;
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) pf[n][u][e] = (__bf16)0.f;
   }
 
-  // lane-constant pieces of the transposing V read (see header comment)
+  // lane-constant pieces of the fragment addresses
   const int tr_key = 4 * h + ((lane & 15) >> 2);               // + K-step base (+8 for the second read)
   const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);  // + 32*db
+  int v_off[2][DB][2];  // V^T fragment byte offsets inside a 32-key block: [K-step][d block][first/second read]
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+#pragma unroll
+    for (int d = 0; d < DB; ++d)
+#pragma unroll
+      for (int x = 0; x < 2; ++x) {
+        const int key = 16 * u + 8 * x + tr_key, col = 32 * d + tr_col;
+        v_off[u][d][x] = key * RB + 16 * ((col >> 3) ^ (key & 7)) + 2 * (col & 7);
+      }
+  int k_off[KS];  // K fragment byte offsets inside a 32-key block
+#pragma unroll
+  for (int t = 0; t < KS; ++t) k_off[t] = r * RB + 16 * ((2 * t + h) ^ (r & 7));
 
-  for (int it = 0; it < n_tiles; ++it) {
-    // wait for tile `it`; the younger tiles (at most kStages-2 of them) may stay in flight
-    const int ahead = min(kStages - 2, n_tiles - 1 - it);
-    if (ahead >= 2) wait_vmcnt<2 * VM>();
-    else if (ahead == 1) wait_vmcnt<VM>();
-    else wait_vmcnt<0>();
-    __syncthreads();  // every wave's part of tile `it` has landed; every wave is done with tile it-1
+  // V rows of the previous block (first iteration: the block itself, multiplied by pf = 0)
+  const char* v_prev = lds_v;
+  float alpha[NQ];
+  bool any_rescale = false;  // the rescale decided at block g is applied at the top of block g+1
 #pragma unroll
-    for (int n = 0; n < NQ; ++n)
-#pragma unroll
-      for (int t = 0; t < KS; ++t) pin(qf[n][t]);
-#if defined(XP_NODMA)
-    if (false) {
-#else
-    if (it + kStages - 1 < n_tiles) {
-#endif
-      const int nx = it + kStages - 1, slot = nx % kStages;
-      Loader::issue(kb, vb, lds_k + slot * kTileBytes, lds_v + slot * kTileBytes, nx * kTileKeys, t_kv, seg, wave,
-                    lane);
-    }
-    if (!wave_active) continue;
-    const int j0 = it * kTileKeys;
-    const char* tk = lds_k + (it % kStages) * kTileBytes;
-    const char* tv = lds_v + (it % kStages) * kTileBytes;
+  for (int n = 0; n < NQ; ++n) alpha[n] = 1.f;
 
-    // ---- S^T = K Q^T for two 32-key blocks
-    f32x16 sacc[NQ][2];
-#pragma unroll
-    for (int n = 0; n < NQ; ++n)
-#pragma unroll
-      for (int kbk = 0; kbk < 2; ++kbk)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) sacc[n][kbk][v] = 0.f;
-#pragma unroll
-    for (int kbk = 0; kbk < 2; ++kbk) {
-      const int row = 32 * kbk + r;
-#pragma unroll
-      for (int t = 0; t < KS; ++t) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(tk + row * RB + 16 * ((2 * t + h) ^ (row & 7)));
+  for (int g = 0; g < n_blocks; ++g) {
+    const int it = g / kBlocksPerTile;
+    const int sub = g % kBlocksPerTile;
+    if (sub == 0) {
+      // wait for tile `it`; one younger tile may stay in flight
+      if (it + 1 < n_tiles) wait_vmcnt<VM>();
+      else wait_vmcnt<0>();
+      __syncthreads();  // every wave's part of tile `it` has landed; every wave is done with tile it-2
+      if (g == 0) {
 #pragma unroll
         for (int n = 0; n < NQ; ++n)
-          sacc[n][kbk] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[n][t], sacc[n][kbk], 0, 0, 0);
+#pragma unroll
+          for (int t = 0; t < KS; ++t) pin(qf[n][t]);
+      }
+      if (it + 2 < n_tiles) {
+        const int slot = (it + 2) % kStages;
+        Loader::issue(kb, vb, lds_k + slot * kTileBytes, lds_v + slot * kTileBytes, (it + 2) * kTileKeys, t_kv, seg,
+                      wave, lane);
       }
     }
-    if (j0 + kTileKeys > t_kv) {  // ragged tail: keys past the end get zero weight
+    if (!wave_active) continue;
+    // ---- (rarely) move the accumulators to the running max chosen in the previous iteration;
+    // placed here so that the softmax and the matrix products below stay one basic block
+    if (any_rescale) {
 #pragma unroll
-      for (int kbk = 0; kbk < 2; ++kbk)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int key = j0 + 32 * kbk + 8 * (v >> 2) + 4 * h + (v & 3);
-          if (key >= t_kv) {
-#pragma unroll
-            for (int n = 0; n < NQ; ++n) sacc[n][kbk][v] = -INFINITY;
-          }
-        }
-    }
-
-    // ---- online softmax; probabilities packed as B operands of the second product
-    bf16x8 pf[NQ][2][2];
-#if defined(XP_NOSOFTMAX)
-#pragma unroll
-    for (int n = 0; n < NQ; ++n)
-#pragma unroll
-      for (int kbk = 0; kbk < 2; ++kbk)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) pf[n][kbk][v >> 3][v & 7] = (__bf16)sacc[n][kbk][v];
-#else
-#pragma unroll
-    for (int n = 0; n < NQ; ++n) {
-      // in-lane max of this lane's 32 scores (16 x v_max3), then one exchange between the halves
-      float mx = max3(sacc[n][0][0], sacc[n][0][1], sacc[n][0][2]);
-#pragma unroll
-      for (int v = 3; v < 15; v += 2) mx = max3(mx, sacc[n][0][v], sacc[n][0][v + 1]);
-      mx = max3(mx, sacc[n][0][15], sacc[n][1][0]);
-#pragma unroll
-      for (int v = 1; v < 15; v += 2) mx = max3(mx, sacc[n][1][v], sacc[n][1][v + 1]);
-      const float other = __shfl_xor(max3(mx, sacc[n][1][15], sacc[n][1][15]), 32, 64);
-      mx = max3(mx, sacc[n][1][15], other);
-      const bool lag = (mx - run_max[n]) * scale_log2e > kMaxLag;
-      if (__builtin_amdgcn_ballot_w64(lag) != 0) {   // wave-uniform branch
-        const float new_max = fmaxf(run_max[n], mx);
-        const float alpha = __builtin_amdgcn_exp2f((run_max[n] - new_max) * scale_log2e);
-        run_max[n] = new_max;
-        run_sum[n] *= alpha;
+      for (int n = 0; n < NQ; ++n)
 #pragma unroll
         for (int d = 0; d < DB; ++d)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) oacc[n][d][v] *= alpha;
+          for (int v = 0; v < 16; ++v) oacc[n][d][v] *= alpha[n];
+    }
+    const int blk_off = (it % kStages) * kTileBytes + sub * 32 * RB;
+    const char* tk = lds_k + blk_off;
+    const char* tv = lds_v + blk_off;
+
+    // ---- S^T = K Q^T for this 32-key block
+    f32x16 sacc[NQ];
+#pragma unroll
+    for (int n = 0; n < NQ; ++n)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sacc[n][v] = 0.f;
+#pragma unroll
+    for (int t = 0; t < KS; ++t) {
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(tk + k_off[t]);
+#pragma unroll
+      for (int n = 0; n < NQ; ++n) sacc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[n][t], sacc[n], 0, 0, 0);
+    }
+    if (g == n_blocks - 1 && (t_kv & 31) != 0) {  // ragged tail: keys past the end get zero weight
+      const int valid = t_kv & 31;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int key = 8 * (v >> 2) + 4 * h + (v & 3);
+        if (key >= valid) {
+#pragma unroll
+          for (int n = 0; n < NQ; ++n) sacc[n][v] = -INFINITY;
+        }
       }
+    }
+
+    // ---- softmax statistics of this block (vector ALU)
+    any_rescale = false;
+#pragma unroll
+    for (int n = 0; n < NQ; ++n) {
+      float mx = max3(sacc[n][0], sacc[n][1], sacc[n][2]);
+#pragma unroll
+      for (int v = 3; v < 15; v += 2) mx = max3(mx, sacc[n][v], sacc[n][v + 1]);
+      const float other = __shfl_xor(max3(mx, sacc[n][15], sacc[n][15]), 32, 64);
+      mx = max3(mx, sacc[n][15], other);
+      // lazy rescale: keep the old reference while the block's max exceeds it by < 2^kMaxLag
+      const bool lag = (mx - run_max[n]) * scale_log2e > kMaxLag;
+      const float new_max = lag ? mx : run_max[n];
+      alpha[n] = __builtin_amdgcn_exp2f((run_max[n] - new_max) * scale_log2e);  // 1 when unchanged, 0 on the first block
+      run_max[n] = new_max;
+      any_rescale |= (__builtin_amdgcn_ballot_w64(lag) != 0);
+    }
+
+    // ---- one basic block: probabilities of this block (vector ALU) next to O^T += V^T P^T of the
+    // previous block (matrix cores); the two share no data
+    bf16x8 pnew[NQ][2];
+#pragma unroll
+    for (int n = 0; n < NQ; ++n) {
       // p = 2^(s*c - m*c), rounded to bf16 in pairs; the row sum is taken over the ROUNDED values
       // (the same weights the second product uses) with one v_dot2c_f32_bf16 per pair
       const float mc = run_max[n] * scale_log2e;
       const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-      float sum = run_sum[n];
+      float sum = run_sum[n] * alpha[n];
 #pragma unroll
-      for (int kbk = 0; kbk < 2; ++kbk)
-#pragma unroll
-        for (int v = 0; v < 16; v += 2) {
-          bf16x2 pk;
-          pk[0] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[n][kbk][v], scale_log2e, -mc));
-          pk[1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[n][kbk][v + 1], scale_log2e, -mc));
-          sum = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, sum, false);
-          pf[n][kbk][v >> 3][v & 7] = pk[0];
-          pf[n][kbk][v >> 3][(v & 7) + 1] = pk[1];
-        }
+      for (int v = 0; v < 16; v += 2) {
+        bf16x2 pk;
+        pk[0] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[n][v], scale_log2e, -mc));
+        pk[1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[n][v + 1], scale_log2e, -mc));
+        sum = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, sum, false);
+        pnew[n][v >> 3][v & 7] = pk[0];
+        pnew[n][v >> 3][(v & 7) + 1] = pk[1];
+      }
       run_sum[n] = sum;
     }
-#endif
-
-    // ---- O^T += V^T P^T
 #pragma unroll
-    for (int kbk = 0; kbk < 2; ++kbk)
+    for (int u = 0; u < 2; ++u)
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const int key0 = 32 * kbk + 16 * u + tr_key;
-        const int key1 = key0 + 8;
+      for (int d = 0; d < DB; ++d) {
+        const bf16x4 lo = lds_read_tr16(v_prev + v_off[u][d][0]);
+        const bf16x4 hi = lds_read_tr16(v_prev + v_off[u][d][1]);
+        bf16x8 a;
+        a[0] = lo[0]; a[1] = lo[1]; a[2] = lo[2]; a[3] = lo[3];
+        a[4] = hi[0]; a[5] = hi[1]; a[6] = hi[2]; a[7] = hi[3];
 #pragma unroll
-        for (int d = 0; d < DB; ++d) {
-          const int col = 32 * d + tr_col;
-          const bf16x4 lo = lds_read_tr16(tv + key0 * RB + 16 * ((col >> 3) ^ (key0 & 7)) + 2 * (col & 7));
-          const bf16x4 hi = lds_read_tr16(tv + key1 * RB + 16 * ((col >> 3) ^ (key1 & 7)) + 2 * (col & 7));
-          bf16x8 a;
-          a[0] = lo[0]; a[1] = lo[1]; a[2] = lo[2]; a[3] = lo[3];
-          a[4] = hi[0]; a[5] = hi[1]; a[6] = hi[2]; a[7] = hi[3];
-#pragma unroll
-          for (int n = 0; n < NQ; ++n)
-            oacc[n][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[n][kbk][u], oacc[n][d], 0, 0, 0);
-        }
+        for (int n = 0; n < NQ; ++n) oacc[n][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[n][u], oacc[n][d], 0, 0, 0);
       }
+
+#pragma unroll
+    for (int n = 0; n < NQ; ++n)
+#pragma unroll
+      for (int u = 0; u < 2; ++u) pf[n][u] = pnew[n][u];
+    v_prev = tv;
   }
 
   if (!wave_active) return;
+  if (any_rescale) {
+#pragma unroll
+    for (int n = 0; n < NQ; ++n)
+#pragma unroll
+      for (int d = 0; d < DB; ++d)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) oacc[n][d][v] *= alpha[n];
+  }
+  // ---- drain: the last block's O^T += V^T P^T
+#pragma unroll
+  for (int u = 0; u < 2; ++u)
+#pragma unroll
+    for (int d = 0; d < DB; ++d) {
+      const bf16x4 lo = lds_read_tr16(v_prev + v_off[u][d][0]);
+      const bf16x4 hi = lds_read_tr16(v_prev + v_off[u][d][1]);
+      bf16x8 a;
+      a[0] = lo[0]; a[1] = lo[1]; a[2] = lo[2]; a[3] = lo[3];
+      a[4] = hi[0]; a[5] = hi[1]; a[6] = hi[2]; a[7] = hi[3];
+#pragma unroll
+      for (int n = 0; n < NQ; ++n) oacc[n][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[n][u], oacc[n][d], 0, 0, 0);
+    }
+
   // ---- O[row][d] = O^T[d][row] / l ; lane (r,h) holds d = 32*db + 8*(v/4) + 4h + v%4 of row r
 #pragma unroll
   for (int n = 0; n < NQ; ++n) {
@@ -327,14 +367,13 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
   }
 }
 
-template <int D, int NQ, int kWaves, int kStages, int kMinWavesPerSimd>
+template <int D, int NQ, int kWaves, int kTileKeys, int kMinWavesPerSimd>
 hipError_t launch(const void* q, void* o, const void* kc, const void* vc, int bh, int t_q, int64_t cap_tokens,
                   const SegTable& seg, float c, hipStream_t st) {
   constexpr int BM = kWaves * 32 * NQ;
   dim3 grid(bh, (t_q + BM - 1) / BM), block(64 * kWaves);
-  static_assert(kStages >= 2 && kStages <= 4, "the tile wait handles at most two younger tiles in flight");
-  hipLaunchKernelGGL((attend_bf16_kernel<D, NQ, kWaves, kStages, kMinWavesPerSimd>), grid, block, 0, st, (const __bf16*)q, (__bf16*)o,
-                     (const char*)kc, (const char*)vc, t_q, (long long)cap_tokens, seg, c);
+  hipLaunchKernelGGL((attend_bf16_kernel<D, NQ, kWaves, kTileKeys, kMinWavesPerSimd>), grid, block, 0, st,
+                     (const __bf16*)q, (__bf16*)o, (const char*)kc, (const char*)vc, t_q, (long long)cap_tokens, seg, c);
   return hipGetLastError();
 }
 
@@ -347,12 +386,11 @@ hipError_t launch_attend_bf16(const void* q, void* o, const void* kc, const void
   const bool wide = t_q > 128;  // 256 query rows per workgroup keeps K/V single-pass up to T_q = 256
   if (head_dim == 64)
     // eight waves of 32 rows: ~110 registers per lane, so two workgroups (16 waves) share a CU
-    // and one wave's softmax overlaps another's matrix products
-    return wide ? launch<64, 1, 8, 3, 4>(q, o, kc, vc, bh, t_q, cap_tokens, seg, c, st)
-                : launch<64, 1, 4, 3, 3>(q, o, kc, vc, bh, t_q, cap_tokens, seg, c, st);
-  // head dim 128: 16 KB tiles; two stages keep two workgroups per CU inside 160 KB of LDS
-  return wide ? launch<128, 2, 4, 2, 1>(q, o, kc, vc, bh, t_q, cap_tokens, seg, c, st)
-              : launch<128, 1, 4, 2, 1>(q, o, kc, vc, bh, t_q, cap_tokens, seg, c, st);
+    return wide ? launch<64, 1, 8, 64, 4>(q, o, kc, vc, bh, t_q, cap_tokens, seg, c, st)
+                : launch<64, 1, 4, 64, 3>(q, o, kc, vc, bh, t_q, cap_tokens, seg, c, st);
+  // head dim 128: 32-key tiles (16 KB per slot) keep two workgroups per CU inside 160 KB of LDS
+  return wide ? launch<128, 2, 4, 32, 1>(q, o, kc, vc, bh, t_q, cap_tokens, seg, c, st)
+              : launch<128, 1, 4, 32, 1>(q, o, kc, vc, bh, t_q, cap_tokens, seg, c, st);
 }
 
 }  // namespace amskv
