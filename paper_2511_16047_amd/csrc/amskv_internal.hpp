@@ -32,6 +32,9 @@ struct MoveList {
 hipError_t launch_attend_bf16(const void* q, void* o, const void* kc, const void* vc, int bh,
                               int t_q, int head_dim, int64_t cap_tokens, const SegTable& seg,
                               float softmax_scale, hipStream_t st);
+hipError_t launch_attend_bf16_small(const void* q, void* o, const void* kc, const void* vc, int bh,
+                                    int t_q, int head_dim, int64_t cap_tokens, const SegTable& seg,
+                                    float softmax_scale, hipStream_t st);
 hipError_t launch_attend_f32(const void* q, void* o, const void* kc, const void* vc, int bh,
                              int t_q, int head_dim, int64_t cap_tokens, const SegTable& seg,
                              float softmax_scale, hipStream_t st);

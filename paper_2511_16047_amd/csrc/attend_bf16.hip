@@ -36,6 +36,8 @@
 // position c' of row r fetches global chunk c' ^ (r & 7).  Rows past the end of K~ re-read the
 // last valid row (finite data) and their scores are set to -inf.  The ring has four slots: tile
 // t-1 (its last block's V is still being multiplied), t (in use), t+1 and t+2 (in flight).
+#include <cstdlib>
+
 #include "amskv_internal.hpp"
 
 namespace amskv {
@@ -47,6 +49,8 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kStages = 4;
+// query-token count up to which the latency-oriented kernel of attend_bf16_small.hip is used
+constexpr int kSmallTq = 32;
 // the online softmax lets the running max lag by up to this many powers of two before the
 // accumulators are rescaled; probabilities then stay below 2^kMaxLag, far inside fp32/bf16 range
 constexpr float kMaxLag = 6.0f;
@@ -120,7 +124,7 @@ struct TileLoader {
 template <int D, int NQ, int kWaves, int kTileKeys, int kMinWavesPerSimd>
 __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_kernel(
     const __bf16* __restrict__ q, __bf16* __restrict__ o, const char* __restrict__ kc, const char* __restrict__ vc,
-    int t_q, long long cap_tokens, SegTable seg, float scale_log2e) {
+    int t_q, long long cap_tokens, SegTable seg, float scale_log2e, int n_bh, int n_qtiles) {
   using Loader = TileLoader<D, kWaves, kTileKeys>;
   constexpr int RB = D * 2;   // bytes per token row
   constexpr int KS = D / 16;  // K-steps of the first product
@@ -138,8 +142,14 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
   const int lane = tid & 63;
   const int r = lane & 31;  // column (query) / row (key or head-dim) index inside a block
   const int h = lane >> 5;  // which half of the K-step this lane feeds
-  const long long bh = blockIdx.x;
-  const int q_base = blockIdx.y * BM + wave * (32 * NQ);
+  // XCD-aware unit mapping: consecutive workgroup ids go round-robin to the 8 XCDs, each with its own L2,
+  // so the query tiles of one (b,h) are given ids 8 apart: they land on the same XCD back to back and the
+  // second one finds K~/V~ in that L2 instead of fetching them from HBM again.
+  const int per_group = 8 * n_qtiles;
+  const int within = blockIdx.x % per_group;
+  const long long bh = (long long)(blockIdx.x / per_group) * 8 + (within & 7);
+  if (bh >= n_bh) return;  // whole workgroup leaves together (n_bh not a multiple of 8)
+  const int q_base = (within >> 3) * BM + wave * (32 * NQ);
   const bool wave_active = q_base < t_q;
   const int t_kv = seg.total;
   const int n_tiles = (t_kv + kTileKeys - 1) / kTileKeys;
@@ -371,9 +381,11 @@ template <int D, int NQ, int kWaves, int kTileKeys, int kMinWavesPerSimd>
 hipError_t launch(const void* q, void* o, const void* kc, const void* vc, int bh, int t_q, int64_t cap_tokens,
                   const SegTable& seg, float c, hipStream_t st) {
   constexpr int BM = kWaves * 32 * NQ;
-  dim3 grid(bh, (t_q + BM - 1) / BM), block(64 * kWaves);
+  const int n_qtiles = (t_q + BM - 1) / BM;
+  dim3 grid((unsigned)(((bh + 7) / 8) * 8 * n_qtiles)), block(64 * kWaves);
   hipLaunchKernelGGL((attend_bf16_kernel<D, NQ, kWaves, kTileKeys, kMinWavesPerSimd>), grid, block, 0, st,
-                     (const __bf16*)q, (__bf16*)o, (const char*)kc, (const char*)vc, t_q, (long long)cap_tokens, seg, c);
+                     (const __bf16*)q, (__bf16*)o, (const char*)kc, (const char*)vc, t_q, (long long)cap_tokens, seg, c,
+                     bh, n_qtiles);
   return hipGetLastError();
 }
 
@@ -382,12 +394,19 @@ hipError_t launch(const void* q, void* o, const void* kc, const void* vc, int bh
 hipError_t launch_attend_bf16(const void* q, void* o, const void* kc, const void* vc, int bh, int t_q,
                               int head_dim, int64_t cap_tokens, const SegTable& seg, float softmax_scale,
                               hipStream_t st) {
+#if defined(AMSKV_TUNE_ENV)
+  static const int small_tq = getenv("AMSKV_SMALL_TQ") ? atoi(getenv("AMSKV_SMALL_TQ")) : kSmallTq;
+#else
+  constexpr int small_tq = kSmallTq;
+#endif
+  // coarse scales: latency-bound, one independent wave per 32 query rows
+  if (t_q <= small_tq) return launch_attend_bf16_small(q, o, kc, vc, bh, t_q, head_dim, cap_tokens, seg, softmax_scale, st);
   const float c = softmax_scale * 1.4426950408889634f;
   const bool wide = t_q > 128;  // 256 query rows per workgroup keeps K/V single-pass up to T_q = 256
   if (head_dim == 64)
     // eight waves of 32 rows: ~110 registers per lane, so two workgroups (16 waves) share a CU
     return wide ? launch<64, 1, 8, 64, 4>(q, o, kc, vc, bh, t_q, cap_tokens, seg, c, st)
-                : launch<64, 1, 4, 64, 3>(q, o, kc, vc, bh, t_q, cap_tokens, seg, c, st);
+                : launch<64, 1, 4, 32, 4>(q, o, kc, vc, bh, t_q, cap_tokens, seg, c, st);
   // head dim 128: 32-key tiles (16 KB per slot) keep two workgroups per CU inside 160 KB of LDS
   return wide ? launch<128, 2, 4, 32, 1>(q, o, kc, vc, bh, t_q, cap_tokens, seg, c, st)
               : launch<128, 1, 4, 32, 1>(q, o, kc, vc, bh, t_q, cap_tokens, seg, c, st);

@@ -13,24 +13,17 @@ __device__ __forceinline__ void wait_all_vector_loads() {
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
-// One workgroup owns one (b,h) row of one tensor (blockIdx.y: 0 = K, 1 = V).
-//
-// Phase 1 slides the surviving segments toward offset 0.  The moved chunks, taken in
+// Eviction in the COMPACT layout: one workgroup owns one (b,h) row of one tensor (blockIdx.y:
+// 0 = K, 1 = V) and slides the surviving segments toward offset 0.  The moved chunks, taken in
 // ascending address order, have strictly increasing source and destination addresses with
 // dst < src, so a pass that first loads all of its chunks, waits for the data, meets at a
 // barrier and only then stores can never overwrite a chunk that a later pass still has to
 // read: a store to address X can only alias the source of an EARLIER chunk.
-// Phase 2 copies the new scale into its slot; that slot may overlap the old position of a
-// moved segment, so it starts after the last pass's barrier.
-__global__ __launch_bounds__(kThreads) void append_kernel(char* __restrict__ kc, char* __restrict__ vc,
-                                                          const char* __restrict__ k_new,
-                                                          const char* __restrict__ v_new, int row_bytes,
-                                                          long long cap_tokens, MoveList mv, int t_new,
-                                                          int dst_new) {
+__global__ __launch_bounds__(kThreads) void compact_kernel(char* __restrict__ kc, char* __restrict__ vc,
+                                                           int row_bytes, long long cap_tokens, MoveList mv) {
   const int tid = threadIdx.x;
   const long long bh = blockIdx.x;
   char* base = (blockIdx.y ? vc : kc) + bh * cap_tokens * row_bytes;
-  const char* src_new = (blockIdx.y ? v_new : k_new) + bh * (long long)t_new * row_bytes;
   const int cpr = row_bytes >> 4;  // chunks per token row
 
   int total = 0;
@@ -65,26 +58,39 @@ __global__ __launch_bounds__(kThreads) void append_kernel(char* __restrict__ kc,
     for (int u = 0; u < kUnroll; ++u)
       if (dst_byte[u] >= 0) *reinterpret_cast<uint4*>(base + dst_byte[u]) = buf[u];
   }
-  if (total > 0) {
-    wait_all_vector_loads();
-    __syncthreads();
-  }
+}
 
-  const int n_new = t_new * cpr;
-  char* dst = base + (long long)dst_new * row_bytes;
-  for (int c0 = 0; c0 < n_new; c0 += kThreads * kUnroll) {
-    uint4 buf[kUnroll];
+// Append: copy the new scale K_s, V_s ([BH][T_s][row], contiguous) into its slot of every (b,h)
+// row of the cache.  Flat over all 16-byte chunks of both tensors, so a one-token scale and a
+// 256-token scale both run full workgroups; the source side is one contiguous stream.
+// Enqueued after compact_kernel: the slot may overlap the old position of a moved segment.
+__global__ __launch_bounds__(kThreads) void append_kernel(char* __restrict__ kc, char* __restrict__ vc,
+                                                          const char* __restrict__ k_new,
+                                                          const char* __restrict__ v_new, int row_bytes,
+                                                          long long cap_tokens, int t_new, int dst_new,
+                                                          long long chunks_per_tensor) {
+  const int cpr = row_bytes >> 4;
+  const int per_bh = t_new * cpr;  // chunks of one (b,h) row
+  const long long first = (long long)blockIdx.x * (kThreads * kUnroll) + threadIdx.x;
+  uint4 buf[kUnroll];
+  long long dst_off[kUnroll];
+  int which[kUnroll];
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      const int c = c0 + u * kThreads + tid;
-      if (c < n_new) buf[u] = *reinterpret_cast<const uint4*>(src_new + ((long long)c << 4));
-    }
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      const int c = c0 + u * kThreads + tid;
-      if (c < n_new) *reinterpret_cast<uint4*>(dst + ((long long)c << 4)) = buf[u];
+  for (int u = 0; u < kUnroll; ++u) {
+    long long c = first + (long long)u * kThreads;
+    which[u] = -1;
+    if (c < 2 * chunks_per_tensor) {
+      which[u] = c >= chunks_per_tensor;
+      if (which[u]) c -= chunks_per_tensor;
+      const long long bh = c / per_bh;
+      const int rem = (int)(c - bh * per_bh);
+      dst_off[u] = (bh * cap_tokens + dst_new) * row_bytes + ((long long)rem << 4);
+      buf[u] = *reinterpret_cast<const uint4*>((which[u] ? v_new : k_new) + (c << 4));
     }
   }
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u)
+    if (which[u] >= 0) *reinterpret_cast<uint4*>((which[u] ? vc : kc) + dst_off[u]) = buf[u];
 }
 
 // Gather the resident segments, ascending and back to back, into [BH][T_kept][row].
@@ -113,9 +119,17 @@ __global__ __launch_bounds__(kThreads) void export_kernel(const char* __restrict
 
 hipError_t launch_append(void* kc, void* vc, const void* k_new, const void* v_new, int bh, int row_bytes,
                          int64_t cap_tokens, const MoveList& mv, int t_new, int dst_new, hipStream_t st) {
-  dim3 grid(bh, 2), block(kThreads);
-  hipLaunchKernelGGL(append_kernel, grid, block, 0, st, (char*)kc, (char*)vc, (const char*)k_new,
-                     (const char*)v_new, row_bytes, (long long)cap_tokens, mv, t_new, dst_new);
+  if (mv.n > 0) {
+    hipLaunchKernelGGL(compact_kernel, dim3(bh, 2), dim3(kThreads), 0, st, (char*)kc, (char*)vc, row_bytes,
+                       (long long)cap_tokens, mv);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  const long long chunks = (long long)bh * t_new * (row_bytes >> 4);
+  const long long per_block = (long long)kThreads * kUnroll;
+  const unsigned grid = (unsigned)((2 * chunks + per_block - 1) / per_block);
+  hipLaunchKernelGGL(append_kernel, dim3(grid), dim3(kThreads), 0, st, (char*)kc, (char*)vc, (const char*)k_new,
+                     (const char*)v_new, row_bytes, (long long)cap_tokens, t_new, dst_new, chunks);
   return hipGetLastError();
 }
 

@@ -1,7 +1,7 @@
 // Inter-scale similarity (Eq. 3): scale s-1 is resized bilinearly to the grid of scale s on
 // the fly (never materialised) and compared with scale s, straight from the cache.
 // Bandwidth-bound: each token row is read with 16-byte loads by consecutive lanes.
-// Reduction order is fixed (lane tree -> workgroup tree -> sequential over batch), so the
+// Reduction order is fixed (lane tree -> workgroup tree -> strided lanes and an xor tree over batch), so the
 // result is deterministic from run to run.
 #include "amskv_internal.hpp"
 
@@ -119,22 +119,23 @@ __global__ __launch_bounds__(kThreads) void similarity_partial_kernel(
     partial[((long long)blockIdx.y * gridDim.x + bh) * 4 + threadIdx.x] = red[threadIdx.x][0];
 }
 
-// totals[(tensor*H + h)*4 + q] = sum over b (ascending) of partial[(tensor*B*H + b*H + h)*4 + q].
-__global__ void similarity_total_kernel(const float* __restrict__ partial, int batch, int heads, int tensors,
-                                        float* __restrict__ totals) {
-  const int id = blockIdx.x * blockDim.x + threadIdx.x;
-  if (id >= tensors * heads * 4) return;
-  const int q = id & 3, h = (id >> 2) % heads, tn = (id >> 2) / heads;
-  // compensated (Kahan) sum in ascending batch order: small fp32 error, fixed order
-  float s = 0.f, comp = 0.f;
-  for (int b = 0; b < batch; ++b) {
-    const float x = partial[(((long long)tn * batch + b) * heads + h) * 4 + q];
-    const float y = x - comp;
-    const float t = s + y;
-    comp = (t - s) - y;
-    s = t;
+// totals[(tensor*H + h)*4 + q] = sum over b of partial[(tensor*B*H + b*H + h)*4 + q].
+// One 64-lane workgroup per (tensor, h): lane i sums batch entries i, i+64, ... in ascending
+// order, then a fixed xor tree joins the lanes -- the same order on every run.
+__global__ __launch_bounds__(64) void similarity_total_kernel(const float* __restrict__ partial, int batch, int heads,
+                                                              float* __restrict__ totals) {
+  const int h = blockIdx.x % heads, tn = blockIdx.x / heads;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int b = threadIdx.x; b < batch; b += 64) {
+    const float4 x = *reinterpret_cast<const float4*>(partial + (((long long)tn * batch + b) * heads + h) * 4);
+    acc[0] += x.x; acc[1] += x.y; acc[2] += x.z; acc[3] += x.w;
   }
-  totals[id] = s;
+#pragma unroll
+  for (int m = 32; m > 0; m >>= 1)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[q] += __shfl_xor(acc[q], m, 64);
+  if (threadIdx.x == 0)
+    *reinterpret_cast<float4*>(totals + ((long long)tn * heads + h) * 4) = make_float4(acc[0], acc[1], acc[2], acc[3]);
 }
 
 }  // namespace
@@ -156,9 +157,8 @@ hipError_t launch_similarity(const void* kc, const void* vc, int batch, int head
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const int n = tensors * heads * 4;
-  hipLaunchKernelGGL(similarity_total_kernel, dim3((n + 63) / 64), dim3(64), 0, st, (const float*)partial_ws,
-                     batch, heads, tensors, out_dev);
+  hipLaunchKernelGGL(similarity_total_kernel, dim3(tensors * heads), dim3(64), 0, st, (const float*)partial_ws, batch,
+                     heads, out_dev);
   return hipGetLastError();
 }
 
