@@ -55,6 +55,9 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="0 = the configuration's batch")
     ap.add_argument("--mode", default="amskv", choices=["amskv", "vanilla"])
     ap.add_argument("--layout", default="compact", choices=["compact", "planned"])
+    ap.add_argument("--no-borrow", action="store_true",
+                    help="copy every appended scale into the arena, also the ones no later step reads "
+                         "(default: borrow_unretained=1, the final scale is attended in place as in Algorithm 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-scale", action="store_true", help="print a per-scale timing table to stderr")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -94,6 +97,7 @@ def main():
     S = len(tokens)
     eb = 2
     layout = amskv.AMSKV_LAYOUT_PLANNED if args.layout == "planned" else amskv.AMSKV_LAYOUT_COMPACT
+    borrow = not args.no_borrow
 
     # ---------------- synthetic inputs, resident in HBM
     t0 = time.time()
@@ -136,9 +140,10 @@ def main():
     else:
         pols = base_pol
 
-    need = amskv.amskv_cache_required_bytes(L, H, D, w.sides, w.sides, B, 1, pols, 0.0, layout)
+    need = amskv.amskv_cache_required_bytes(L, H, D, w.sides, w.sides, B, 1, pols, 0.0, layout, borrow)
     arena = torch.empty(need, dtype=torch.uint8, device=dev)
-    cache = amskv.amskv_cache_create(L, H, D, w.sides, w.sides, B, 1, pols, 0.0, layout, arena=arena)
+    cache = amskv.amskv_cache_create(L, H, D, w.sides, w.sides, B, 1, pols, 0.0, layout, arena=arena,
+                                     borrow_unretained=borrow)
     probe_layers = list(range(L))
     probe = PROBE_SCALE if S > PROBE_SCALE else S - 1
 
@@ -199,7 +204,10 @@ def main():
         if layout == amskv.AMSKV_LAYOUT_COMPACT and len(now) != len(prev):
             first_gone = min(k for k in prev if k not in now)
             moved = sum(tokens[k] for k in now if k > first_gone)
-        aby = 2 * (2 * moved + 2 * tokens[s]) * D * eb * B * H
+        copied = tokens[s]
+        if borrow and (s == S - 1 or not (pols[l][2] or s < pols[l][0] or pols[l][1] >= 1)):
+            copied = 0                # no later step reads this scale: attended in place, never copied
+        aby = 2 * (2 * moved + 2 * copied) * D * eb * B * H
         att_t += tt; app_t += ta; att_bytes += by; app_bytes += aby
         per_scale[s][0] += ta; per_scale[s][1] += tt; per_scale[s][2] += fl; per_scale[s][3] += by
         if tokens[s] > dom_rows:
@@ -233,7 +241,7 @@ def main():
         "value": flops / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": w.name, "mode": args.mode, "layout": args.layout, "layers": L, "heads": H,
+        "config": {"workload": w.name, "mode": args.mode, "layout": args.layout, "borrow_unretained": int(borrow), "layers": L, "heads": H,
                    "head_dim": D, "batch": B, "tokens": sum(tokens), "scales": S,
                    "cache_demanding_layers": sum(1 for p in pols if p[2]), "probe_scale": probe},
         "ms_per_image": ms_per_step / B,

@@ -79,7 +79,19 @@ typedef struct {
   const amskv_layer_policy* layer;  /* host, [n_layers]                                   */
   float softmax_scale;              /* 0 => 1/sqrt(head_dim)                              */
   int32_t layout;                   /* AMSKV_LAYOUT_COMPACT or AMSKV_LAYOUT_PLANNED       */
+  int32_t borrow_unretained;        /* 0 / 1, see below                                   */
 } amskv_policy;
+
+/* borrow_unretained.  Algorithm 1 stores a scale only if a later step will read it (a scale
+ * larger than the budget is skipped, so the final scale is never cached); the attention of the
+ * current step still uses that scale's own K/V.  With borrow_unretained != 0 the library does
+ * the same: when scale s is appended and the policy does not keep it at step s+1 (always true
+ * for the last scale of the schedule), nothing is copied -- the cache records K_dev/V_dev, and
+ * amskv_attend, amskv_interscale_similarity and amskv_cache_export read the scale in place.
+ * The caller must then keep K_dev/V_dev valid and unchanged until the next append or reset on
+ * that layer (or the destroy).  Such a scale needs no arena space (capacities shrink
+ * accordingly) and amskv_cache_layout reports it with tok_offset = -1.  With 0 (default) every
+ * appended scale is copied and K_dev/V_dev may be reused as soon as the append has run. */
 
 /* Bytes the arena must have for this configuration: for every layer the K and V regions
  * sized for the largest kept set the policy ever reaches (Section 4.3: capacity is fixed
@@ -106,7 +118,8 @@ int32_t amskv_cache_create(int32_t layers, int32_t heads, int32_t head_dim,
  * K_dev/V_dev ([B][H][T_s][D], device) are copied to their slot.  Scales must arrive in
  * order 0,1,2,... per layer (else AMSKV_ERR_ORDER).  The host metadata is updated before
  * the call returns, the device work is asynchronous on `stream`; K_dev/V_dev must stay
- * valid until it has run.  K_dev == V_dev == NULL updates metadata only. */
+ * valid until it has run (longer for a borrowed scale, see borrow_unretained).
+ * K_dev == V_dev == NULL updates metadata only. */
 int32_t amskv_append_scale(amskv_cache* cache, int32_t layer, int32_t s,
                            const void* K_dev, const void* V_dev, void* stream);
 
@@ -135,7 +148,8 @@ int32_t amskv_interscale_similarity(amskv_cache* cache, int32_t layer, int32_t s
 
 /* Resident segments of a layer, ascending scale id: n_seg entries written to each
  * caller array of at least AMSKV_MAX_SCALES elements.  tok_offset is the position of the
- * segment inside the [cap_l] token axis of the layer's K and V regions.  Host only. */
+ * segment inside the [cap_l] token axis of the layer's K and V regions, or -1 for a scale
+ * that is read in place from the caller's buffers (borrow_unretained).  Host only. */
 int32_t amskv_cache_layout(const amskv_cache* cache, int32_t layer, int32_t* n_seg,
                            int32_t* scale_id, int64_t* tok_offset, int32_t* tok_len);
 
@@ -143,7 +157,8 @@ int32_t amskv_cache_layout(const amskv_cache* cache, int32_t layer, int32_t* n_s
 int32_t amskv_cache_last_evicted(const amskv_cache* cache, int32_t layer, int32_t* n_evicted,
                                  int32_t* scale_id);
 
-/* K+V bytes resident in a layer: 2 * elem * B * H * D * sum of T_k over resident scales
+/* K+V bytes visible to a layer's attention: 2 * elem * B * H * D * sum of T_k over the resident
+ * scales (a borrowed current scale counts only under include_current != 0)
  * (Eq. 4's accounting with its constant written as 2*elem).  include_current == 0 leaves
  * out the newest scale (Algorithm 1 never stores a scale larger than C_max, so the
  * paper's end-of-generation figure excludes it).  Negative status on error.  Host only. */

@@ -93,6 +93,24 @@ def evicted_scales(policy: Policy, s: int) -> List[int]:
     return sorted(before - after)
 
 
+def stored_scales(policy: Policy, s: int, n_scales: int) -> List[int]:
+    """Scales that occupy cache memory after step s when only scales a LATER step reads are
+    stored (Algorithm 1 appends a scale for the benefit of the following iterations; a scale
+    no later step sees -- the last one of the schedule, or any non-condensed scale under a
+    zero window -- is used by its own step's attention and never written to the cache)."""
+    out = []
+    for k in kept_scales(policy, s):
+        read_later = any(visible(policy, later, k) for later in range(k + 1, n_scales))
+        if read_later:
+            out.append(k)
+    return out
+
+
+def stored_capacity(tokens: Sequence[int], policy: Policy) -> int:
+    n = len(tokens)
+    return max(sum(int(tokens[k]) for k in stored_scales(policy, s, n)) for s in range(n))
+
+
 def kept_token_count(tokens: Sequence[int], policy: Policy, s: int) -> int:
     return sum(int(tokens[k]) for k in kept_scales(policy, s))
 

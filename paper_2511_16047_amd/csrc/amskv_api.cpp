@@ -11,13 +11,17 @@
 
 namespace {
 
+using amskv::ExtKV;
 using amskv::MoveList;
+using amskv::ScaleRef;
 using amskv::SegTable;
 
 struct Segment {
   int32_t scale;
-  int32_t off;  // token offset inside the layer's [cap] axis
+  int32_t off;  // token offset inside the layer's [cap] axis; -1: borrowed (read in place)
   int32_t len;
+  const void* ext_k = nullptr;  // borrowed scale: the caller's K/V of that scale
+  const void* ext_v = nullptr;
 };
 
 struct LayerState {
@@ -34,7 +38,7 @@ struct LayerState {
 }  // namespace
 
 struct amskv_cache {
-  int32_t layers, heads, head_dim, batch, dtype, n_scales, layout;
+  int32_t layers, heads, head_dim, batch, dtype, n_scales, layout, borrow;
   int32_t side_h[AMSKV_MAX_SCALES], side_w[AMSKV_MAX_SCALES], tokens[AMSKV_MAX_SCALES];
   float softmax_scale;
   int32_t elem_bytes;
@@ -62,6 +66,13 @@ inline int last_step_resident(const amskv_layer_policy& p, int k, int n_scales) 
   return std::min(n_scales - 1, k + p.window);
 }
 
+// Algorithm 1 stores a scale only when a later step will read it.  With borrow_unretained a
+// scale that no step after its own reads (the last scale of the schedule; every scale under a
+// zero window outside the condensed set) is never copied into the arena.
+inline bool stored(const amskv_layer_policy& p, int k, int n_scales, bool borrow) {
+  return !borrow || last_step_resident(p, k, n_scales) > k;
+}
+
 int validate(int32_t layers, int32_t heads, int32_t head_dim, const amskv_schedule* sc,
              const amskv_policy* po) {
   if (!sc || !po || layers < 1 || heads < 1) return AMSKV_ERR_INVALID_ARG;
@@ -82,32 +93,36 @@ int validate(int32_t layers, int32_t heads, int32_t head_dim, const amskv_schedu
   if (po->n_layers != layers || !po->layer) return AMSKV_ERR_INVALID_ARG;
   if (po->layout != AMSKV_LAYOUT_COMPACT && po->layout != AMSKV_LAYOUT_PLANNED)
     return AMSKV_ERR_INVALID_ARG;
+  if (po->borrow_unretained != 0 && po->borrow_unretained != 1) return AMSKV_ERR_INVALID_ARG;
   if (!(po->softmax_scale >= 0.f) || !std::isfinite(po->softmax_scale)) return AMSKV_ERR_INVALID_ARG;
   for (int l = 0; l < layers; ++l)
     if (po->layer[l].n_condensed < 0 || po->layer[l].window < 0) return AMSKV_ERR_INVALID_ARG;
   return AMSKV_OK;
 }
 
-// Capacity of a layer in the COMPACT layout: the largest kept-token count over all steps.
-int64_t compact_capacity(const amskv_layer_policy& p, const int32_t* tokens, int n_scales) {
+// Capacity of a layer in the COMPACT layout: the largest stored-token count over all steps.
+int64_t compact_capacity(const amskv_layer_policy& p, const int32_t* tokens, int n_scales, bool borrow) {
   int64_t best = 0;
   for (int s = 0; s < n_scales; ++s) {
     int64_t sum = 0;
     for (int k = 0; k <= s; ++k)
-      if (resident(p, s, k)) sum += tokens[k];
+      if (resident(p, s, k) && stored(p, k, n_scales, borrow)) sum += tokens[k];
     best = std::max(best, sum);
   }
   return best;
 }
 
 // PLANNED layout: the schedule and the policy fix, at create time, the interval of steps
-// [k, last_k] during which scale k is resident.  Give every scale a slot such that scales
-// with overlapping lifetimes never overlap in memory (largest scale first, lowest free
+// [k, last_k] during which scale k is resident.  Give every stored scale a slot such that
+// scales with overlapping lifetimes never overlap in memory (largest scale first, lowest free
 // offset), so eviction needs no data movement at all.  Returns the capacity reached.
-int64_t plan_slots(const amskv_layer_policy& p, const int32_t* tokens, int n_scales,
+int64_t plan_slots(const amskv_layer_policy& p, const int32_t* tokens, int n_scales, bool borrow,
                    int32_t* off_out) {
-  std::vector<int> order(n_scales);
-  for (int i = 0; i < n_scales; ++i) order[i] = i;
+  std::vector<int> order;
+  for (int i = 0; i < n_scales; ++i) {
+    off_out[i] = -1;
+    if (stored(p, i, n_scales, borrow)) order.push_back(i);
+  }
   std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return tokens[a] > tokens[b]; });
   std::vector<char> placed(n_scales, 0);
   int64_t cap = 0;
@@ -146,6 +161,7 @@ void build_plan(int32_t layers, int32_t heads, int32_t head_dim, const amskv_sch
   const uint64_t eb = sc->dtype == AMSKV_DTYPE_BF16 ? 2 : 4;
   const uint64_t row = (uint64_t)head_dim * eb;
   const uint64_t bh = (uint64_t)sc->batch * heads;
+  const bool borrow = po->borrow_unretained != 0;
   uint64_t at = 0;
   pl->cap.resize(layers);
   pl->k_off.resize(layers);
@@ -154,9 +170,9 @@ void build_plan(int32_t layers, int32_t heads, int32_t head_dim, const amskv_sch
   for (int l = 0; l < layers; ++l) {
     int64_t cap;
     if (po->layout == AMSKV_LAYOUT_PLANNED)
-      cap = plan_slots(po->layer[l], tokens, sc->n_scales, pl->slot[l].data());
+      cap = plan_slots(po->layer[l], tokens, sc->n_scales, borrow, pl->slot[l].data());
     else
-      cap = compact_capacity(po->layer[l], tokens, sc->n_scales);
+      cap = compact_capacity(po->layer[l], tokens, sc->n_scales, borrow);
     pl->cap[l] = cap;
     pl->k_off[l] = at;
     at = align_up(at + bh * (uint64_t)cap * row);
@@ -173,18 +189,28 @@ inline bool bad_layer(const amskv_cache* c, int32_t layer) {
   return !c || layer < 0 || layer >= c->layers;
 }
 
-SegTable seg_table(const LayerState& L) {
+// Segment table for the kernels; a borrowed segment (always the newest scale, hence last)
+// becomes the external tail of the virtual concatenation.
+SegTable seg_table(const LayerState& L, ExtKV* ext) {
   SegTable t;
   std::memset(&t, 0, sizeof(t));
+  ext->k = ext->v = nullptr;
   t.n = (int32_t)L.segs.size();
   int32_t v = 0;
+  int32_t ext_start = -1;
   for (int i = 0; i < t.n; ++i) {
     t.virt_start[i] = v;
-    t.phys_off[i] = L.segs[i].off;
+    t.phys_off[i] = L.segs[i].off < 0 ? 0 : L.segs[i].off;
     t.len[i] = L.segs[i].len;
+    if (L.segs[i].off < 0) {
+      ext_start = v;
+      ext->k = L.segs[i].ext_k;
+      ext->v = L.segs[i].ext_v;
+    }
     v += L.segs[i].len;
   }
   t.total = v;
+  t.ext_start = ext_start < 0 ? v : ext_start;
   return t;
 }
 
@@ -239,6 +265,7 @@ int32_t amskv_cache_create(int32_t layers, int32_t heads, int32_t head_dim,
   c->dtype = sc->dtype;
   c->n_scales = sc->n_scales;
   c->layout = po->layout;
+  c->borrow = po->borrow_unretained;
   c->elem_bytes = sc->dtype == AMSKV_DTYPE_BF16 ? 2 : 4;
   c->softmax_scale = po->softmax_scale > 0.f ? po->softmax_scale : 1.0f / std::sqrt((float)head_dim);
   for (int i = 0; i < sc->n_scales; ++i) {
@@ -270,7 +297,8 @@ int32_t amskv_append_scale(amskv_cache* c, int32_t layer, int32_t s, const void*
   if (s != L.last_scale + 1) return AMSKV_ERR_ORDER;
   if (K_dev && !c->arena) return AMSKV_ERR_NO_DEVICE_MEMORY;
 
-  // new resident list (ascending scale id) and where each segment goes
+  // new resident list (ascending scale id) and where each segment goes; a borrowed segment of
+  // the previous step is by construction not resident any more and simply drops out
   std::vector<Segment> next;
   std::vector<int32_t> evicted;
   MoveList mv;
@@ -297,15 +325,22 @@ int32_t amskv_append_scale(amskv_cache* c, int32_t layer, int32_t s, const void*
   Segment cur;
   cur.scale = s;
   cur.len = c->tokens[s];
-  cur.off = c->layout == AMSKV_LAYOUT_COMPACT ? at : L.planned_off[s];
-  if ((int64_t)cur.off + cur.len > L.cap) return AMSKV_ERR_ARENA_TOO_SMALL;  // cannot happen: cap is the max over steps
+  const bool keep_copy = stored(L.pol, s, c->n_scales, c->borrow != 0);
+  if (keep_copy) {
+    cur.off = c->layout == AMSKV_LAYOUT_COMPACT ? at : L.planned_off[s];
+    if ((int64_t)cur.off + cur.len > L.cap) return AMSKV_ERR_ARENA_TOO_SMALL;  // cannot happen: cap is the max over steps
+  } else {
+    cur.off = -1;
+    cur.ext_k = K_dev;
+    cur.ext_v = V_dev;
+  }
   next.push_back(cur);
 
-  if (K_dev) {
+  if (K_dev && (keep_copy || mv.n > 0)) {
     const int bh = c->batch * c->heads;
-    hipError_t e = amskv::launch_append(c->arena + L.k_off, c->arena + L.v_off, K_dev, V_dev, bh,
-                                        c->head_dim * c->elem_bytes, L.cap, mv, cur.len, cur.off,
-                                        (hipStream_t)stream);
+    hipError_t e = amskv::launch_append(c->arena + L.k_off, c->arena + L.v_off, keep_copy ? K_dev : nullptr,
+                                        keep_copy ? V_dev : nullptr, bh, c->head_dim * c->elem_bytes, L.cap,
+                                        mv, cur.len, keep_copy ? cur.off : 0, (hipStream_t)stream);
     if (e != hipSuccess) return AMSKV_ERR_HIP;
   }
   L.segs.swap(next);
@@ -321,16 +356,18 @@ int32_t amskv_attend(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev
   LayerState& L = c->layer[layer];
   if (s != L.last_scale) return AMSKV_ERR_ORDER;
   if (!c->arena) return AMSKV_ERR_NO_DEVICE_MEMORY;
-  const SegTable t = seg_table(L);
+  ExtKV ext;
+  const SegTable t = seg_table(L, &ext);
+  if (t.ext_start < t.total && !ext.k) return AMSKV_ERR_NO_DEVICE_MEMORY;  // borrowed scale appended without data
   const int bh = c->batch * c->heads;
   hipError_t e;
   if (c->dtype == AMSKV_DTYPE_BF16)
     e = amskv::launch_attend_bf16(Q_dev, O_dev, c->arena + L.k_off, c->arena + L.v_off, bh,
-                                  c->tokens[s], c->head_dim, L.cap, t, c->softmax_scale,
+                                  c->tokens[s], c->head_dim, L.cap, t, ext, c->softmax_scale,
                                   (hipStream_t)stream);
   else
     e = amskv::launch_attend_f32(Q_dev, O_dev, c->arena + L.k_off, c->arena + L.v_off, bh,
-                                 c->tokens[s], c->head_dim, L.cap, t, c->softmax_scale,
+                                 c->tokens[s], c->head_dim, L.cap, t, ext, c->softmax_scale,
                                  (hipStream_t)stream);
   return e == hipSuccess ? AMSKV_OK : AMSKV_ERR_HIP;
 }
@@ -348,14 +385,29 @@ int32_t amskv_interscale_similarity(amskv_cache* c, int32_t layer, int32_t s, fl
   }
   if (!cur || !prev) return AMSKV_ERR_EVICTED;
   if (!c->arena) return AMSKV_ERR_NO_DEVICE_MEMORY;
+  if ((cur->off < 0 && !cur->ext_k) || (prev->off < 0 && !prev->ext_k)) return AMSKV_ERR_NO_DEVICE_MEMORY;
   const uint64_t bh = (uint64_t)c->batch * c->heads;
   float* partial = (float*)(c->arena + c->ws_off);
   float* totals = partial + 2 * bh * 4;
   hipStream_t st = (hipStream_t)stream;
-  hipError_t e = amskv::launch_similarity(
-      c->arena + L.k_off, cosV_host ? c->arena + L.v_off : nullptr, c->batch, c->heads,
-      c->head_dim, c->dtype, L.cap, cur->off, prev->off, c->side_h[s], c->side_w[s],
-      c->side_h[s - 1], c->side_w[s - 1], partial, totals, st);
+  auto ref = [&](const Segment* g) {
+    ScaleRef r;
+    if (g->off < 0) {
+      r.k = g->ext_k;
+      r.v = cosV_host ? g->ext_v : nullptr;
+      r.stride_tokens = g->len;
+      r.off_tokens = 0;
+    } else {
+      r.k = c->arena + L.k_off;
+      r.v = cosV_host ? c->arena + L.v_off : nullptr;
+      r.stride_tokens = L.cap;
+      r.off_tokens = g->off;
+    }
+    return r;
+  };
+  hipError_t e = amskv::launch_similarity(ref(cur), ref(prev), c->batch, c->heads, c->head_dim, c->dtype,
+                                          c->side_h[s], c->side_w[s], c->side_h[s - 1], c->side_w[s - 1],
+                                          partial, totals, st);
   if (e != hipSuccess) return AMSKV_ERR_HIP;
   std::vector<float> host(2 * (size_t)c->heads * 4);
   const size_t n_t = cosV_host ? 2 : 1;
@@ -419,9 +471,11 @@ int32_t amskv_cache_export(const amskv_cache* c, int32_t layer, void* K_out_dev,
   if (!c->arena) return AMSKV_ERR_NO_DEVICE_MEMORY;
   const LayerState& L = c->layer[layer];
   if (L.segs.empty()) return AMSKV_OK;
-  const SegTable t = seg_table(L);
+  ExtKV ext;
+  const SegTable t = seg_table(L, &ext);
+  if (t.ext_start < t.total && !ext.k) return AMSKV_ERR_NO_DEVICE_MEMORY;
   hipError_t e = amskv::launch_export(c->arena + L.k_off, c->arena + L.v_off, K_out_dev, V_out_dev,
-                                      c->batch * c->heads, c->head_dim * c->elem_bytes, L.cap, t,
+                                      c->batch * c->heads, c->head_dim * c->elem_bytes, L.cap, t, ext,
                                       (hipStream_t)stream);
   return e == hipSuccess ? AMSKV_OK : AMSKV_ERR_HIP;
 }

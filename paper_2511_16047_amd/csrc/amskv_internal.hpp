@@ -11,12 +11,22 @@ namespace amskv {
 // `len[i]` tokens; in the virtual concatenation K~ of Section 3.1's per-step attention it
 // covers rows [virt_start[i], virt_start[i]+len[i]); in the layer's K/V regions it sits at
 // token offset phys_off[i].  Passed to kernels by value (lives in scalar registers).
+// A borrowed current scale (read in place from the caller's K/V, never copied) is always the
+// last segment: it covers virtual rows [ext_start, total) and its rows come from the external
+// pointers handed to the kernel next to the table; ext_start == total when nothing is borrowed.
 struct SegTable {
   int32_t n;
-  int32_t total;  // sum of len = T_kv
+  int32_t total;      // sum of len = T_kv
+  int32_t ext_start;  // first virtual row of the borrowed segment (== total: none)
   int32_t virt_start[AMSKV_MAX_SCALES];
   int32_t phys_off[AMSKV_MAX_SCALES];
   int32_t len[AMSKV_MAX_SCALES];
+};
+
+// External (borrowed) K and V of the current scale: [BH][ext_len][row], or null pointers.
+struct ExtKV {
+  const void* k;
+  const void* v;
 };
 
 // Token ranges that slide toward lower offsets when scales are evicted (COMPACT layout),
@@ -28,24 +38,48 @@ struct MoveList {
   int32_t len[AMSKV_MAX_SCALES];
 };
 
+#if defined(__HIPCC__)
+// Virtual row j of K~/V~ -> row index inside the layer's cache region of this (b,h), or, for a
+// row of the borrowed segment, row index inside the external tensor of this (b,h) (ext = true).
+__device__ __forceinline__ int locate_row(const SegTable& seg, int j, bool& ext) {
+  ext = j >= seg.ext_start;
+  int delta = -seg.ext_start;
+  if (!ext) {
+    delta = 0;
+    for (int g = 0; g < seg.n; ++g)
+      if (j >= seg.virt_start[g]) delta = seg.phys_off[g] - seg.virt_start[g];
+  }
+  return j + delta;
+}
+#endif
+
 // ---- kernel launchers (each validates nothing: the host layer has checked shapes) ----
 hipError_t launch_attend_bf16(const void* q, void* o, const void* kc, const void* vc, int bh,
                               int t_q, int head_dim, int64_t cap_tokens, const SegTable& seg,
-                              float softmax_scale, hipStream_t st);
+                              const ExtKV& ext, float softmax_scale, hipStream_t st);
 hipError_t launch_attend_bf16_small(const void* q, void* o, const void* kc, const void* vc, int bh,
                                     int t_q, int head_dim, int64_t cap_tokens, const SegTable& seg,
-                                    float softmax_scale, hipStream_t st);
+                                    const ExtKV& ext, float softmax_scale, hipStream_t st);
 hipError_t launch_attend_f32(const void* q, void* o, const void* kc, const void* vc, int bh,
                              int t_q, int head_dim, int64_t cap_tokens, const SegTable& seg,
-                             float softmax_scale, hipStream_t st);
+                             const ExtKV& ext, float softmax_scale, hipStream_t st);
+// k_new == nullptr: compaction only (the new scale is borrowed, nothing to copy)
 hipError_t launch_append(void* kc, void* vc, const void* k_new, const void* v_new, int bh,
                          int row_bytes, int64_t cap_tokens, const MoveList& mv, int t_new,
                          int dst_new, hipStream_t st);
 hipError_t launch_export(const void* kc, const void* vc, void* k_out, void* v_out, int bh,
-                         int row_bytes, int64_t cap_tokens, const SegTable& seg, hipStream_t st);
-hipError_t launch_similarity(const void* kc, const void* vc, int batch, int heads, int head_dim,
-                             int dtype, int64_t cap_tokens, int off_cur, int off_prev, int h_cur,
-                             int w_cur, int h_prev, int w_prev, float* partial_ws, float* out_dev,
-                             hipStream_t st);
+                         int row_bytes, int64_t cap_tokens, const SegTable& seg, const ExtKV& ext,
+                         hipStream_t st);
+// cur_k/cur_v, prev_k/prev_v: base of the tensor holding the scale ([BH][stride tokens][row]),
+// token offset of the scale inside each (b,h) row; v pointers may be null (keys only)
+struct ScaleRef {
+  const void* k;
+  const void* v;
+  int64_t stride_tokens;
+  int32_t off_tokens;
+};
+hipError_t launch_similarity(const ScaleRef& cur, const ScaleRef& prev, int batch, int heads,
+                             int head_dim, int dtype, int h_cur, int w_cur, int h_prev, int w_prev,
+                             float* partial_ws, float* out_dev, hipStream_t st);
 
 }  // namespace amskv

@@ -34,7 +34,8 @@
 // puts lane i's 16 bytes at base + 16*i, so the XOR swizzle that keeps the 16-byte fragment reads
 // conflict-free (chunk ^= row & 7) is applied on the global side: the lane that fills LDS chunk
 // position c' of row r fetches global chunk c' ^ (r & 7).  Rows past the end of K~ re-read the
-// last valid row (finite data) and their scores are set to -inf.  The ring has four slots: tile
+// last valid row (finite data) and their scores are set to -inf.  A borrowed current scale is the
+// tail of the virtual concatenation and its rows are fetched from the caller's K/V instead.  The ring has four slots: tile
 // t-1 (its last block's V is still being multiplied), t (in use), t+1 and t+2 (in flight).
 #include <cstdlib>
 
@@ -103,20 +104,18 @@ struct TileLoader {
   static_assert(kLoadsPerWave >= 1 && kLoadsPerWave * kRowsPerLoad * kWaves == kTileKeys, "tile/wave split");
 
   // Issue the loads of tile rows j0..j0+kTileKeys-1 of the virtual concatenation into one ring slot.
-  __device__ static __forceinline__ void issue(const char* kb, const char* vb, char* lds_k, char* lds_v, int j0,
+  __device__ static __forceinline__ void issue(const char* kb, const char* vb, const char* xk, const char* xv, char* lds_k, char* lds_v, int j0,
                                                int t_kv, const SegTable& seg, int wave, int lane) {
 #pragma unroll
     for (int i = 0; i < kLoadsPerWave; ++i) {
       const int blk = wave * kLoadsPerWave + i;  // which 1 KB block of the tile
       const int row = blk * kRowsPerLoad + lane / CPR;
       const int cpos = lane % CPR;
-      const int j = min(j0 + row, t_kv - 1);
-      int delta = 0;
-      for (int g = 0; g < seg.n; ++g)
-        if (j >= seg.virt_start[g]) delta = seg.phys_off[g] - seg.virt_start[g];
-      const long long off = (long long)(j + delta) * RB + 16 * (cpos ^ (row & 7));
-      lds_dma16(kb + off, lds_k + blk * 1024);
-      lds_dma16(vb + off, lds_v + blk * 1024);
+      bool ext;
+      const int row_at = locate_row(seg, min(j0 + row, t_kv - 1), ext);
+      const long long off = (long long)row_at * RB + 16 * (cpos ^ (row & 7));
+      lds_dma16((ext ? xk : kb) + off, lds_k + blk * 1024);
+      lds_dma16((ext ? xv : vb) + off, lds_v + blk * 1024);
     }
   }
 };
@@ -124,7 +123,7 @@ struct TileLoader {
 template <int D, int NQ, int kWaves, int kTileKeys, int kMinWavesPerSimd>
 __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_kernel(
     const __bf16* __restrict__ q, __bf16* __restrict__ o, const char* __restrict__ kc, const char* __restrict__ vc,
-    int t_q, long long cap_tokens, SegTable seg, float scale_log2e, int n_bh, int n_qtiles) {
+    int t_q, long long cap_tokens, SegTable seg, ExtKV ext_kv, float scale_log2e, int n_bh, int n_qtiles) {
   using Loader = TileLoader<D, kWaves, kTileKeys>;
   constexpr int RB = D * 2;   // bytes per token row
   constexpr int KS = D / 16;  // K-steps of the first product
@@ -156,6 +155,10 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
   const int n_blocks = (t_kv + 31) / 32;
   const char* kb = kc + bh * cap_tokens * RB;
   const char* vb = vc + bh * cap_tokens * RB;
+  // the borrowed current scale, if any: [BH][T_s][D] in the caller's buffers
+  const long long ext_rows = bh * (long long)(seg.total - seg.ext_start);
+  const char* xk = (const char*)ext_kv.k + ext_rows * RB;
+  const char* xv = (const char*)ext_kv.v + ext_rows * RB;
 
   // ---- prologue: the Q fragments, then two tiles; all of it stays in flight until the first
   // wait of the tile loop (loads complete in issue order, so that wait covers Q as well).
@@ -171,7 +174,7 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
 #pragma unroll
   for (int st = 0; st < 2; ++st)
     if (st < n_tiles)
-      Loader::issue(kb, vb, lds_k + st * kTileBytes, lds_v + st * kTileBytes, st * kTileKeys, t_kv, seg, wave, lane);
+      Loader::issue(kb, vb, xk, xv, lds_k + st * kTileBytes, lds_v + st * kTileBytes, st * kTileKeys, t_kv, seg, wave, lane);
 
   f32x16 oacc[NQ][DB];
 #pragma unroll
@@ -232,7 +235,7 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
       }
       if (it + 2 < n_tiles) {
         const int slot = (it + 2) % kStages;
-        Loader::issue(kb, vb, lds_k + slot * kTileBytes, lds_v + slot * kTileBytes, (it + 2) * kTileKeys, t_kv, seg,
+        Loader::issue(kb, vb, xk, xv, lds_k + slot * kTileBytes, lds_v + slot * kTileBytes, (it + 2) * kTileKeys, t_kv, seg,
                       wave, lane);
       }
     }
@@ -379,12 +382,12 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
 
 template <int D, int NQ, int kWaves, int kTileKeys, int kMinWavesPerSimd>
 hipError_t launch(const void* q, void* o, const void* kc, const void* vc, int bh, int t_q, int64_t cap_tokens,
-                  const SegTable& seg, float c, hipStream_t st) {
+                  const SegTable& seg, const ExtKV& ext, float c, hipStream_t st) {
   constexpr int BM = kWaves * 32 * NQ;
   const int n_qtiles = (t_q + BM - 1) / BM;
   dim3 grid((unsigned)(((bh + 7) / 8) * 8 * n_qtiles)), block(64 * kWaves);
   hipLaunchKernelGGL((attend_bf16_kernel<D, NQ, kWaves, kTileKeys, kMinWavesPerSimd>), grid, block, 0, st,
-                     (const __bf16*)q, (__bf16*)o, (const char*)kc, (const char*)vc, t_q, (long long)cap_tokens, seg, c,
+                     (const __bf16*)q, (__bf16*)o, (const char*)kc, (const char*)vc, t_q, (long long)cap_tokens, seg, ext, c,
                      bh, n_qtiles);
   return hipGetLastError();
 }
@@ -392,7 +395,7 @@ hipError_t launch(const void* q, void* o, const void* kc, const void* vc, int bh
 }  // namespace
 
 hipError_t launch_attend_bf16(const void* q, void* o, const void* kc, const void* vc, int bh, int t_q,
-                              int head_dim, int64_t cap_tokens, const SegTable& seg, float softmax_scale,
+                              int head_dim, int64_t cap_tokens, const SegTable& seg, const ExtKV& ext, float softmax_scale,
                               hipStream_t st) {
 #if defined(AMSKV_TUNE_ENV)
   static const int small_tq = getenv("AMSKV_SMALL_TQ") ? atoi(getenv("AMSKV_SMALL_TQ")) : kSmallTq;
@@ -400,16 +403,16 @@ hipError_t launch_attend_bf16(const void* q, void* o, const void* kc, const void
   constexpr int small_tq = kSmallTq;
 #endif
   // coarse scales: latency-bound, one independent wave per 32 query rows
-  if (t_q <= small_tq) return launch_attend_bf16_small(q, o, kc, vc, bh, t_q, head_dim, cap_tokens, seg, softmax_scale, st);
+  if (t_q <= small_tq) return launch_attend_bf16_small(q, o, kc, vc, bh, t_q, head_dim, cap_tokens, seg, ext, softmax_scale, st);
   const float c = softmax_scale * 1.4426950408889634f;
   const bool wide = t_q > 128;  // 256 query rows per workgroup keeps K/V single-pass up to T_q = 256
   if (head_dim == 64)
     // eight waves of 32 rows: ~110 registers per lane, so two workgroups (16 waves) share a CU
-    return wide ? launch<64, 1, 8, 64, 4>(q, o, kc, vc, bh, t_q, cap_tokens, seg, c, st)
-                : launch<64, 1, 4, 32, 4>(q, o, kc, vc, bh, t_q, cap_tokens, seg, c, st);
+    return wide ? launch<64, 1, 8, 64, 4>(q, o, kc, vc, bh, t_q, cap_tokens, seg, ext, c, st)
+                : launch<64, 1, 4, 32, 4>(q, o, kc, vc, bh, t_q, cap_tokens, seg, ext, c, st);
   // head dim 128: 32-key tiles (16 KB per slot) keep two workgroups per CU inside 160 KB of LDS
-  return wide ? launch<128, 2, 4, 32, 1>(q, o, kc, vc, bh, t_q, cap_tokens, seg, c, st)
-              : launch<128, 1, 4, 32, 1>(q, o, kc, vc, bh, t_q, cap_tokens, seg, c, st);
+  return wide ? launch<128, 2, 4, 32, 1>(q, o, kc, vc, bh, t_q, cap_tokens, seg, ext, c, st)
+              : launch<128, 1, 4, 32, 1>(q, o, kc, vc, bh, t_q, cap_tokens, seg, ext, c, st);
 }
 
 }  // namespace amskv

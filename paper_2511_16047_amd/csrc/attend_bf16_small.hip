@@ -35,17 +35,10 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
   return r;
 }
 
-__device__ __forceinline__ int phys_row(const SegTable& seg, int j) {
-  int delta = 0;
-  for (int g = 0; g < seg.n; ++g)
-    if (j >= seg.virt_start[g]) delta = seg.phys_off[g] - seg.virt_start[g];
-  return j + delta;
-}
-
 template <int D>
 __global__ __launch_bounds__(64 * kWavesPerGroup) void attend_bf16_small_kernel(
     const __bf16* __restrict__ q, __bf16* __restrict__ o, const char* __restrict__ kc, const char* __restrict__ vc,
-    int t_q, long long cap_tokens, SegTable seg, float scale_log2e, int n_qblk, int n_units) {
+    int t_q, long long cap_tokens, SegTable seg, ExtKV ext_kv, float scale_log2e, int n_qblk, int n_units) {
   constexpr int RB = D * 2;
   constexpr int CPR = D / 8;
   constexpr int KS = D / 16;
@@ -65,6 +58,9 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void attend_bf16_small_kernel(
   const int n_blocks = (t_kv + 31) / 32;
   const char* kb = kc + bh * cap_tokens * RB;
   const char* vb = vc + bh * cap_tokens * RB;
+  const long long ext_rows = bh * (long long)(seg.total - seg.ext_start);  // borrowed current scale, if any
+  const char* xk = (const char*)ext_kv.k + ext_rows * RB;
+  const char* xv = (const char*)ext_kv.v + ext_rows * RB;
   char* my_v = lds_v[wave];
 
   bf16x8 qf[KS];
@@ -78,13 +74,17 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void attend_bf16_small_kernel(
   uint4 vch[VCH];
   auto load_block = [&](int g) {
     const int j0 = 32 * g;
-    const long long krow = (long long)phys_row(seg, min(j0 + r, t_kv - 1)) * RB;
+    bool kext;
+    const long long krow = (long long)locate_row(seg, min(j0 + r, t_kv - 1), kext) * RB;
+    const char* kp = (kext ? xk : kb) + krow;
 #pragma unroll
-    for (int t = 0; t < KS; ++t) kf[t] = *reinterpret_cast<const bf16x8*>(kb + krow + 32 * t + 16 * h);
+    for (int t = 0; t < KS; ++t) kf[t] = *reinterpret_cast<const bf16x8*>(kp + 32 * t + 16 * h);
 #pragma unroll
     for (int k = 0; k < VCH; ++k) {
       const int id = k * 64 + lane, row = id / CPR, c = id % CPR;
-      vch[k] = *reinterpret_cast<const uint4*>(vb + (long long)phys_row(seg, min(j0 + row, t_kv - 1)) * RB + 16 * c);
+      bool vext;
+      const long long vrow = (long long)locate_row(seg, min(j0 + row, t_kv - 1), vext) * RB;
+      vch[k] = *reinterpret_cast<const uint4*>((vext ? xv : vb) + vrow + 16 * c);
     }
   };
   load_block(0);
@@ -182,7 +182,8 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void attend_bf16_small_kernel(
 }  // namespace
 
 hipError_t launch_attend_bf16_small(const void* q, void* o, const void* kc, const void* vc, int bh, int t_q,
-                                    int head_dim, int64_t cap_tokens, const SegTable& seg, float softmax_scale,
+                                    int head_dim, int64_t cap_tokens, const SegTable& seg, const ExtKV& ext,
+                                    float softmax_scale,
                                     hipStream_t st) {
   const float c = softmax_scale * 1.4426950408889634f;
   const int n_qblk = (t_q + 31) / 32;
@@ -190,10 +191,10 @@ hipError_t launch_attend_bf16_small(const void* q, void* o, const void* kc, cons
   dim3 grid((unsigned)((n_units + kWavesPerGroup - 1) / kWavesPerGroup)), block(64 * kWavesPerGroup);
   if (head_dim == 64)
     hipLaunchKernelGGL(attend_bf16_small_kernel<64>, grid, block, 0, st, (const __bf16*)q, (__bf16*)o, (const char*)kc,
-                       (const char*)vc, t_q, (long long)cap_tokens, seg, c, n_qblk, (int)n_units);
+                       (const char*)vc, t_q, (long long)cap_tokens, seg, ext, c, n_qblk, (int)n_units);
   else
     hipLaunchKernelGGL(attend_bf16_small_kernel<128>, grid, block, 0, st, (const __bf16*)q, (__bf16*)o, (const char*)kc,
-                       (const char*)vc, t_q, (long long)cap_tokens, seg, c, n_qblk, (int)n_units);
+                       (const char*)vc, t_q, (long long)cap_tokens, seg, ext, c, n_qblk, (int)n_units);
   return hipGetLastError();
 }
 

@@ -18,7 +18,7 @@ __global__ __launch_bounds__(kThreads) void attend_f32_kernel(const float* __res
                                                               const float* __restrict__ kc,
                                                               const float* __restrict__ vc, int t_q,
                                                               long long cap_tokens, SegTable seg,
-                                                              float scale_log2e) {
+                                                              ExtKV ext_kv, float scale_log2e) {
   constexpr int M = D / 16;  // float4 pieces per lane
   __shared__ __align__(16) float lds_k[kTileKeys * D];
   __shared__ __align__(16) float lds_v[kTileKeys * D];
@@ -30,6 +30,9 @@ __global__ __launch_bounds__(kThreads) void attend_f32_kernel(const float* __res
   const bool row_ok = row < t_q;
   const float* kb = kc + bh * cap_tokens * D;
   const float* vb = vc + bh * cap_tokens * D;
+  const long long ext_rows = bh * (long long)(seg.total - seg.ext_start);  // borrowed current scale, if any
+  const float* xk = (const float*)ext_kv.k + ext_rows * D;
+  const float* xv = (const float*)ext_kv.v + ext_rows * D;
   const int t_kv = seg.total;
 
   float4 qv[M], acc[M];
@@ -49,12 +52,10 @@ __global__ __launch_bounds__(kThreads) void attend_f32_kernel(const float* __res
       const int j = j0 + r;
       float4 kk = make_float4(0.f, 0.f, 0.f, 0.f), vv = kk;
       if (j < t_kv) {
-        int delta = 0;
-        for (int i = 0; i < seg.n; ++i)
-          if (j >= seg.virt_start[i]) delta = seg.phys_off[i] - seg.virt_start[i];
-        const long long off = (long long)(j + delta) * D + 4 * c;
-        kk = *reinterpret_cast<const float4*>(kb + off);
-        vv = *reinterpret_cast<const float4*>(vb + off);
+        bool ext;
+        const long long off = (long long)locate_row(seg, j, ext) * D + 4 * c;
+        kk = *reinterpret_cast<const float4*>((ext ? xk : kb) + off);
+        vv = *reinterpret_cast<const float4*>((ext ? xv : vb) + off);
       }
       *reinterpret_cast<float4*>(lds_k + r * D + 4 * c) = kk;
       *reinterpret_cast<float4*>(lds_v + r * D + 4 * c) = vv;
@@ -114,16 +115,16 @@ __global__ __launch_bounds__(kThreads) void attend_f32_kernel(const float* __res
 }  // namespace
 
 hipError_t launch_attend_f32(const void* q, void* o, const void* kc, const void* vc, int bh, int t_q,
-                             int head_dim, int64_t cap_tokens, const SegTable& seg, float softmax_scale,
-                             hipStream_t st) {
+                             int head_dim, int64_t cap_tokens, const SegTable& seg, const ExtKV& ext,
+                             float softmax_scale, hipStream_t st) {
   const float c = softmax_scale * 1.4426950408889634f;
   dim3 grid(bh, (t_q + kRowsPerBlock - 1) / kRowsPerBlock), block(kThreads);
   if (head_dim == 64)
     hipLaunchKernelGGL(attend_f32_kernel<64>, grid, block, 0, st, (const float*)q, (float*)o, (const float*)kc,
-                       (const float*)vc, t_q, (long long)cap_tokens, seg, c);
+                       (const float*)vc, t_q, (long long)cap_tokens, seg, ext, c);
   else
     hipLaunchKernelGGL(attend_f32_kernel<128>, grid, block, 0, st, (const float*)q, (float*)o, (const float*)kc,
-                       (const float*)vc, t_q, (long long)cap_tokens, seg, c);
+                       (const float*)vc, t_q, (long long)cap_tokens, seg, ext, c);
   return hipGetLastError();
 }
 

@@ -97,9 +97,10 @@ __global__ __launch_bounds__(kThreads) void append_kernel(char* __restrict__ kc,
 __global__ __launch_bounds__(kThreads) void export_kernel(const char* __restrict__ kc,
                                                           const char* __restrict__ vc, char* __restrict__ k_out,
                                                           char* __restrict__ v_out, int row_bytes,
-                                                          long long cap_tokens, SegTable seg) {
+                                                          long long cap_tokens, SegTable seg, ExtKV ext_kv) {
   const long long bh = blockIdx.x;
   const char* base = (blockIdx.y ? vc : kc) + bh * cap_tokens * row_bytes;
+  const char* xbase = (const char*)(blockIdx.y ? ext_kv.v : ext_kv.k) + bh * (long long)(seg.total - seg.ext_start) * row_bytes;
   char* out = blockIdx.y ? v_out : k_out;
   if (!out) return;
   out += bh * (long long)seg.total * row_bytes;
@@ -107,11 +108,9 @@ __global__ __launch_bounds__(kThreads) void export_kernel(const char* __restrict
   const int n = seg.total * cpr;
   for (int c = threadIdx.x; c < n; c += kThreads) {
     const int tok = c / cpr, piece = c - tok * cpr;
-    int delta = 0;
-    for (int i = 0; i < seg.n; ++i)
-      if (tok >= seg.virt_start[i]) delta = seg.phys_off[i] - seg.virt_start[i];
-    const long long so = (long long)(tok + delta) * row_bytes + (piece << 4);
-    *reinterpret_cast<uint4*>(out + ((long long)c << 4)) = *reinterpret_cast<const uint4*>(base + so);
+    bool ext;
+    const long long so = (long long)locate_row(seg, tok, ext) * row_bytes + (piece << 4);
+    *reinterpret_cast<uint4*>(out + ((long long)c << 4)) = *reinterpret_cast<const uint4*>((ext ? xbase : base) + so);
   }
 }
 
@@ -125,6 +124,7 @@ hipError_t launch_append(void* kc, void* vc, const void* k_new, const void* v_ne
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
+  if (!k_new) return hipSuccess;  // borrowed scale: compaction only
   const long long chunks = (long long)bh * t_new * (row_bytes >> 4);
   const long long per_block = (long long)kThreads * kUnroll;
   const unsigned grid = (unsigned)((2 * chunks + per_block - 1) / per_block);
@@ -134,10 +134,10 @@ hipError_t launch_append(void* kc, void* vc, const void* k_new, const void* v_ne
 }
 
 hipError_t launch_export(const void* kc, const void* vc, void* k_out, void* v_out, int bh, int row_bytes,
-                         int64_t cap_tokens, const SegTable& seg, hipStream_t st) {
+                         int64_t cap_tokens, const SegTable& seg, const ExtKV& ext, hipStream_t st) {
   dim3 grid(bh, 2), block(kThreads);
   hipLaunchKernelGGL(export_kernel, grid, block, 0, st, (const char*)kc, (const char*)vc, (char*)k_out,
-                     (char*)v_out, row_bytes, (long long)cap_tokens, seg);
+                     (char*)v_out, row_bytes, (long long)cap_tokens, seg, ext);
   return hipGetLastError();
 }
 

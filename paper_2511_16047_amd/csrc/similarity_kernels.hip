@@ -52,12 +52,13 @@ __device__ __forceinline__ void taps(int dst, int n_in, int n_out, int& i0, int&
 // partial[(tensor*BH + bh)*4 + {0,1,2,3}] = sum_t cos_t, sum a.b, sum |a|^2, sum |b|^2.
 template <bool BF16>
 __global__ __launch_bounds__(kThreads) void similarity_partial_kernel(
-    const char* __restrict__ kc, const char* __restrict__ vc, int row_bytes, long long cap_tokens,
-    int off_cur, int off_prev, int h_cur, int w_cur, int h_prev, int w_prev, float* __restrict__ partial) {
+    ScaleRef cur_ref, ScaleRef prev_ref, int row_bytes, int h_cur, int w_cur, int h_prev, int w_prev,
+    float* __restrict__ partial) {
   const long long bh = blockIdx.x;
-  const char* base = (blockIdx.y ? vc : kc) + bh * cap_tokens * row_bytes;
-  const char* cur = base + (long long)off_cur * row_bytes;
-  const char* prev = base + (long long)off_prev * row_bytes;
+  const char* cur = (const char*)(blockIdx.y ? cur_ref.v : cur_ref.k) +
+                    (bh * cur_ref.stride_tokens + cur_ref.off_tokens) * row_bytes;
+  const char* prev = (const char*)(blockIdx.y ? prev_ref.v : prev_ref.k) +
+                     (bh * prev_ref.stride_tokens + prev_ref.off_tokens) * row_bytes;
   const int lpt = row_bytes >> 4;          // lanes per token: 8, 16 or 32
   const int sub = threadIdx.x % lpt;       // which 16-byte piece of the row
   const int slot = threadIdx.x / lpt;
@@ -140,20 +141,18 @@ __global__ __launch_bounds__(64) void similarity_total_kernel(const float* __res
 
 }  // namespace
 
-hipError_t launch_similarity(const void* kc, const void* vc, int batch, int heads, int head_dim, int dtype,
-                             int64_t cap_tokens, int off_cur, int off_prev, int h_cur, int w_cur, int h_prev,
-                             int w_prev, float* partial_ws, float* out_dev, hipStream_t st) {
-  const int tensors = vc ? 2 : 1;
+hipError_t launch_similarity(const ScaleRef& cur, const ScaleRef& prev, int batch, int heads, int head_dim,
+                             int dtype, int h_cur, int w_cur, int h_prev, int w_prev, float* partial_ws,
+                             float* out_dev, hipStream_t st) {
+  const int tensors = (cur.v && prev.v) ? 2 : 1;
   const int bh = batch * heads;
   dim3 grid(bh, tensors), block(kThreads);
   if (dtype == AMSKV_DTYPE_BF16) {
-    hipLaunchKernelGGL(similarity_partial_kernel<true>, grid, block, 0, st, (const char*)kc, (const char*)vc,
-                       head_dim * 2, (long long)cap_tokens, off_cur, off_prev, h_cur, w_cur, h_prev, w_prev,
-                       partial_ws);
+    hipLaunchKernelGGL(similarity_partial_kernel<true>, grid, block, 0, st, cur, prev, head_dim * 2, h_cur, w_cur,
+                       h_prev, w_prev, partial_ws);
   } else {
-    hipLaunchKernelGGL(similarity_partial_kernel<false>, grid, block, 0, st, (const char*)kc, (const char*)vc,
-                       head_dim * 4, (long long)cap_tokens, off_cur, off_prev, h_cur, w_cur, h_prev, w_prev,
-                       partial_ws);
+    hipLaunchKernelGGL(similarity_partial_kernel<false>, grid, block, 0, st, cur, prev, head_dim * 4, h_cur, w_cur,
+                       h_prev, w_prev, partial_ws);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

@@ -33,18 +33,18 @@ class Runner:
     """Drives one cache through the ABI and checks every step against the oracle."""
 
     def __init__(self, sides_h, sides_w, B, H, D, dtype, policies, layout=amskv.AMSKV_LAYOUT_COMPACT,
-                 softmax_scale=0.0):
+                 softmax_scale=0.0, borrow=False):
         self.sh, self.sw = list(sides_h), list(sides_w)
         self.tokens = orc.scale_tokens(self.sh, self.sw)
         self.B, self.H, self.D, self.dtype = B, H, D, dtype
-        self.policies, self.layout, self.scale = policies, layout, softmax_scale
+        self.policies, self.layout, self.scale, self.borrow = policies, layout, softmax_scale, borrow
         self.eb = 2 if dtype == "bf16" else 4
         need = amskv.amskv_cache_required_bytes(len(policies), H, D, self.sh, self.sw, B, DT[dtype], policies,
-                                                softmax_scale, layout)
+                                                softmax_scale, layout, borrow)
         self.arena = torch.empty(need, dtype=torch.uint8, device="cuda")
         self.arena.fill_(0xFF)          # every stale or never-written element reads as NaN
         self.h = amskv.amskv_cache_create(len(policies), H, D, self.sh, self.sw, B, DT[dtype], policies,
-                                          softmax_scale, layout, arena=self.arena)
+                                          softmax_scale, layout, arena=self.arena, borrow_unretained=borrow)
 
     def close(self):
         amskv.amskv_cache_destroy(self.h)
@@ -55,7 +55,12 @@ class Runner:
         lay = amskv.amskv_cache_layout(self.h, layer)
         assert [x[0] for x in lay] == kept
         assert [x[2] for x in lay] == [self.tokens[k] for k in kept]
-        if self.layout == amskv.AMSKV_LAYOUT_COMPACT:
+        if self.borrow:
+            stored = orc.stored_scales(pol, s, len(self.tokens))
+            assert [x[0] for x in lay if x[1] >= 0] == stored
+            if self.layout == amskv.AMSKV_LAYOUT_COMPACT:
+                assert [x[1] for x in lay if x[1] >= 0] == [sum(self.tokens[j] for j in stored[:i]) for i in range(len(stored))]
+        elif self.layout == amskv.AMSKV_LAYOUT_COMPACT:
             assert [x[1] for x in lay] == orc.segment_offsets(self.tokens, pol, s)
         assert amskv.amskv_cache_last_evicted(self.h, layer) == orc.evicted_scales(pol, s)
         assert amskv.amskv_cache_bytes_held(self.h, layer) == orc.bytes_held(self.tokens, pol, s, self.B, self.H, self.D, self.eb)
@@ -161,6 +166,21 @@ def test_planned_layout_matches_oracle(dtype):
         r.close()
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("layout", [amskv.AMSKV_LAYOUT_COMPACT, amskv.AMSKV_LAYOUT_PLANNED], ids=["compact", "planned"])
+def test_borrowed_unretained_scales(dtype, layout):
+    """Scales that no later step reads are used in place from the caller's K/V and never copied."""
+    sides = inp.VAR_SIDES
+    pols = [(2, 2, False), (0, 0, False), (2, 0, False), (0, 0, True), (1, 3, False)]
+    r = Runner(sides, sides, 2, 3, 64, dtype, pols, layout=layout, borrow=True)
+    try:
+        for layer in range(len(pols)):
+            q, k, v = _qkv(sides, sides, 2, 3, 64, dtype, 700 + layer)
+            r.run_layer(layer, q, k, v)
+    finally:
+        r.close()
+
+
 def test_sixteen_scales_single_scale_and_scale_override():
     sides = tuple(range(1, 17))
     r = Runner(sides, sides, 1, 2, 64, "bf16", [(2, 1, False)], softmax_scale=0.05)
@@ -220,13 +240,14 @@ def test_config4_infinity_shape_small_batch():
 
 
 # ------------------------------------------------------------------ similarity
+@pytest.mark.parametrize("borrow", [False, True], ids=["copied", "borrowed"])
 @pytest.mark.parametrize("dtype,D", [("bf16", 64), ("f32", 64), ("bf16", 128), ("f32", 128)])
-def test_interscale_similarity(dtype, D):
+def test_interscale_similarity(dtype, D, borrow):
     sides_h = (1, 2, 3, 5, 6, 8, 13, 16)
     sides_w = (1, 2, 4, 5, 6, 9, 13, 16)
     B, H = 3, 5
     pols = [(0, 0, True), (2, 1, False)]
-    r = Runner(sides_h, sides_w, B, H, D, dtype, pols)
+    r = Runner(sides_h, sides_w, B, H, D, dtype, pols, borrow=borrow)
     tokens = r.tokens
     try:
         for layer, rho in enumerate((0.9, 0.4)):

@@ -77,6 +77,53 @@ def test_planned_layout_is_overlap_free_fixed_and_tight(sides):
         amskv.amskv_cache_destroy(h)
 
 
+@pytest.mark.parametrize("layout", [amskv.AMSKV_LAYOUT_COMPACT, amskv.AMSKV_LAYOUT_PLANNED])
+def test_borrow_unretained_layout(layout):
+    sides = VAR
+    tokens = [s * s for s in sides]
+    n = len(sides)
+    pols = [(c, w, False) for c, w in itertools.product(range(4), range(4))] + [(0, 0, True)]
+    B, H, D = 2, 3, 64
+    h = amskv.amskv_cache_create(len(pols), H, D, sides, sides, B, amskv.AMSKV_DTYPE_BF16, pols, 0.0, layout,
+                                 borrow_unretained=True)
+    try:
+        for l, pol in enumerate(pols):
+            assert amskv.amskv_cache_capacity_tokens(h, l) == orc.stored_capacity(tokens, pol)
+        slot = [dict() for _ in pols]
+        for s in range(n):
+            for l, pol in enumerate(pols):
+                amskv.amskv_append_scale(h, l, s)
+                lay = amskv.amskv_cache_layout(h, l)
+                stored = orc.stored_scales(pol, s, n)
+                assert [k for k, _, _ in lay] == orc.kept_scales(pol, s)
+                assert [k for k, o, _ in lay if o >= 0] == stored
+                assert [k for k, o, _ in lay if o < 0] == [k for k in orc.kept_scales(pol, s) if k not in stored]
+                spans = sorted((o, o + ln) for _, o, ln in lay if o >= 0)
+                for (a0, a1), (b0, b1) in zip(spans, spans[1:]):
+                    assert a1 <= b0
+                if spans:
+                    assert spans[-1][1] <= amskv.amskv_cache_capacity_tokens(h, l)
+                if layout == amskv.AMSKV_LAYOUT_COMPACT:
+                    acc = 0
+                    for k, o, ln in lay:
+                        if o >= 0:
+                            assert o == acc
+                            acc += ln
+                else:
+                    for k, o, ln in lay:
+                        if o >= 0:
+                            assert slot[l].setdefault(k, o) == o
+                assert amskv.amskv_cache_last_evicted(h, l) == orc.evicted_scales(pol, s)
+                assert amskv.amskv_cache_bytes_held(h, l, True) == orc.bytes_held(tokens, pol, s, B, H, D, 2, True)
+                assert amskv.amskv_cache_bytes_held(h, l, False) == orc.bytes_held(tokens, pol, s, B, H, D, 2, False)
+    finally:
+        amskv.amskv_cache_destroy(h)
+    # the arena shrinks: {0,1}+window 2 needs 338 tokens per (b,h) instead of 530
+    need_b = amskv.amskv_cache_required_bytes(1, H, D, sides, sides, B, 1, [(2, 2, False)], borrow_unretained=True)
+    need = amskv.amskv_cache_required_bytes(1, H, D, sides, sides, B, 1, [(2, 2, False)])
+    assert need - need_b >= 2 * B * H * (530 - 338) * D * 2 - 1024
+
+
 def test_required_bytes_closed_form():
     B, H, D = 4, 5, 64
     pols = [(2, 2, False), (0, 0, True)]

@@ -15,9 +15,9 @@ GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 VAR_T = [s * s for s in (1, 2, 3, 4, 5, 6, 8, 10, 13, 16)]
 
 
-def _golden_rows():
+def _golden_rows(name="kept_tokens.txt"):
     rows = []
-    with open(os.path.join(GOLDEN, "kept_tokens.txt")) as f:
+    with open(os.path.join(GOLDEN, name)) as f:
         for line in f:
             line = line.strip()
             if not line or line.startswith("#"):
@@ -45,6 +45,27 @@ def test_kept_token_counts_golden(row):
     got = [orc.kept_token_count(t, (c, w, ka), s) for s in range(len(t))]
     assert got == counts
     assert orc.cache_capacity(t, (c, w, ka)) == max(counts)
+
+
+@pytest.mark.parametrize("row", _golden_rows("stored_tokens.txt"), ids=lambda r: r[0])
+def test_stored_token_counts_golden(row):
+    _, sides, c, w, ka, counts = row
+    t = orc.scale_tokens(sides, sides)
+    got = [sum(t[k] for k in orc.stored_scales((c, w, ka), s, len(t))) for s in range(len(t))]
+    assert got == counts
+    assert orc.stored_capacity(t, (c, w, ka)) == max(counts)
+
+
+def test_stored_scales_by_set_enumeration():
+    n = 5
+    for c, w in itertools.product(range(4), range(4)):
+        for s in range(n):
+            kept = {k for k in (set(range(c)) | set(range(s - w, s)) | {s}) if 0 <= k <= s}
+            # the current scale is written only if it is condensed or the window reaches it next step
+            want = kept - ({s} if (s == n - 1 or not (s < c or w >= 1)) else set())
+            assert orc.stored_scales((c, w, False), s, n) == sorted(want)
+        for s in range(n):
+            assert orc.stored_scales((c, w, True), s, n) == [k for k in range(s + 1) if k < n - 1]
 
 
 @pytest.mark.parametrize("n_scales", [3, 5])
