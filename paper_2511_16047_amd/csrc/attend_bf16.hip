@@ -198,19 +198,18 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
   // lane-constant pieces of the fragment addresses
   const int tr_key = 4 * h + ((lane & 15) >> 2);               // + K-step base (+8 for the second read)
   const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);  // + 32*db
-  int v_off[2][DB][2];  // V^T fragment byte offsets inside a 32-key block: [K-step][d block][first/second read]
+  // V^T fragment of K-step u, read x: key = 16u + 8x + tr_key.  (key & 7) == (tr_key & 7), so the swizzle
+  // term does not depend on u or x and those two enter the address as compile-time offsets.
+  int v_base[DB];
 #pragma unroll
-  for (int u = 0; u < 2; ++u)
-#pragma unroll
-    for (int d = 0; d < DB; ++d)
-#pragma unroll
-      for (int x = 0; x < 2; ++x) {
-        const int key = 16 * u + 8 * x + tr_key, col = 32 * d + tr_col;
-        v_off[u][d][x] = key * RB + 16 * ((col >> 3) ^ (key & 7)) + 2 * (col & 7);
-      }
+  for (int d = 0; d < DB; ++d) {
+    const int col = 32 * d + tr_col;
+    v_base[d] = tr_key * RB + 16 * ((col >> 3) ^ (tr_key & 7)) + 2 * (col & 7);
+  }
   int k_off[KS];  // K fragment byte offsets inside a 32-key block
 #pragma unroll
   for (int t = 0; t < KS; ++t) k_off[t] = r * RB + 16 * ((2 * t + h) ^ (r & 7));
+  const int xchg_addr = (lane ^ 32) << 2;  // ds_bpermute source of the other lane half
 
   // V rows of the previous block (first iteration: the block itself, multiplied by pf = 0)
   const char* v_prev = lds_v;
@@ -219,7 +218,10 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
 #pragma unroll
   for (int n = 0; n < NQ; ++n) alpha[n] = 1.f;
 
-  for (int g = 0; g < n_blocks; ++g) {
+  // One 32-key block: S^T of block g, its softmax, and O^T += V^T P^T of block g-1 (probabilities p_in,
+  // packed one step earlier); the new probabilities go to p_out.  The loop below alternates two register
+  // sets for p so that no copies are needed.
+  auto block_step = [&](int g, const bf16x8 (&p_in)[NQ][2], bf16x8 (&p_out)[NQ][2]) {
     const int it = g / kBlocksPerTile;
     const int sub = g % kBlocksPerTile;
     if (sub == 0) {
@@ -239,8 +241,8 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
                       wave, lane);
       }
     }
-    if (!wave_active) continue;
-    // ---- (rarely) move the accumulators to the running max chosen in the previous iteration;
+    if (!wave_active) return;
+    // ---- (rarely) move the accumulators to the running max chosen in the previous step;
     // placed here so that the softmax and the matrix products below stay one basic block
     if (any_rescale) {
 #pragma unroll
@@ -285,8 +287,9 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
       float mx = max3(sacc[n][0], sacc[n][1], sacc[n][2]);
 #pragma unroll
       for (int v = 3; v < 15; v += 2) mx = max3(mx, sacc[n][v], sacc[n][v + 1]);
-      const float other = __shfl_xor(max3(mx, sacc[n][15], sacc[n][15]), 32, 64);
-      mx = max3(mx, sacc[n][15], other);
+      const float mine = max3(mx, sacc[n][15], sacc[n][15]);
+      const float other = __int_as_float(__builtin_amdgcn_ds_bpermute(xchg_addr, __float_as_int(mine)));
+      mx = max3(mine, other, other);
       // lazy rescale: keep the old reference while the block's max exceeds it by < 2^kMaxLag
       const bool lag = (mx - run_max[n]) * scale_log2e > kMaxLag;
       const float new_max = lag ? mx : run_max[n];
@@ -297,7 +300,6 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
 
     // ---- one basic block: probabilities of this block (vector ALU) next to O^T += V^T P^T of the
     // previous block (matrix cores); the two share no data
-    bf16x8 pnew[NQ][2];
 #pragma unroll
     for (int n = 0; n < NQ; ++n) {
       // p = 2^(s*c - m*c), rounded to bf16 in pairs; the row sum is taken over the ROUNDED values
@@ -311,29 +313,40 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
         pk[0] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[n][v], scale_log2e, -mc));
         pk[1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[n][v + 1], scale_log2e, -mc));
         sum = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, sum, false);
-        pnew[n][v >> 3][v & 7] = pk[0];
-        pnew[n][v >> 3][(v & 7) + 1] = pk[1];
+        p_out[n][v >> 3][v & 7] = pk[0];
+        p_out[n][v >> 3][(v & 7) + 1] = pk[1];
       }
       run_sum[n] = sum;
     }
 #pragma unroll
-    for (int u = 0; u < 2; ++u)
+    for (int d = 0; d < DB; ++d) {
+      const char* vp = v_prev + v_base[d];
 #pragma unroll
-      for (int d = 0; d < DB; ++d) {
-        const bf16x4 lo = lds_read_tr16(v_prev + v_off[u][d][0]);
-        const bf16x4 hi = lds_read_tr16(v_prev + v_off[u][d][1]);
+      for (int u = 0; u < 2; ++u) {
+        const bf16x4 lo = lds_read_tr16(vp + (16 * u) * RB);
+        const bf16x4 hi = lds_read_tr16(vp + (16 * u + 8) * RB);
         bf16x8 a;
         a[0] = lo[0]; a[1] = lo[1]; a[2] = lo[2]; a[3] = lo[3];
         a[4] = hi[0]; a[5] = hi[1]; a[6] = hi[2]; a[7] = hi[3];
 #pragma unroll
-        for (int n = 0; n < NQ; ++n) oacc[n][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[n][u], oacc[n][d], 0, 0, 0);
+        for (int n = 0; n < NQ; ++n) oacc[n][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p_in[n][u], oacc[n][d], 0, 0, 0);
       }
+    }
+    v_prev = tv;
+  };
 
+  bf16x8 pf2[NQ][2];  // second register set for the probabilities
+  int g = 0;
+  for (; g + 1 < n_blocks; g += 2) {
+    block_step(g, pf, pf2);
+    block_step(g + 1, pf2, pf);
+  }
+  if (g < n_blocks) {  // odd block count: finish through the second set, then bring it back
+    block_step(g, pf, pf2);
 #pragma unroll
     for (int n = 0; n < NQ; ++n)
 #pragma unroll
-      for (int u = 0; u < 2; ++u) pf[n][u] = pnew[n][u];
-    v_prev = tv;
+      for (int u = 0; u < 2; ++u) pf[n][u] = pf2[n][u];
   }
 
   if (!wave_active) return;
@@ -347,17 +360,19 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
   }
   // ---- drain: the last block's O^T += V^T P^T
 #pragma unroll
-  for (int u = 0; u < 2; ++u)
+  for (int d = 0; d < DB; ++d) {
+    const char* vp = v_prev + v_base[d];
 #pragma unroll
-    for (int d = 0; d < DB; ++d) {
-      const bf16x4 lo = lds_read_tr16(v_prev + v_off[u][d][0]);
-      const bf16x4 hi = lds_read_tr16(v_prev + v_off[u][d][1]);
+    for (int u = 0; u < 2; ++u) {
+      const bf16x4 lo = lds_read_tr16(vp + (16 * u) * RB);
+      const bf16x4 hi = lds_read_tr16(vp + (16 * u + 8) * RB);
       bf16x8 a;
       a[0] = lo[0]; a[1] = lo[1]; a[2] = lo[2]; a[3] = lo[3];
       a[4] = hi[0]; a[5] = hi[1]; a[6] = hi[2]; a[7] = hi[3];
 #pragma unroll
       for (int n = 0; n < NQ; ++n) oacc[n][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[n][u], oacc[n][d], 0, 0, 0);
     }
+  }
 
   // ---- O[row][d] = O^T[d][row] / l ; lane (r,h) holds d = 32*db + 8*(v/4) + 4h + v%4 of row r
 #pragma unroll
