@@ -58,6 +58,9 @@ def main():
     ap.add_argument("--no-borrow", action="store_true",
                     help="copy every appended scale into the arena, also the ones no later step reads "
                          "(default: borrow_unretained=1, the final scale is attended in place as in Algorithm 1)")
+    ap.add_argument("--no-fuse", action="store_true",
+                    help="copy retained scales in amskv_append_scale (default: fuse_append=1, the attend call of the "
+                         "step fills the scale's slot while it streams the scale)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-scale", action="store_true", help="print a per-scale timing table to stderr")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -98,6 +101,7 @@ def main():
     eb = 2
     layout = amskv.AMSKV_LAYOUT_PLANNED if args.layout == "planned" else amskv.AMSKV_LAYOUT_COMPACT
     borrow = not args.no_borrow
+    fuse = not args.no_fuse
 
     # ---------------- synthetic inputs, resident in HBM
     t0 = time.time()
@@ -140,10 +144,10 @@ def main():
     else:
         pols = base_pol
 
-    need = amskv.amskv_cache_required_bytes(L, H, D, w.sides, w.sides, B, 1, pols, 0.0, layout, borrow)
+    need = amskv.amskv_cache_required_bytes(L, H, D, w.sides, w.sides, B, 1, pols, 0.0, layout, borrow, fuse)
     arena = torch.empty(need, dtype=torch.uint8, device=dev)
     cache = amskv.amskv_cache_create(L, H, D, w.sides, w.sides, B, 1, pols, 0.0, layout, arena=arena,
-                                     borrow_unretained=borrow)
+                                     borrow_unretained=borrow, fuse_append=fuse)
     probe_layers = list(range(L))
     probe = PROBE_SCALE if S > PROBE_SCALE else S - 1
 
@@ -207,7 +211,11 @@ def main():
         copied = tokens[s]
         if borrow and (s == S - 1 or not (pols[l][2] or s < pols[l][0] or pols[l][1] >= 1)):
             copied = 0                # no later step reads this scale: attended in place, never copied
-        aby = 2 * (2 * moved + 2 * copied) * D * eb * B * H
+        if fuse and copied:           # the attend launch streams the scale once and writes its slot
+            by += 2 * copied * D * eb * B * H
+            aby = 2 * (2 * moved) * D * eb * B * H
+        else:
+            aby = 2 * (2 * moved + 2 * copied) * D * eb * B * H
         att_t += tt; app_t += ta; att_bytes += by; app_bytes += aby
         per_scale[s][0] += ta; per_scale[s][1] += tt; per_scale[s][2] += fl; per_scale[s][3] += by
         if tokens[s] > dom_rows:
@@ -241,7 +249,7 @@ def main():
         "value": flops / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": w.name, "mode": args.mode, "layout": args.layout, "borrow_unretained": int(borrow), "layers": L, "heads": H,
+        "config": {"workload": w.name, "mode": args.mode, "layout": args.layout, "borrow_unretained": int(borrow), "fuse_append": int(fuse), "layers": L, "heads": H,
                    "head_dim": D, "batch": B, "tokens": sum(tokens), "scales": S,
                    "cache_demanding_layers": sum(1 for p in pols if p[2]), "probe_scale": probe},
         "ms_per_image": ms_per_step / B,

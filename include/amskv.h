@@ -80,6 +80,7 @@ typedef struct {
   float softmax_scale;              /* 0 => 1/sqrt(head_dim)                              */
   int32_t layout;                   /* AMSKV_LAYOUT_COMPACT or AMSKV_LAYOUT_PLANNED       */
   int32_t borrow_unretained;        /* 0 / 1, see below                                   */
+  int32_t fuse_append;              /* 0 / 1, see below                                   */
 } amskv_policy;
 
 /* borrow_unretained.  Algorithm 1 stores a scale only if a later step will read it (a scale
@@ -91,7 +92,16 @@ typedef struct {
  * The caller must then keep K_dev/V_dev valid and unchanged until the next append or reset on
  * that layer (or the destroy).  Such a scale needs no arena space (capacities shrink
  * accordingly) and amskv_cache_layout reports it with tok_offset = -1.  With 0 (default) every
- * appended scale is copied and K_dev/V_dev may be reused as soon as the append has run. */
+ * appended scale is copied and K_dev/V_dev may be reused as soon as the append has run.
+ *
+ * fuse_append.  The attention of step s streams K_s and V_s anyway, so with fuse_append != 0
+ * amskv_append_scale does not copy a retained scale either: it reserves the scale's slot, and
+ * the amskv_attend call of that step reads the scale from K_dev/V_dev and writes it into the
+ * slot as it goes (one read of K_s/V_s instead of two, and no copy kernel).  If the next call
+ * on the layer is another append instead, that append performs the copy first.  Same promise
+ * as above: K_dev/V_dev stay valid and unchanged until the next append or reset on the layer;
+ * until the attend call they are the only copy, and similarity/export read them in place.
+ * Device work of one layer must be enqueued on one stream (or be ordered by the caller). */
 
 /* Bytes the arena must have for this configuration: for every layer the K and V regions
  * sized for the largest kept set the policy ever reaches (Section 4.3: capacity is fixed

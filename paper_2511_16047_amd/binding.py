@@ -50,7 +50,7 @@ class _LayerPolicy(C.Structure):
 
 class _Policy(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("layer", C.POINTER(_LayerPolicy)), ("softmax_scale", C.c_float),
-                ("layout", C.c_int32), ("borrow_unretained", C.c_int32)]
+                ("layout", C.c_int32), ("borrow_unretained", C.c_int32), ("fuse_append", C.c_int32)]
 
 
 _lib = None
@@ -109,13 +109,13 @@ def _check(status: int, where: str):
         raise AmskvError(int(status), where)
 
 
-def _structs(sides_h, sides_w, batch, dtype, policies, softmax_scale, layout, borrow_unretained=False):
+def _structs(sides_h, sides_w, batch, dtype, policies, softmax_scale, layout, borrow_unretained=False, fuse_append=False):
     n = len(sides_h)
     ah = (C.c_int32 * n)(*[int(x) for x in sides_h])
     aw = (C.c_int32 * n)(*[int(x) for x in sides_w])
     sc = _Schedule(n, ah, aw, int(batch), int(dtype))
     lp = (_LayerPolicy * len(policies))(*[_LayerPolicy(int(c), int(w), int(bool(k))) for c, w, k in policies])
-    po = _Policy(len(policies), lp, float(softmax_scale), int(layout), int(bool(borrow_unretained)))
+    po = _Policy(len(policies), lp, float(softmax_scale), int(layout), int(bool(borrow_unretained)), int(bool(fuse_append)))
     return sc, po, (ah, aw, lp)
 
 
@@ -134,8 +134,8 @@ def _stream(stream) -> Optional[int]:
 
 # ------------------------------------------------------------------ the calls of amskv.h
 def amskv_cache_required_bytes(layers, heads, head_dim, sides_h, sides_w, batch, dtype, policies,
-                               softmax_scale=0.0, layout=AMSKV_LAYOUT_COMPACT, borrow_unretained=False) -> int:
-    sc, po, _keep = _structs(sides_h, sides_w, batch, dtype, policies, softmax_scale, layout, borrow_unretained)
+                               softmax_scale=0.0, layout=AMSKV_LAYOUT_COMPACT, borrow_unretained=False, fuse_append=False) -> int:
+    sc, po, _keep = _structs(sides_h, sides_w, batch, dtype, policies, softmax_scale, layout, borrow_unretained, fuse_append)
     out = C.c_uint64(0)
     _check(load_library().amskv_cache_required_bytes(layers, heads, head_dim, C.byref(sc), C.byref(po),
                                                      C.byref(out)), "amskv_cache_required_bytes")
@@ -144,10 +144,10 @@ def amskv_cache_required_bytes(layers, heads, head_dim, sides_h, sides_w, batch,
 
 def amskv_cache_create(layers, heads, head_dim, sides_h, sides_w, batch, dtype, policies,
                        softmax_scale=0.0, layout=AMSKV_LAYOUT_COMPACT, arena=None, arena_bytes=None,
-                       borrow_unretained=False):
+                       borrow_unretained=False, fuse_append=False):
     """arena: torch uint8 device tensor (kept alive by the caller) or None for a plan-only cache.
     Returns the opaque handle (an int)."""
-    sc, po, _keep = _structs(sides_h, sides_w, batch, dtype, policies, softmax_scale, layout, borrow_unretained)
+    sc, po, _keep = _structs(sides_h, sides_w, batch, dtype, policies, softmax_scale, layout, borrow_unretained, fuse_append)
     h = C.c_void_p(None)
     nbytes = 0 if arena is None else (int(arena.numel() * arena.element_size()) if arena_bytes is None else int(arena_bytes))
     _check(load_library().amskv_cache_create(layers, heads, head_dim, C.byref(sc), C.byref(po), _ptr(arena),

@@ -20,8 +20,9 @@ struct Segment {
   int32_t scale;
   int32_t off;  // token offset inside the layer's [cap] axis; -1: borrowed (read in place)
   int32_t len;
-  const void* ext_k = nullptr;  // borrowed scale: the caller's K/V of that scale
+  const void* ext_k = nullptr;  // the caller's K/V of that scale while it is read in place
   const void* ext_v = nullptr;
+  bool pending = false;         // fuse_append: slot reserved at `off`, data still only in ext_k/ext_v
 };
 
 struct LayerState {
@@ -38,7 +39,7 @@ struct LayerState {
 }  // namespace
 
 struct amskv_cache {
-  int32_t layers, heads, head_dim, batch, dtype, n_scales, layout, borrow;
+  int32_t layers, heads, head_dim, batch, dtype, n_scales, layout, borrow, fuse;
   int32_t side_h[AMSKV_MAX_SCALES], side_w[AMSKV_MAX_SCALES], tokens[AMSKV_MAX_SCALES];
   float softmax_scale;
   int32_t elem_bytes;
@@ -94,6 +95,7 @@ int validate(int32_t layers, int32_t heads, int32_t head_dim, const amskv_schedu
   if (po->layout != AMSKV_LAYOUT_COMPACT && po->layout != AMSKV_LAYOUT_PLANNED)
     return AMSKV_ERR_INVALID_ARG;
   if (po->borrow_unretained != 0 && po->borrow_unretained != 1) return AMSKV_ERR_INVALID_ARG;
+  if (po->fuse_append != 0 && po->fuse_append != 1) return AMSKV_ERR_INVALID_ARG;
   if (!(po->softmax_scale >= 0.f) || !std::isfinite(po->softmax_scale)) return AMSKV_ERR_INVALID_ARG;
   for (int l = 0; l < layers; ++l)
     if (po->layer[l].n_condensed < 0 || po->layer[l].window < 0) return AMSKV_ERR_INVALID_ARG;
@@ -195,6 +197,7 @@ SegTable seg_table(const LayerState& L, ExtKV* ext) {
   SegTable t;
   std::memset(&t, 0, sizeof(t));
   ext->k = ext->v = nullptr;
+  ext->wb_off = -1;
   t.n = (int32_t)L.segs.size();
   int32_t v = 0;
   int32_t ext_start = -1;
@@ -202,7 +205,7 @@ SegTable seg_table(const LayerState& L, ExtKV* ext) {
     t.virt_start[i] = v;
     t.phys_off[i] = L.segs[i].off < 0 ? 0 : L.segs[i].off;
     t.len[i] = L.segs[i].len;
-    if (L.segs[i].off < 0) {
+    if (L.segs[i].off < 0 || L.segs[i].pending) {
       ext_start = v;
       ext->k = L.segs[i].ext_k;
       ext->v = L.segs[i].ext_v;
@@ -266,6 +269,7 @@ int32_t amskv_cache_create(int32_t layers, int32_t heads, int32_t head_dim,
   c->n_scales = sc->n_scales;
   c->layout = po->layout;
   c->borrow = po->borrow_unretained;
+  c->fuse = po->fuse_append;
   c->elem_bytes = sc->dtype == AMSKV_DTYPE_BF16 ? 2 : 4;
   c->softmax_scale = po->softmax_scale > 0.f ? po->softmax_scale : 1.0f / std::sqrt((float)head_dim);
   for (int i = 0; i < sc->n_scales; ++i) {
@@ -296,6 +300,22 @@ int32_t amskv_append_scale(amskv_cache* c, int32_t layer, int32_t s, const void*
   LayerState& L = c->layer[layer];
   if (s != L.last_scale + 1) return AMSKV_ERR_ORDER;
   if (K_dev && !c->arena) return AMSKV_ERR_NO_DEVICE_MEMORY;
+
+  const int bh = c->batch * c->heads;
+  const int row_bytes = c->head_dim * c->elem_bytes;
+  // fuse_append: a scale whose attend never came still lives only in the caller's buffers; copy it now
+  for (Segment& g : L.segs) {
+    if (!g.pending) continue;
+    if (g.ext_k) {
+      MoveList none;
+      std::memset(&none, 0, sizeof(none));
+      hipError_t e = amskv::launch_append(c->arena + L.k_off, c->arena + L.v_off, g.ext_k, g.ext_v, bh, row_bytes,
+                                          L.cap, none, g.len, g.off, (hipStream_t)stream);
+      if (e != hipSuccess) return AMSKV_ERR_HIP;
+    }
+    g.pending = false;
+    g.ext_k = g.ext_v = nullptr;
+  }
 
   // new resident list (ascending scale id) and where each segment goes; a borrowed segment of
   // the previous step is by construction not resident any more and simply drops out
@@ -334,13 +354,19 @@ int32_t amskv_append_scale(amskv_cache* c, int32_t layer, int32_t s, const void*
     cur.ext_k = K_dev;
     cur.ext_v = V_dev;
   }
+  const bool defer = keep_copy && c->fuse != 0;  // the attend call of this step writes the slot
+  if (defer) {
+    cur.pending = true;
+    cur.ext_k = K_dev;
+    cur.ext_v = V_dev;
+  }
   next.push_back(cur);
 
-  if (K_dev && (keep_copy || mv.n > 0)) {
-    const int bh = c->batch * c->heads;
-    hipError_t e = amskv::launch_append(c->arena + L.k_off, c->arena + L.v_off, keep_copy ? K_dev : nullptr,
-                                        keep_copy ? V_dev : nullptr, bh, c->head_dim * c->elem_bytes, L.cap,
-                                        mv, cur.len, keep_copy ? cur.off : 0, (hipStream_t)stream);
+  const bool copy_now = keep_copy && !defer;
+  if (K_dev && (copy_now || mv.n > 0)) {
+    hipError_t e = amskv::launch_append(c->arena + L.k_off, c->arena + L.v_off, copy_now ? K_dev : nullptr,
+                                        copy_now ? V_dev : nullptr, bh, row_bytes, L.cap, mv, cur.len,
+                                        copy_now ? cur.off : 0, (hipStream_t)stream);
     if (e != hipSuccess) return AMSKV_ERR_HIP;
   }
   L.segs.swap(next);
@@ -359,6 +385,8 @@ int32_t amskv_attend(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev
   ExtKV ext;
   const SegTable t = seg_table(L, &ext);
   if (t.ext_start < t.total && !ext.k) return AMSKV_ERR_NO_DEVICE_MEMORY;  // borrowed scale appended without data
+  Segment& newest = L.segs.back();
+  if (newest.pending) ext.wb_off = newest.off;  // fused append: this launch also fills the slot
   const int bh = c->batch * c->heads;
   hipError_t e;
   if (c->dtype == AMSKV_DTYPE_BF16)
@@ -369,7 +397,12 @@ int32_t amskv_attend(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev
     e = amskv::launch_attend_f32(Q_dev, O_dev, c->arena + L.k_off, c->arena + L.v_off, bh,
                                  c->tokens[s], c->head_dim, L.cap, t, ext, c->softmax_scale,
                                  (hipStream_t)stream);
-  return e == hipSuccess ? AMSKV_OK : AMSKV_ERR_HIP;
+  if (e != hipSuccess) return AMSKV_ERR_HIP;
+  if (newest.pending) {  // from here on (in stream order) the slot holds the scale
+    newest.pending = false;
+    newest.ext_k = newest.ext_v = nullptr;
+  }
+  return AMSKV_OK;
 }
 
 int32_t amskv_interscale_similarity(amskv_cache* c, int32_t layer, int32_t s, float* cosK_host,
@@ -385,14 +418,15 @@ int32_t amskv_interscale_similarity(amskv_cache* c, int32_t layer, int32_t s, fl
   }
   if (!cur || !prev) return AMSKV_ERR_EVICTED;
   if (!c->arena) return AMSKV_ERR_NO_DEVICE_MEMORY;
-  if ((cur->off < 0 && !cur->ext_k) || (prev->off < 0 && !prev->ext_k)) return AMSKV_ERR_NO_DEVICE_MEMORY;
+  if (((cur->off < 0 || cur->pending) && !cur->ext_k) || ((prev->off < 0 || prev->pending) && !prev->ext_k))
+    return AMSKV_ERR_NO_DEVICE_MEMORY;
   const uint64_t bh = (uint64_t)c->batch * c->heads;
   float* partial = (float*)(c->arena + c->ws_off);
   float* totals = partial + 2 * bh * 4;
   hipStream_t st = (hipStream_t)stream;
   auto ref = [&](const Segment* g) {
     ScaleRef r;
-    if (g->off < 0) {
+    if (g->off < 0 || g->pending) {
       r.k = g->ext_k;
       r.v = cosV_host ? g->ext_v : nullptr;
       r.stride_tokens = g->len;

@@ -24,9 +24,12 @@ struct SegTable {
 };
 
 // External (borrowed) K and V of the current scale: [BH][ext_len][row], or null pointers.
+// wb_off >= 0 asks the attention kernel to also write the scale it streams from k/v into the
+// layer's K/V regions at that token offset (the append fused into the attention of its step).
 struct ExtKV {
   const void* k;
   const void* v;
+  int32_t wb_off;
 };
 
 // Token ranges that slide toward lower offsets when scales are evicted (COMPACT layout),
@@ -54,13 +57,14 @@ __device__ __forceinline__ int locate_row(const SegTable& seg, int j, bool& ext)
 #endif
 
 // ---- kernel launchers (each validates nothing: the host layer has checked shapes) ----
-hipError_t launch_attend_bf16(const void* q, void* o, const void* kc, const void* vc, int bh,
+// kc/vc are written only when ext.wb_off >= 0 (fused append)
+hipError_t launch_attend_bf16(const void* q, void* o, void* kc, void* vc, int bh,
                               int t_q, int head_dim, int64_t cap_tokens, const SegTable& seg,
                               const ExtKV& ext, float softmax_scale, hipStream_t st);
-hipError_t launch_attend_bf16_small(const void* q, void* o, const void* kc, const void* vc, int bh,
+hipError_t launch_attend_bf16_small(const void* q, void* o, void* kc, void* vc, int bh,
                                     int t_q, int head_dim, int64_t cap_tokens, const SegTable& seg,
                                     const ExtKV& ext, float softmax_scale, hipStream_t st);
-hipError_t launch_attend_f32(const void* q, void* o, const void* kc, const void* vc, int bh,
+hipError_t launch_attend_f32(const void* q, void* o, void* kc, void* vc, int bh,
                              int t_q, int head_dim, int64_t cap_tokens, const SegTable& seg,
                              const ExtKV& ext, float softmax_scale, hipStream_t st);
 // k_new == nullptr: compaction only (the new scale is borrowed, nothing to copy)

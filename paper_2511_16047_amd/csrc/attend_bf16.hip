@@ -118,11 +118,33 @@ struct TileLoader {
       lds_dma16((ext ? xv : vb) + off, lds_v + blk * 1024);
     }
   }
+
+  // Fused append: copy the rows of the landed tile that belong to the current (external) scale from
+  // LDS into the scale's slot of the cache.  Each wave stores exactly the 1 KB blocks it fetched, so
+  // lane i re-reads its own 16 bytes at block + 16*i and the swizzle of issue() is undone by using the
+  // same chunk mapping for the destination.  The stores are ordinary vector-memory operations issued
+  // before the next tile's loads; the tile waits of the caller stay valid because a vmcnt wait only
+  // counts operations (loads complete in order, and outstanding stores make the wait stricter, not laxer).
+  __device__ static __forceinline__ void write_back(char* kb, char* vb, const char* lds_k, const char* lds_v, int j0,
+                                                    int t_kv, const SegTable& seg, int wb_off, int wave, int lane) {
+#pragma unroll
+    for (int i = 0; i < kLoadsPerWave; ++i) {
+      const int blk = wave * kLoadsPerWave + i;
+      const int row = blk * kRowsPerLoad + lane / CPR;
+      const int cpos = lane % CPR;
+      const int j = j0 + row;
+      if (j >= seg.ext_start && j < t_kv) {
+        const long long dst = (long long)(wb_off + j - seg.ext_start) * RB + 16 * (cpos ^ (row & 7));
+        *reinterpret_cast<uint4*>(kb + dst) = *reinterpret_cast<const uint4*>(lds_k + blk * 1024 + 16 * lane);
+        *reinterpret_cast<uint4*>(vb + dst) = *reinterpret_cast<const uint4*>(lds_v + blk * 1024 + 16 * lane);
+      }
+    }
+  }
 };
 
 template <int D, int NQ, int kWaves, int kTileKeys, int kMinWavesPerSimd>
 __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_kernel(
-    const __bf16* __restrict__ q, __bf16* __restrict__ o, const char* __restrict__ kc, const char* __restrict__ vc,
+    const __bf16* __restrict__ q, __bf16* __restrict__ o, char* __restrict__ kc, char* __restrict__ vc,
     int t_q, long long cap_tokens, SegTable seg, ExtKV ext_kv, float scale_log2e, int n_bh, int n_qtiles) {
   using Loader = TileLoader<D, kWaves, kTileKeys>;
   constexpr int RB = D * 2;   // bytes per token row
@@ -153,12 +175,14 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
   const int t_kv = seg.total;
   const int n_tiles = (t_kv + kTileKeys - 1) / kTileKeys;
   const int n_blocks = (t_kv + 31) / 32;
-  const char* kb = kc + bh * cap_tokens * RB;
-  const char* vb = vc + bh * cap_tokens * RB;
+  char* kb = kc + bh * cap_tokens * RB;
+  char* vb = vc + bh * cap_tokens * RB;
   // the borrowed current scale, if any: [BH][T_s][D] in the caller's buffers
   const long long ext_rows = bh * (long long)(seg.total - seg.ext_start);
   const char* xk = (const char*)ext_kv.k + ext_rows * RB;
   const char* xv = (const char*)ext_kv.v + ext_rows * RB;
+  // fused append: the workgroup of the first query tile also fills the current scale's slot
+  const bool write_back = ext_kv.wb_off >= 0 && (within >> 3) == 0;
 
   // ---- prologue: the Q fragments, then two tiles; all of it stays in flight until the first
   // wait of the tile loop (loads complete in issue order, so that wait covers Q as well).
@@ -235,6 +259,9 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
 #pragma unroll
           for (int t = 0; t < KS; ++t) pin(qf[n][t]);
       }
+      if (write_back && (it + 1) * kTileKeys > seg.ext_start)
+        Loader::write_back(kb, vb, lds_k + (it % kStages) * kTileBytes, lds_v + (it % kStages) * kTileBytes,
+                           it * kTileKeys, t_kv, seg, ext_kv.wb_off, wave, lane);
       if (it + 2 < n_tiles) {
         const int slot = (it + 2) % kStages;
         Loader::issue(kb, vb, xk, xv, lds_k + slot * kTileBytes, lds_v + slot * kTileBytes, (it + 2) * kTileKeys, t_kv, seg,
@@ -396,20 +423,20 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
 }
 
 template <int D, int NQ, int kWaves, int kTileKeys, int kMinWavesPerSimd>
-hipError_t launch(const void* q, void* o, const void* kc, const void* vc, int bh, int t_q, int64_t cap_tokens,
+hipError_t launch(const void* q, void* o, void* kc, void* vc, int bh, int t_q, int64_t cap_tokens,
                   const SegTable& seg, const ExtKV& ext, float c, hipStream_t st) {
   constexpr int BM = kWaves * 32 * NQ;
   const int n_qtiles = (t_q + BM - 1) / BM;
   dim3 grid((unsigned)(((bh + 7) / 8) * 8 * n_qtiles)), block(64 * kWaves);
   hipLaunchKernelGGL((attend_bf16_kernel<D, NQ, kWaves, kTileKeys, kMinWavesPerSimd>), grid, block, 0, st,
-                     (const __bf16*)q, (__bf16*)o, (const char*)kc, (const char*)vc, t_q, (long long)cap_tokens, seg, ext, c,
+                     (const __bf16*)q, (__bf16*)o, (char*)kc, (char*)vc, t_q, (long long)cap_tokens, seg, ext, c,
                      bh, n_qtiles);
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_attend_bf16(const void* q, void* o, const void* kc, const void* vc, int bh, int t_q,
+hipError_t launch_attend_bf16(const void* q, void* o, void* kc, void* vc, int bh, int t_q,
                               int head_dim, int64_t cap_tokens, const SegTable& seg, const ExtKV& ext, float softmax_scale,
                               hipStream_t st) {
 #if defined(AMSKV_TUNE_ENV)

@@ -37,7 +37,7 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
 
 template <int D>
 __global__ __launch_bounds__(64 * kWavesPerGroup) void attend_bf16_small_kernel(
-    const __bf16* __restrict__ q, __bf16* __restrict__ o, const char* __restrict__ kc, const char* __restrict__ vc,
+    const __bf16* __restrict__ q, __bf16* __restrict__ o, char* __restrict__ kc, char* __restrict__ vc,
     int t_q, long long cap_tokens, SegTable seg, ExtKV ext_kv, float scale_log2e, int n_qblk, int n_units) {
   constexpr int RB = D * 2;
   constexpr int CPR = D / 8;
@@ -56,12 +56,13 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void attend_bf16_small_kernel(
   const int q_base = (unit % n_qblk) * 32;
   const int t_kv = seg.total;
   const int n_blocks = (t_kv + 31) / 32;
-  const char* kb = kc + bh * cap_tokens * RB;
-  const char* vb = vc + bh * cap_tokens * RB;
+  char* kb = kc + bh * cap_tokens * RB;
+  char* vb = vc + bh * cap_tokens * RB;
   const long long ext_rows = bh * (long long)(seg.total - seg.ext_start);  // borrowed current scale, if any
   const char* xk = (const char*)ext_kv.k + ext_rows * RB;
   const char* xv = (const char*)ext_kv.v + ext_rows * RB;
   char* my_v = lds_v[wave];
+  const bool write_back = ext_kv.wb_off >= 0 && q_base == 0;
 
   bf16x8 qf[KS];
   {
@@ -111,6 +112,21 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void attend_bf16_small_kernel(
     for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
 #pragma unroll
     for (int t = 0; t < KS; ++t) sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[t], sacc, 0, 0, 0);
+    if (write_back) {
+      // fused append: this unit also fills the current scale's slot from the registers it just used
+      const int j0 = 32 * g;
+      if (j0 + r >= seg.ext_start && j0 + r < t_kv) {
+        char* dst = kb + (long long)(ext_kv.wb_off + j0 + r - seg.ext_start) * RB + 16 * h;
+#pragma unroll
+        for (int t = 0; t < KS; ++t) *reinterpret_cast<bf16x8*>(dst + 32 * t) = kf[t];
+      }
+#pragma unroll
+      for (int k = 0; k < VCH; ++k) {
+        const int id = k * 64 + lane, row = id / CPR, c = id % CPR;
+        if (j0 + row >= seg.ext_start && j0 + row < t_kv)
+          *reinterpret_cast<uint4*>(vb + (long long)(ext_kv.wb_off + j0 + row - seg.ext_start) * RB + 16 * c) = vch[k];
+      }
+    }
     if (g + 1 < n_blocks) load_block(g + 1);  // in flight during the softmax and the second product
 
     if (g == n_blocks - 1 && (t_kv & 31) != 0) {
@@ -181,7 +197,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void attend_bf16_small_kernel(
 
 }  // namespace
 
-hipError_t launch_attend_bf16_small(const void* q, void* o, const void* kc, const void* vc, int bh, int t_q,
+hipError_t launch_attend_bf16_small(const void* q, void* o, void* kc, void* vc, int bh, int t_q,
                                     int head_dim, int64_t cap_tokens, const SegTable& seg, const ExtKV& ext,
                                     float softmax_scale,
                                     hipStream_t st) {
@@ -190,11 +206,11 @@ hipError_t launch_attend_bf16_small(const void* q, void* o, const void* kc, cons
   const long long n_units = (long long)bh * n_qblk;
   dim3 grid((unsigned)((n_units + kWavesPerGroup - 1) / kWavesPerGroup)), block(64 * kWavesPerGroup);
   if (head_dim == 64)
-    hipLaunchKernelGGL(attend_bf16_small_kernel<64>, grid, block, 0, st, (const __bf16*)q, (__bf16*)o, (const char*)kc,
-                       (const char*)vc, t_q, (long long)cap_tokens, seg, ext, c, n_qblk, (int)n_units);
+    hipLaunchKernelGGL(attend_bf16_small_kernel<64>, grid, block, 0, st, (const __bf16*)q, (__bf16*)o, (char*)kc,
+                       (char*)vc, t_q, (long long)cap_tokens, seg, ext, c, n_qblk, (int)n_units);
   else
-    hipLaunchKernelGGL(attend_bf16_small_kernel<128>, grid, block, 0, st, (const __bf16*)q, (__bf16*)o, (const char*)kc,
-                       (const char*)vc, t_q, (long long)cap_tokens, seg, ext, c, n_qblk, (int)n_units);
+    hipLaunchKernelGGL(attend_bf16_small_kernel<128>, grid, block, 0, st, (const __bf16*)q, (__bf16*)o, (char*)kc,
+                       (char*)vc, t_q, (long long)cap_tokens, seg, ext, c, n_qblk, (int)n_units);
   return hipGetLastError();
 }
 

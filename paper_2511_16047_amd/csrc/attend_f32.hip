@@ -15,8 +15,8 @@ constexpr int kTileKeys = 32;
 template <int D>
 __global__ __launch_bounds__(kThreads) void attend_f32_kernel(const float* __restrict__ q,
                                                               float* __restrict__ o,
-                                                              const float* __restrict__ kc,
-                                                              const float* __restrict__ vc, int t_q,
+                                                              float* __restrict__ kc,
+                                                              float* __restrict__ vc, int t_q,
                                                               long long cap_tokens, SegTable seg,
                                                               ExtKV ext_kv, float scale_log2e) {
   constexpr int M = D / 16;  // float4 pieces per lane
@@ -28,8 +28,8 @@ __global__ __launch_bounds__(kThreads) void attend_f32_kernel(const float* __res
   const long long bh = blockIdx.x;
   const int row = blockIdx.y * kRowsPerBlock + (tid >> 2);
   const bool row_ok = row < t_q;
-  const float* kb = kc + bh * cap_tokens * D;
-  const float* vb = vc + bh * cap_tokens * D;
+  float* kb = kc + bh * cap_tokens * D;
+  float* vb = vc + bh * cap_tokens * D;
   const long long ext_rows = bh * (long long)(seg.total - seg.ext_start);  // borrowed current scale, if any
   const float* xk = (const float*)ext_kv.k + ext_rows * D;
   const float* xv = (const float*)ext_kv.v + ext_rows * D;
@@ -56,6 +56,11 @@ __global__ __launch_bounds__(kThreads) void attend_f32_kernel(const float* __res
         const long long off = (long long)locate_row(seg, j, ext) * D + 4 * c;
         kk = *reinterpret_cast<const float4*>((ext ? xk : kb) + off);
         vv = *reinterpret_cast<const float4*>((ext ? xv : vb) + off);
+        if (ext && ext_kv.wb_off >= 0 && blockIdx.y == 0) {  // fused append: fill the scale's slot while streaming it
+          const long long dst = (long long)ext_kv.wb_off * D + off;
+          *reinterpret_cast<float4*>(kb + dst) = kk;
+          *reinterpret_cast<float4*>(vb + dst) = vv;
+        }
       }
       *reinterpret_cast<float4*>(lds_k + r * D + 4 * c) = kk;
       *reinterpret_cast<float4*>(lds_v + r * D + 4 * c) = vv;
@@ -114,17 +119,17 @@ __global__ __launch_bounds__(kThreads) void attend_f32_kernel(const float* __res
 
 }  // namespace
 
-hipError_t launch_attend_f32(const void* q, void* o, const void* kc, const void* vc, int bh, int t_q,
+hipError_t launch_attend_f32(const void* q, void* o, void* kc, void* vc, int bh, int t_q,
                              int head_dim, int64_t cap_tokens, const SegTable& seg, const ExtKV& ext,
                              float softmax_scale, hipStream_t st) {
   const float c = softmax_scale * 1.4426950408889634f;
   dim3 grid(bh, (t_q + kRowsPerBlock - 1) / kRowsPerBlock), block(kThreads);
   if (head_dim == 64)
-    hipLaunchKernelGGL(attend_f32_kernel<64>, grid, block, 0, st, (const float*)q, (float*)o, (const float*)kc,
-                       (const float*)vc, t_q, (long long)cap_tokens, seg, ext, c);
+    hipLaunchKernelGGL(attend_f32_kernel<64>, grid, block, 0, st, (const float*)q, (float*)o, (float*)kc,
+                       (float*)vc, t_q, (long long)cap_tokens, seg, ext, c);
   else
-    hipLaunchKernelGGL(attend_f32_kernel<128>, grid, block, 0, st, (const float*)q, (float*)o, (const float*)kc,
-                       (const float*)vc, t_q, (long long)cap_tokens, seg, ext, c);
+    hipLaunchKernelGGL(attend_f32_kernel<128>, grid, block, 0, st, (const float*)q, (float*)o, (float*)kc,
+                       (float*)vc, t_q, (long long)cap_tokens, seg, ext, c);
   return hipGetLastError();
 }
 

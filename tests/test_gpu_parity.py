@@ -33,18 +33,19 @@ class Runner:
     """Drives one cache through the ABI and checks every step against the oracle."""
 
     def __init__(self, sides_h, sides_w, B, H, D, dtype, policies, layout=amskv.AMSKV_LAYOUT_COMPACT,
-                 softmax_scale=0.0, borrow=False):
+                 softmax_scale=0.0, borrow=False, fuse=False):
         self.sh, self.sw = list(sides_h), list(sides_w)
         self.tokens = orc.scale_tokens(self.sh, self.sw)
         self.B, self.H, self.D, self.dtype = B, H, D, dtype
-        self.policies, self.layout, self.scale, self.borrow = policies, layout, softmax_scale, borrow
+        self.policies, self.layout, self.scale, self.borrow, self.fuse = policies, layout, softmax_scale, borrow, fuse
         self.eb = 2 if dtype == "bf16" else 4
         need = amskv.amskv_cache_required_bytes(len(policies), H, D, self.sh, self.sw, B, DT[dtype], policies,
-                                                softmax_scale, layout, borrow)
+                                                softmax_scale, layout, borrow, fuse)
         self.arena = torch.empty(need, dtype=torch.uint8, device="cuda")
         self.arena.fill_(0xFF)          # every stale or never-written element reads as NaN
         self.h = amskv.amskv_cache_create(len(policies), H, D, self.sh, self.sw, B, DT[dtype], policies,
-                                          softmax_scale, layout, arena=self.arena, borrow_unretained=borrow)
+                                          softmax_scale, layout, arena=self.arena, borrow_unretained=borrow,
+                                          fuse_append=fuse)
 
     def close(self):
         amskv.amskv_cache_destroy(self.h)
@@ -181,6 +182,55 @@ def test_borrowed_unretained_scales(dtype, layout):
         r.close()
 
 
+@pytest.mark.parametrize("dtype,D", [("bf16", 64), ("f32", 64), ("bf16", 128)])
+@pytest.mark.parametrize("layout", [amskv.AMSKV_LAYOUT_COMPACT, amskv.AMSKV_LAYOUT_PLANNED], ids=["compact", "planned"])
+@pytest.mark.parametrize("borrow", [False, True], ids=["copyall", "borrow"])
+def test_fused_append(dtype, D, layout, borrow):
+    """fuse_append: the attend call of a step fills the scale's slot; the cache must end up bit-identical."""
+    sides_h = (1, 2, 3, 5, 7, 8, 11, 13, 16, 9)
+    sides_w = (1, 3, 3, 4, 7, 8, 11, 13, 16, 9)
+    pols = [(2, 2, False), (0, 0, False), (2, 0, False), (0, 0, True), (1, 3, False)]
+    r = Runner(sides_h, sides_w, 2, 3, D, dtype, pols, layout=layout, borrow=borrow, fuse=True)
+    try:
+        for layer in range(len(pols)):
+            q, k, v = _qkv(sides_h, sides_w, 2, 3, D, dtype, 800 + layer)
+            r.run_layer(layer, q, k, v)
+    finally:
+        r.close()
+
+
+def test_fused_append_without_attend_is_flushed_by_the_next_append():
+    sides = (1, 2, 4, 6, 8, 12)
+    tokens = [s * s for s in sides]
+    pol = [(1, 2, False)]
+    B, H, D = 2, 2, 64
+    r = Runner(sides, sides, B, H, D, "bf16", pol, fuse=True)
+    try:
+        q, k, v = _qkv(sides, sides, B, H, D, "bf16", 900)
+        for s in range(len(sides)):
+            amskv.amskv_append_scale(r.h, 0, s, k[s], v[s])
+            if s % 2 == 0 or s == len(sides) - 1:   # other steps never attend: the next append must copy them
+                o = torch.empty_like(q[s])
+                amskv.amskv_attend(r.h, 0, s, q[s], o)
+            r.check_cache(0, s, k, v)            # export reads pending scales in place
+        # after the last append+attend every resident scale must be in the arena itself: clobber the sources
+        for s in range(len(sides)):
+            k[s].fill_(float("nan"))
+            v[s].fill_(float("nan"))
+        torch.cuda.synchronize()
+        q2, k2, v2 = _qkv(sides, sides, B, H, D, "bf16", 900)
+        kept = orc.kept_scales(pol[0], len(sides) - 1)
+        tk = sum(tokens[j] for j in kept)
+        ko = torch.empty(B, H, tk, D, dtype=torch.bfloat16, device="cuda")
+        vo = torch.empty_like(ko)
+        amskv.amskv_cache_export(r.h, 0, ko, vo)
+        torch.cuda.synchronize()
+        assert np.array_equal(_bits(ko), orc.cache_contents([_bits(x) for x in k2], pol[0], len(sides) - 1))
+        assert np.array_equal(_bits(vo), orc.cache_contents([_bits(x) for x in v2], pol[0], len(sides) - 1))
+    finally:
+        r.close()
+
+
 def test_sixteen_scales_single_scale_and_scale_override():
     sides = tuple(range(1, 17))
     r = Runner(sides, sides, 1, 2, 64, "bf16", [(2, 1, False)], softmax_scale=0.05)
@@ -279,8 +329,8 @@ def test_interscale_similarity(dtype, D, borrow):
 
 
 # ------------------------------------------------------------------ full-size launches, sampled units
-def _full_size_layers(w, layers, n_units, gen, policies_of):
-    r = Runner(w.sides, w.sides, w.batch, w.heads, w.head_dim, w.dtype, policies_of)
+def _full_size_layers(w, layers, n_units, gen, policies_of, **flags):
+    r = Runner(w.sides, w.sides, w.batch, w.heads, w.head_dim, w.dtype, policies_of, **flags)
     try:
         for li, layer in enumerate(layers):
             q, k, v = gen(layer)
@@ -317,6 +367,19 @@ def test_config3_full_batch_sampled_units():
         return inp.correlated_qkv(w.sides, w.batch, w.heads, w.head_dim, "bf16", inp.layer_seed(3, layer), rhos[layer], device="cuda")
 
     _full_size_layers(w, layers, 24, gen, pols)
+
+
+def test_config3_full_batch_bench_flags_sampled_units():
+    """The same launches with the flags the benchmark runs with (borrowed final scale, fused append)."""
+    w = inp.config3(batch=256)
+    rhos = inp.layer_rhos(w.layers, inp.layer_seed(3, 999))
+    layers = [1, 7]
+    pols = [(2, 2, False), (0, 0, True)]
+
+    def gen(layer):
+        return inp.correlated_qkv(w.sides, w.batch, w.heads, w.head_dim, "bf16", inp.layer_seed(3, layer), rhos[layer], device="cuda")
+
+    _full_size_layers(w, layers, 24, gen, pols, borrow=True, fuse=True)
 
 
 def test_config5_policy_sweep_sampled_units():
