@@ -120,10 +120,15 @@ def _structs(sides_h, sides_w, batch, dtype, policies, softmax_scale, layout, bo
 
 
 def _ptr(t) -> Optional[int]:
-    return None if t is None else int(t.data_ptr())
+    """Device address of a torch tensor (or a raw address passed through)."""
+    if t is None or isinstance(t, int):
+        return t
+    return int(t.data_ptr())
 
 
 def _stream(stream) -> Optional[int]:
+    if isinstance(stream, int):
+        return stream or None
     if stream is None:
         import torch
         if torch.cuda.is_available():
