@@ -72,14 +72,10 @@ __device__ __forceinline__ void lds_dma16(const char* g, char* lds_wave_base) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(m0v) : "memory", "m0");
 }
 
-// Asynchronous 16-byte global load into registers, also outside the compiler's bookkeeping so
-// that it does not drain the direct-to-LDS loads issued after it; the value may only be used
-// after a wait_vmcnt that covers it, followed by pin().
-__device__ __forceinline__ void global_load16_async(bf16x8& dst, const void* g) {
-  asm volatile("global_load_dwordx4 %0, %1, off" : "=&v"(dst) : "v"(g) : "memory");
-}
-// Zero-instruction fence for one register value: later uses cannot be scheduled above it.
-__device__ __forceinline__ void pin(bf16x8& x) { asm volatile("" : "+v"(x)); }
+// Compiler-visible use of a register value: the compiler places its own wait for the load that
+// produced it here (and not inside the tile loop, where it could not tell the first iteration
+// from the rest and would drain every outstanding load on each trip).
+__device__ __forceinline__ void settle(const bf16x8& x) { asm volatile("" ::"v"(x)); }
 
 // v_max3_f32 written out: the compiler's fmaxf first canonicalises every operand (one extra
 // v_max per element under IEEE rules), which alone costs more than the whole reduction
@@ -184,8 +180,8 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
   // fused append: the workgroup of the first query tile also fills the current scale's slot
   const bool write_back = ext_kv.wb_off >= 0 && (within >> 3) == 0;
 
-  // ---- prologue: the Q fragments, then two tiles; all of it stays in flight until the first
-  // wait of the tile loop (loads complete in issue order, so that wait covers Q as well).
+  // ---- prologue: the Q fragments (ordinary loads), then two tiles; everything is in flight
+  // together, and the Q values are settled once, before the tile loop.
   // Q fragments: B operand of S^T = K Q^T; lane (r,h) holds Q[row r][16t + 8h .. +8).  Query rows
   // past T_q re-read the last row; their results are never stored.
   bf16x8 qf[NQ][KS];
@@ -193,12 +189,17 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
   for (int n = 0; n < NQ; ++n) {
     const int row = min(q_base + 32 * n + r, t_q - 1);
 #pragma unroll
-    for (int t = 0; t < KS; ++t) global_load16_async(qf[n][t], q + (bh * t_q + row) * D + 16 * t + 8 * h);
+    for (int t = 0; t < KS; ++t) qf[n][t] = *reinterpret_cast<const bf16x8*>(q + (bh * t_q + row) * D + 16 * t + 8 * h);
   }
 #pragma unroll
   for (int st = 0; st < 2; ++st)
     if (st < n_tiles)
       Loader::issue(kb, vb, xk, xv, lds_k + st * kTileBytes, lds_v + st * kTileBytes, st * kTileKeys, t_kv, seg, wave, lane);
+
+#pragma unroll
+  for (int n = 0; n < NQ; ++n)
+#pragma unroll
+    for (int t = 0; t < KS; ++t) settle(qf[n][t]);
 
   f32x16 oacc[NQ][DB];
 #pragma unroll
@@ -253,12 +254,6 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
       if (it + 1 < n_tiles) wait_vmcnt<VM>();
       else wait_vmcnt<0>();
       __syncthreads();  // every wave's part of tile `it` has landed; every wave is done with tile it-2
-      if (g == 0) {
-#pragma unroll
-        for (int n = 0; n < NQ; ++n)
-#pragma unroll
-          for (int t = 0; t < KS; ++t) pin(qf[n][t]);
-      }
       if (write_back && (it + 1) * kTileKeys > seg.ext_start)
         Loader::write_back(kb, vb, lds_k + (it % kStages) * kTileBytes, lds_v + (it % kStages) * kTileBytes,
                            it * kTileKeys, t_kv, seg, ext_kv.wb_off, wave, lane);
