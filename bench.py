@@ -266,7 +266,7 @@ def main():
     amskv.amskv_cache_destroy(cache2)
     del arena2
 
-    dom_name = "attend_bf16_kernel<%d,%s>" % (D, "1,8,64,4" if D == 64 else "2,4,32,1")
+    dom_name = "attend_bf16_kernel<%d,%s>" % (D, "1,8,64,4" if D == 64 else "1,4,32,2")
     ai = dom_flops / dom_bytes
     hbm_bound = ai < PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
     if hbm_bound:
