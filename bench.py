@@ -3,8 +3,11 @@
 
 One "step" is one whole pass of the hot path over one image batch of synthetic input, already
 resident in HBM: for every scale s and every layer l, amskv_append_scale (policy -> kept set,
-evict + compact + append) then amskv_attend; at the probe scale, amskv_interscale_similarity for
-every layer; bytes-held accounting at the end.  Default workload: VAR-d30 shape (30 layers,
+eviction, slot assignment) then amskv_attend (which, with fuse_append, also writes the scale it
+streams into its cache slot); at the probe scale, amskv_interscale_similarity for every layer;
+bytes-held accounting at the end.  Defaults: PLANNED layout, borrow_unretained, fuse_append (the
+configuration with the least HBM traffic); --layout compact --no-borrow --no-fuse gives the plain
+evict + compact + copy path, whose kernels are also timed once per run ("standalone_append").  Default workload: VAR-d30 shape (30 layers,
 30 heads x 64, ten scales = 680 tokens), bf16, batch 256, cache-demanding layers chosen by the
 similarity call (mean cosine < 0.5 -> keep all scales), the rest {0,1} + window 2.
 
@@ -31,9 +34,9 @@ COS_THRESHOLD = 0.5
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (summaries under profiles/); None until measured for the workload.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/var_d30_b256_hbm_traffic.txt: (FETCH_SIZE*2.0000 + WRITE_SIZE*1.0000) KiB per launch, mean over
-    # the dominant kernel's launches of one step
-    ("attend_bf16_kernel<64,1,8,64,4>", "var_d30_bf16_b256", "amskv"): 1425818771,
+    # profiles/var_d30_b256_hbm_traffic.txt: (FETCH_SIZE*2.0000 + WRITE_SIZE*1.0000) KiB per launch, mean over the
+    # dominant kernel's launches of one step; key = (kernel, workload, mode, layout, borrow, fuse)
+    ("attend_bf16_kernel<64,1,8,64,4>", "var_d30_bf16_b256", "amskv", "planned", 1, 1): 1592007379,
 }
 
 
@@ -274,7 +277,7 @@ def main():
     else:
         roof = {"bound": "mfma", "achieved": dom_flops / dom_t / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((dom_name, w.name, args.mode))
+    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((dom_name, w.name, args.mode, args.layout, int(borrow), int(fuse)))
     roof.update({"kernel": dom_name, "launches": dom_n, "avg_launch_ms": dom_t / dom_n * 1e3,
                  "algorithmic_bytes_per_launch": dom_bytes / dom_n, "flops_per_launch": dom_flops / dom_n,
                  "arithmetic_intensity": ai, "tflops": dom_flops / dom_t / 1e12,
