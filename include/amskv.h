@@ -49,6 +49,7 @@ typedef enum {
 
 enum { AMSKV_DTYPE_F32 = 0, AMSKV_DTYPE_BF16 = 1 };
 enum { AMSKV_LAYOUT_COMPACT = 0, AMSKV_LAYOUT_PLANNED = 1 };
+enum { AMSKV_MODE_SCALE_WINDOW = 0, AMSKV_MODE_TOKEN_BUDGET = 1 };
 enum { AMSKV_MAX_SCALES = 16 };
 
 typedef struct amskv_cache amskv_cache; /* opaque, host memory, owned by the library */
@@ -74,13 +75,34 @@ typedef struct {
   int32_t keep_all;       /* 0 / 1 */
 } amskv_layer_policy;
 
+/* Per-layer budgets in tokens for AMSKV_MODE_TOKEN_BUDGET: Algorithm 1 and Algorithm 2 taken
+ * literally (Section 4.3).  The layer starts with the budget c_min; the first time the cache
+ * would exceed it, the layer is tested for being cache-demanding (Eq. 3 score below theta) and,
+ * if so, the budget becomes c_max for good.  A scale larger than c_max, or larger than the
+ * budget in force, is never cached.  Otherwise the cache keeps its first c_cds tokens and the
+ * most recent (budget - c_cds) tokens, so a scale may stay in part.
+ * The score compared with theta is the mean over heads of the mean per-token cosine between
+ * the keys of the new scale and the bilinearly upsampled keys of the scale before it (the
+ * cosine form of Eq. 3 that amskv_interscale_similarity returns as cosK).  It can be computed
+ * only while that earlier scale is cached whole; when it is not, the test counts as failed and
+ * the budget stays.  theta > 1 always expands and theta < -1 never does, both without device
+ * work (the cosine lies in [-1, 1]). */
+typedef struct {
+  int32_t c_min;          /* >= c_cds           */
+  int32_t c_max;          /* >= c_min, >= 1     */
+  int32_t c_cds;          /* >= 0               */
+  float theta;
+} amskv_layer_budget;
+
 typedef struct {
   int32_t n_layers;                 /* must equal `layers` of the create call            */
-  const amskv_layer_policy* layer;  /* host, [n_layers]                                   */
+  const amskv_layer_policy* layer;  /* host, [n_layers]; unused (may be NULL) in token-budget mode */
   float softmax_scale;              /* 0 => 1/sqrt(head_dim)                              */
   int32_t layout;                   /* AMSKV_LAYOUT_COMPACT or AMSKV_LAYOUT_PLANNED       */
   int32_t borrow_unretained;        /* 0 / 1, see below                                   */
   int32_t fuse_append;              /* 0 / 1, see below                                   */
+  int32_t mode;                     /* AMSKV_MODE_SCALE_WINDOW (0) or AMSKV_MODE_TOKEN_BUDGET */
+  const amskv_layer_budget* budget; /* host, [n_layers]; token-budget mode only           */
 } amskv_policy;
 
 /* borrow_unretained.  Algorithm 1 stores a scale only if a later step will read it (a scale
@@ -101,7 +123,18 @@ typedef struct {
  * on the layer is another append instead, that append performs the copy first.  Same promise
  * as above: K_dev/V_dev stay valid and unchanged until the next append or reset on the layer;
  * until the attend call they are the only copy, and similarity/export read them in place.
- * Device work of one layer must be enqueued on one stream (or be ordered by the caller). */
+ * Device work of one layer must be enqueued on one stream (or be ordered by the caller).
+ *
+ * mode = AMSKV_MODE_TOKEN_BUDGET.  The cache of a layer is a list of tokens, oldest first, kept
+ * back to back from offset 0 of the layer's regions (layout must be AMSKV_LAYOUT_COMPACT,
+ * borrow_unretained and fuse_append must be 0; the capacity of a layer is c_max tokens).
+ * Step s runs in this order: amskv_append_scale(s) only records K_dev/V_dev; amskv_attend(s)
+ * attends to the cache as the previous step left it plus scale s read in place, and then, in
+ * stream order behind the attention kernel, performs Algorithm 1's iteration for scale s
+ * (budget test, skip, Algorithm 2's trim, copy of what stays of scale s).  If amskv_attend(s)
+ * is not called, the next amskv_append_scale or amskv_cache_settle on the layer performs that
+ * iteration.  K_dev/V_dev of scale s must stay valid and unchanged until that work has run.
+ * The one iteration per layer that evaluates Eq. 3 waits for the stream. */
 
 /* Bytes the arena must have for this configuration: for every layer the K and V regions
  * sized for the largest kept set the policy ever reaches (Section 4.3: capacity is fixed
@@ -159,11 +192,31 @@ int32_t amskv_interscale_similarity(amskv_cache* cache, int32_t layer, int32_t s
 /* Resident segments of a layer, ascending scale id: n_seg entries written to each
  * caller array of at least AMSKV_MAX_SCALES elements.  tok_offset is the position of the
  * segment inside the [cap_l] token axis of the layer's K and V regions, or -1 for a scale
- * that is read in place from the caller's buffers (borrow_unretained).  Host only. */
+ * that is read in place from the caller's buffers (borrow_unretained).  In token-budget mode
+ * the arrays need AMSKV_MAX_SCALES + 2 elements (see amskv_cache_segments).  Host only. */
 int32_t amskv_cache_layout(const amskv_cache* cache, int32_t layer, int32_t* n_seg,
                            int32_t* scale_id, int64_t* tok_offset, int32_t* tok_len);
 
-/* Scales dropped by the most recent append to this layer (ascending), for inspection. */
+/* Token-granular view of the same list: segment i holds tokens [first_token[i],
+ * first_token[i]+tok_len[i]) of scale scale_id[i]; a scale may appear in two segments
+ * (Algorithm 2 can keep its head and its tail).  In scale-window mode first_token is 0 and the
+ * output equals amskv_cache_layout's.  Arrays hold up to AMSKV_MAX_SCALES + 2 entries.  Host only. */
+int32_t amskv_cache_segments(const amskv_cache* cache, int32_t layer, int32_t* n_seg,
+                             int32_t* scale_id, int32_t* first_token, int64_t* tok_offset,
+                             int32_t* tok_len);
+
+/* Token-budget mode: the budget in force on the layer (c_min, or c_max once expanded);
+ * scale-window mode: the layer's capacity in tokens.  Negative amskv_status on error.  Host only. */
+int64_t amskv_cache_budget_tokens(const amskv_cache* cache, int32_t layer);
+
+/* Finish whatever the layer still owes for its newest scale without running attention: in
+ * token-budget mode Algorithm 1's iteration for that scale, with fuse_append the deferred copy.
+ * A no-op when nothing is owed.  On a plan-only cache only the metadata advances. */
+int32_t amskv_cache_settle(amskv_cache* cache, int32_t layer, void* stream);
+
+/* Scales dropped by the most recent append to this layer (ascending), for inspection.  In
+ * token-budget mode: scales that lost cached tokens, wholly or in part, in the most recent
+ * iteration of Algorithm 1 on the layer. */
 int32_t amskv_cache_last_evicted(const amskv_cache* cache, int32_t layer, int32_t* n_evicted,
                                  int32_t* scale_id);
 

@@ -305,8 +305,9 @@ def alg1_cache_trace(tokens: Sequence[int], c_min: int, c_max: int, c_cds: int,
                      below_theta: Sequence[bool]) -> List[Tuple[List[int], int]]:
     """Algorithm 1 on token ids (token-granular, exactly as printed).
 
-    below_theta[i] says whether S(k_i, k^_{i-1}) < theta would hold at scale i.  Returns,
-    for every scale i, (global token ids cached after the iteration, budget in force).
+    below_theta[i] says whether S(k_i, k^_{i-1}) < theta would hold at scale i; a callable
+    (i, cached_ids_before) -> bool is asked only when the algorithm evaluates the test.
+    Returns, for every scale i, (global token ids cached after the iteration, budget in force).
     """
     starts = scale_starts(tokens)
     cache: List[int] = []
@@ -319,7 +320,8 @@ def alg1_cache_trace(tokens: Sequence[int], c_min: int, c_max: int, c_cds: int,
             continue
         cand = cache + ids
         if len(cand) > bgt:
-            if bgt == c_min and below_theta[i]:
+            if bgt == c_min and (below_theta(i, list(cache)) if callable(below_theta)
+                                 else below_theta[i]):
                 bgt = c_max
             if len(ids) > bgt:
                 trace.append((list(cache), bgt))
@@ -328,3 +330,19 @@ def alg1_cache_trace(tokens: Sequence[int], c_min: int, c_max: int, c_cds: int,
         cache = cand
         trace.append((list(cache), bgt))
     return trace
+
+
+def alg1_allow_mask(tokens: Sequence[int], trace: Sequence[Tuple[List[int], int]]) -> np.ndarray:
+    """T x T mask of the token-granular reading of Algorithm 1 (Section 4.3): the tokens of
+    scale i attend to what the cache held after iteration i-1 and to their own scale (the
+    paper never says when attention runs; this reading makes C_min = "condensed plus the
+    penultimate scale" of Section 5 what the final step sees)."""
+    st = scale_starts(tokens)
+    n = sum(int(t) for t in tokens)
+    allow = np.zeros((n, n), dtype=bool)
+    for i, t in enumerate(tokens):
+        rows = slice(st[i], st[i] + int(t))
+        allow[rows, st[i]: st[i] + int(t)] = True
+        if i > 0:
+            allow[rows, np.asarray(trace[i - 1][0], dtype=np.int64)] = True
+    return allow

@@ -23,13 +23,16 @@ AMSKV_ERR_HIP = -5
 AMSKV_ERR_NO_DEVICE_MEMORY = -6
 AMSKV_DTYPE_F32, AMSKV_DTYPE_BF16 = 0, 1
 AMSKV_LAYOUT_COMPACT, AMSKV_LAYOUT_PLANNED = 0, 1
+AMSKV_MODE_SCALE_WINDOW, AMSKV_MODE_TOKEN_BUDGET = 0, 1
 AMSKV_MAX_SCALES = 16
+_MAX_SEGMENTS = AMSKV_MAX_SCALES + 2
 
 EXPORTED = [
     "amskv_cache_required_bytes", "amskv_cache_create", "amskv_append_scale", "amskv_attend",
     "amskv_interscale_similarity", "amskv_cache_layout", "amskv_cache_last_evicted",
     "amskv_cache_bytes_held", "amskv_cache_capacity_tokens", "amskv_cache_export",
     "amskv_cache_reset", "amskv_cache_destroy", "amskv_status_string",
+    "amskv_cache_segments", "amskv_cache_budget_tokens", "amskv_cache_settle",
 ]
 
 
@@ -48,9 +51,14 @@ class _LayerPolicy(C.Structure):
     _fields_ = [("n_condensed", C.c_int32), ("window", C.c_int32), ("keep_all", C.c_int32)]
 
 
+class _LayerBudget(C.Structure):
+    _fields_ = [("c_min", C.c_int32), ("c_max", C.c_int32), ("c_cds", C.c_int32), ("theta", C.c_float)]
+
+
 class _Policy(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("layer", C.POINTER(_LayerPolicy)), ("softmax_scale", C.c_float),
-                ("layout", C.c_int32), ("borrow_unretained", C.c_int32), ("fuse_append", C.c_int32)]
+                ("layout", C.c_int32), ("borrow_unretained", C.c_int32), ("fuse_append", C.c_int32),
+                ("mode", C.c_int32), ("budget", C.POINTER(_LayerBudget))]
 
 
 _lib = None
@@ -96,6 +104,13 @@ def load_library() -> C.CDLL:
     lib.amskv_cache_destroy.restype = None
     lib.amskv_status_string.argtypes = [i32]
     lib.amskv_status_string.restype = C.c_char_p
+    lib.amskv_cache_segments.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i32), C.POINTER(i32), C.POINTER(i64),
+                                         C.POINTER(i32)]
+    lib.amskv_cache_segments.restype = i32
+    lib.amskv_cache_budget_tokens.argtypes = [vp, i32]
+    lib.amskv_cache_budget_tokens.restype = i64
+    lib.amskv_cache_settle.argtypes = [vp, i32, vp]
+    lib.amskv_cache_settle.restype = i32
     _lib = lib
     return lib
 
@@ -109,14 +124,23 @@ def _check(status: int, where: str):
         raise AmskvError(int(status), where)
 
 
-def _structs(sides_h, sides_w, batch, dtype, policies, softmax_scale, layout, borrow_unretained=False, fuse_append=False):
+def _structs(sides_h, sides_w, batch, dtype, policies, softmax_scale, layout, borrow_unretained=False, fuse_append=False,
+             budgets=None):
+    """policies: [(n_condensed, window, keep_all)] per layer (scale-window mode), or None with
+    budgets: [(c_min, c_max, c_cds, theta)] per layer (token-budget mode)."""
     n = len(sides_h)
     ah = (C.c_int32 * n)(*[int(x) for x in sides_h])
     aw = (C.c_int32 * n)(*[int(x) for x in sides_w])
     sc = _Schedule(n, ah, aw, int(batch), int(dtype))
-    lp = (_LayerPolicy * len(policies))(*[_LayerPolicy(int(c), int(w), int(bool(k))) for c, w, k in policies])
-    po = _Policy(len(policies), lp, float(softmax_scale), int(layout), int(bool(borrow_unretained)), int(bool(fuse_append)))
-    return sc, po, (ah, aw, lp)
+    lp = bp = None
+    if policies is not None:
+        lp = (_LayerPolicy * len(policies))(*[_LayerPolicy(int(c), int(w), int(bool(k))) for c, w, k in policies])
+    if budgets is not None:
+        bp = (_LayerBudget * len(budgets))(*[_LayerBudget(int(a), int(b), int(c), float(t)) for a, b, c, t in budgets])
+    n_layers = len(budgets) if budgets is not None else len(policies)
+    po = _Policy(n_layers, lp, float(softmax_scale), int(layout), int(bool(borrow_unretained)), int(bool(fuse_append)),
+                 AMSKV_MODE_TOKEN_BUDGET if budgets is not None else AMSKV_MODE_SCALE_WINDOW, bp)
+    return sc, po, (ah, aw, lp, bp)
 
 
 def _ptr(t) -> Optional[int]:
@@ -139,8 +163,10 @@ def _stream(stream) -> Optional[int]:
 
 # ------------------------------------------------------------------ the calls of amskv.h
 def amskv_cache_required_bytes(layers, heads, head_dim, sides_h, sides_w, batch, dtype, policies,
-                               softmax_scale=0.0, layout=AMSKV_LAYOUT_COMPACT, borrow_unretained=False, fuse_append=False) -> int:
-    sc, po, _keep = _structs(sides_h, sides_w, batch, dtype, policies, softmax_scale, layout, borrow_unretained, fuse_append)
+                               softmax_scale=0.0, layout=AMSKV_LAYOUT_COMPACT, borrow_unretained=False, fuse_append=False,
+                               budgets=None) -> int:
+    sc, po, _keep = _structs(sides_h, sides_w, batch, dtype, policies, softmax_scale, layout, borrow_unretained, fuse_append,
+                             budgets)
     out = C.c_uint64(0)
     _check(load_library().amskv_cache_required_bytes(layers, heads, head_dim, C.byref(sc), C.byref(po),
                                                      C.byref(out)), "amskv_cache_required_bytes")
@@ -149,10 +175,11 @@ def amskv_cache_required_bytes(layers, heads, head_dim, sides_h, sides_w, batch,
 
 def amskv_cache_create(layers, heads, head_dim, sides_h, sides_w, batch, dtype, policies,
                        softmax_scale=0.0, layout=AMSKV_LAYOUT_COMPACT, arena=None, arena_bytes=None,
-                       borrow_unretained=False, fuse_append=False):
+                       borrow_unretained=False, fuse_append=False, budgets=None):
     """arena: torch uint8 device tensor (kept alive by the caller) or None for a plan-only cache.
-    Returns the opaque handle (an int)."""
-    sc, po, _keep = _structs(sides_h, sides_w, batch, dtype, policies, softmax_scale, layout, borrow_unretained, fuse_append)
+    budgets (with policies=None) selects the token-budget mode.  Returns the opaque handle (an int)."""
+    sc, po, _keep = _structs(sides_h, sides_w, batch, dtype, policies, softmax_scale, layout, borrow_unretained, fuse_append,
+                             budgets)
     h = C.c_void_p(None)
     nbytes = 0 if arena is None else (int(arena.numel() * arena.element_size()) if arena_bytes is None else int(arena_bytes))
     _check(load_library().amskv_cache_create(layers, heads, head_dim, C.byref(sc), C.byref(po), _ptr(arena),
@@ -183,11 +210,33 @@ def amskv_interscale_similarity(cache, layer, s, heads, want_v=True, want_sums=T
 def amskv_cache_layout(cache, layer) -> List[Tuple[int, int, int]]:
     """[(scale_id, tok_offset, tok_len)] ascending scale id."""
     n = C.c_int32(0)
-    sid = (C.c_int32 * AMSKV_MAX_SCALES)()
-    off = (C.c_int64 * AMSKV_MAX_SCALES)()
-    ln = (C.c_int32 * AMSKV_MAX_SCALES)()
+    sid = (C.c_int32 * _MAX_SEGMENTS)()
+    off = (C.c_int64 * _MAX_SEGMENTS)()
+    ln = (C.c_int32 * _MAX_SEGMENTS)()
     _check(load_library().amskv_cache_layout(cache, layer, C.byref(n), sid, off, ln), "amskv_cache_layout")
     return [(int(sid[i]), int(off[i]), int(ln[i])) for i in range(n.value)]
+
+
+def amskv_cache_segments(cache, layer) -> List[Tuple[int, int, int, int]]:
+    """[(scale_id, first_token, tok_offset, tok_len)] oldest token first."""
+    n = C.c_int32(0)
+    sid = (C.c_int32 * _MAX_SEGMENTS)()
+    first = (C.c_int32 * _MAX_SEGMENTS)()
+    off = (C.c_int64 * _MAX_SEGMENTS)()
+    ln = (C.c_int32 * _MAX_SEGMENTS)()
+    _check(load_library().amskv_cache_segments(cache, layer, C.byref(n), sid, first, off, ln), "amskv_cache_segments")
+    return [(int(sid[i]), int(first[i]), int(off[i]), int(ln[i])) for i in range(n.value)]
+
+
+def amskv_cache_budget_tokens(cache, layer) -> int:
+    v = int(load_library().amskv_cache_budget_tokens(cache, layer))
+    if v < 0:
+        raise AmskvError(v, "amskv_cache_budget_tokens")
+    return v
+
+
+def amskv_cache_settle(cache, layer, stream=None):
+    _check(load_library().amskv_cache_settle(cache, layer, _stream(stream)), "amskv_cache_settle")
 
 
 def amskv_cache_last_evicted(cache, layer) -> List[int]:

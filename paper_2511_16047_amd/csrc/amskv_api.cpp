@@ -20,6 +20,7 @@ struct Segment {
   int32_t scale;
   int32_t off;  // token offset inside the layer's [cap] axis; -1: borrowed (read in place)
   int32_t len;
+  int32_t first = 0;  // first token of the scale held here (token-budget mode keeps scales in part)
   const void* ext_k = nullptr;  // the caller's K/V of that scale while it is read in place
   const void* ext_v = nullptr;
   bool pending = false;         // fuse_append: slot reserved at `off`, data still only in ext_k/ext_v
@@ -34,12 +35,17 @@ struct LayerState {
   std::vector<Segment> segs;        // ascending scale id
   std::vector<int32_t> last_evicted;
   int32_t planned_off[AMSKV_MAX_SCALES];  // PLANNED layout: fixed slot of every scale
+  // token-budget mode (Algorithm 1): budgets, the budget in force, and whether the newest scale
+  // (last segment, read in place) still awaits its iteration of the algorithm
+  amskv_layer_budget bud = {0, 0, 0, 0.f};
+  int32_t c_bgt = 0;
+  bool roll_pending = false;
 };
 
 }  // namespace
 
 struct amskv_cache {
-  int32_t layers, heads, head_dim, batch, dtype, n_scales, layout, borrow, fuse;
+  int32_t layers, heads, head_dim, batch, dtype, n_scales, layout, borrow, fuse, mode;
   int32_t side_h[AMSKV_MAX_SCALES], side_w[AMSKV_MAX_SCALES], tokens[AMSKV_MAX_SCALES];
   float softmax_scale;
   int32_t elem_bytes;
@@ -91,12 +97,24 @@ int validate(int32_t layers, int32_t heads, int32_t head_dim, const amskv_schedu
   }
   if (total > (1 << 22)) return AMSKV_ERR_INVALID_ARG;
   if ((int64_t)sc->batch * heads > (1 << 24)) return AMSKV_ERR_INVALID_ARG;
-  if (po->n_layers != layers || !po->layer) return AMSKV_ERR_INVALID_ARG;
+  if (po->n_layers != layers) return AMSKV_ERR_INVALID_ARG;
   if (po->layout != AMSKV_LAYOUT_COMPACT && po->layout != AMSKV_LAYOUT_PLANNED)
     return AMSKV_ERR_INVALID_ARG;
   if (po->borrow_unretained != 0 && po->borrow_unretained != 1) return AMSKV_ERR_INVALID_ARG;
   if (po->fuse_append != 0 && po->fuse_append != 1) return AMSKV_ERR_INVALID_ARG;
   if (!(po->softmax_scale >= 0.f) || !std::isfinite(po->softmax_scale)) return AMSKV_ERR_INVALID_ARG;
+  if (po->mode == AMSKV_MODE_TOKEN_BUDGET) {
+    if (!po->budget || po->layout != AMSKV_LAYOUT_COMPACT || po->borrow_unretained || po->fuse_append)
+      return AMSKV_ERR_INVALID_ARG;
+    for (int l = 0; l < layers; ++l) {
+      const amskv_layer_budget& b = po->budget[l];
+      if (b.c_cds < 0 || b.c_min < b.c_cds || b.c_max < b.c_min || b.c_max < 1 || b.c_max > (1 << 22) ||
+          std::isnan(b.theta))
+        return AMSKV_ERR_INVALID_ARG;
+    }
+    return AMSKV_OK;
+  }
+  if (po->mode != AMSKV_MODE_SCALE_WINDOW || !po->layer) return AMSKV_ERR_INVALID_ARG;
   for (int l = 0; l < layers; ++l)
     if (po->layer[l].n_condensed < 0 || po->layer[l].window < 0) return AMSKV_ERR_INVALID_ARG;
   return AMSKV_OK;
@@ -171,7 +189,9 @@ void build_plan(int32_t layers, int32_t heads, int32_t head_dim, const amskv_sch
   pl->slot.assign(layers, std::vector<int32_t>(AMSKV_MAX_SCALES, 0));
   for (int l = 0; l < layers; ++l) {
     int64_t cap;
-    if (po->layout == AMSKV_LAYOUT_PLANNED)
+    if (po->mode == AMSKV_MODE_TOKEN_BUDGET)
+      cap = po->budget[l].c_max;  // Section 4.3: C_max is the most a layer ever holds
+    else if (po->layout == AMSKV_LAYOUT_PLANNED)
       cap = plan_slots(po->layer[l], tokens, sc->n_scales, borrow, pl->slot[l].data());
     else
       cap = compact_capacity(po->layer[l], tokens, sc->n_scales, borrow);
@@ -198,23 +218,222 @@ SegTable seg_table(const LayerState& L, ExtKV* ext) {
   std::memset(&t, 0, sizeof(t));
   ext->k = ext->v = nullptr;
   ext->wb_off = -1;
-  t.n = (int32_t)L.segs.size();
   int32_t v = 0;
   int32_t ext_start = -1;
-  for (int i = 0; i < t.n; ++i) {
-    t.virt_start[i] = v;
-    t.phys_off[i] = L.segs[i].off < 0 ? 0 : L.segs[i].off;
-    t.len[i] = L.segs[i].len;
-    if (L.segs[i].off < 0 || L.segs[i].pending) {
-      ext_start = v;
-      ext->k = L.segs[i].ext_k;
-      ext->v = L.segs[i].ext_v;
+  int n = 0;
+  for (const Segment& g : L.segs) {
+    const bool outside = g.off < 0 || g.pending;
+    // neighbours that are also back to back in memory form one run for the kernels (in the
+    // COMPACT layout the whole cached part is one run; token-budget mode relies on that to
+    // stay within the table however many partial scales it holds)
+    if (!outside && n > 0 && ext_start < 0 && t.phys_off[n - 1] + t.len[n - 1] == g.off) {
+      t.len[n - 1] += g.len;
+    } else {
+      t.virt_start[n] = v;
+      t.phys_off[n] = g.off < 0 ? 0 : g.off;
+      t.len[n] = g.len;
+      ++n;
     }
-    v += L.segs[i].len;
+    if (outside) {
+      ext_start = v;
+      ext->k = g.ext_k;
+      ext->v = g.ext_v;
+    }
+    v += g.len;
   }
+  t.n = n;
   t.total = v;
   t.ext_start = ext_start < 0 ? v : ext_start;
   return t;
+}
+
+inline bool whole_scale(const amskv_cache* c, const Segment& g, int s) {
+  return g.scale == s && g.first == 0 && g.len == c->tokens[s];
+}
+
+// Eq. 3 between scale s (segment cur) and the upsampled scale s-1 (segment prev), both held
+// whole: per head four sums (cosine total, k.k^, |k|^2, |k^|^2) of K into host[0 .. 4H) and,
+// when want_v, of V into host[4H .. 8H).  Waits for the stream.
+int similarity_sums(amskv_cache* c, const LayerState& L, const Segment& cur, const Segment& prev, int s,
+                    bool want_v, std::vector<float>* host, hipStream_t st) {
+  const uint64_t bh = (uint64_t)c->batch * c->heads;
+  float* partial = (float*)(c->arena + c->ws_off);
+  float* totals = partial + 2 * bh * 4;
+  auto ref = [&](const Segment& g) {
+    ScaleRef r;
+    if (g.off < 0 || g.pending) {
+      r.k = g.ext_k;
+      r.v = want_v ? g.ext_v : nullptr;
+      r.stride_tokens = g.len;
+      r.off_tokens = 0;
+    } else {
+      r.k = c->arena + L.k_off;
+      r.v = want_v ? c->arena + L.v_off : nullptr;
+      r.stride_tokens = L.cap;
+      r.off_tokens = g.off;
+    }
+    return r;
+  };
+  hipError_t e = amskv::launch_similarity(ref(cur), ref(prev), c->batch, c->heads, c->head_dim, c->dtype,
+                                          c->side_h[s], c->side_w[s], c->side_h[s - 1], c->side_w[s - 1],
+                                          partial, totals, st);
+  if (e != hipSuccess) return AMSKV_ERR_HIP;
+  host->assign(2 * (size_t)c->heads * 4, 0.f);
+  const size_t n_t = want_v ? 2 : 1;
+  e = hipMemcpyAsync(host->data(), totals, n_t * c->heads * 4 * sizeof(float), hipMemcpyDeviceToHost, st);
+  if (e != hipSuccess) return AMSKV_ERR_HIP;
+  e = hipStreamSynchronize(st);
+  return e == hipSuccess ? AMSKV_OK : AMSKV_ERR_HIP;
+}
+
+// Algorithm 1's test for a cache-demanding layer: Eq. 3 (cosine form, mean over heads) of the
+// newest scale against the scale before it, compared with theta.
+int below_theta(amskv_cache* c, const LayerState& L, const Segment& cur, hipStream_t st, bool* below) {
+  *below = false;
+  if (L.bud.theta > 1.f) {
+    *below = true;
+    return AMSKV_OK;
+  }
+  if (L.bud.theta < -1.f || cur.scale < 1) return AMSKV_OK;
+  const Segment* prev = nullptr;
+  for (const Segment& g : L.segs)
+    if (&g != &L.segs.back() && whole_scale(c, g, cur.scale - 1)) prev = &g;
+  if (!prev) return AMSKV_OK;  // the earlier scale is not cached whole: no score, no expansion
+  if (!c->arena || !cur.ext_k) return AMSKV_ERR_NO_DEVICE_MEMORY;
+  std::vector<float> host;
+  int rc = similarity_sums(c, L, cur, *prev, cur.scale, false, &host, st);
+  if (rc) return rc;
+  double mean = 0.0;
+  const double n_tok = (double)c->batch * c->tokens[cur.scale];
+  for (int h = 0; h < c->heads; ++h) mean += (double)(float)(host[h * 4] / n_tok);
+  mean /= c->heads;
+  *below = mean < (double)L.bud.theta;
+  return AMSKV_OK;
+}
+
+// Token-budget mode: Algorithm 1's iteration for the newest scale, which until now has been read
+// in place as the last segment.  Decides whether the scale is cached at all, expands the budget
+// once if the layer tests as cache-demanding, and applies Algorithm 2 to the token list
+// (cached tokens followed by the new scale): the first c_cds tokens and the last
+// (budget - c_cds) tokens stay.  Survivors slide toward offset 0; what stays of the new scale
+// is copied behind them.
+int roll_budget(amskv_cache* c, LayerState& L, hipStream_t st) {
+  if (!L.roll_pending) return AMSKV_OK;
+  const Segment cur = L.segs.back();
+  const int32_t t_new = cur.len;
+  int64_t n_old = 0;
+  for (size_t i = 0; i + 1 < L.segs.size(); ++i) n_old += L.segs[i].len;
+  int32_t bgt = L.c_bgt;
+  bool cache_it = t_new <= L.bud.c_max;
+  if (cache_it && n_old + t_new > bgt) {
+    if (bgt == L.bud.c_min && L.bud.c_max > L.bud.c_min) {
+      bool below = false;
+      int rc = below_theta(c, L, cur, st, &below);
+      if (rc) return rc;
+      if (below) bgt = L.bud.c_max;
+    }
+    if (t_new > bgt) cache_it = false;
+  }
+
+  struct CopyRange {
+    int32_t src_first, len, dst;
+  };
+  std::vector<Segment> next;
+  std::vector<int32_t> evicted;
+  std::vector<CopyRange> copies;
+  MoveList mv;
+  std::memset(&mv, 0, sizeof(mv));
+  if (!cache_it) {
+    next.assign(L.segs.begin(), L.segs.end() - 1);
+  } else {
+    const int64_t total = n_old + t_new;
+    const bool trim = total > bgt;
+    const int64_t head_end = trim ? L.bud.c_cds : total;                       // keep [0, head_end)
+    const int64_t tail_begin = trim ? total - (bgt - L.bud.c_cds) : total;     // and [tail_begin, total)
+    int64_t pos = 0;
+    int32_t at = 0;
+    for (size_t i = 0; i < L.segs.size(); ++i) {
+      const Segment& g = L.segs[i];
+      const bool is_new = i + 1 == L.segs.size();
+      const int64_t lo = pos, hi = pos + g.len;
+      const int64_t range[2][2] = {{lo, std::min(hi, head_end)}, {std::max(lo, tail_begin), hi}};
+      int64_t kept = 0;
+      for (int r = 0; r < 2; ++r) {
+        const int64_t a = range[r][0], b = range[r][1];
+        if (b <= a) continue;
+        Segment n;
+        n.scale = g.scale;
+        n.first = g.first + (int32_t)(a - lo);
+        n.len = (int32_t)(b - a);
+        n.off = at;
+        if (is_new) {
+          copies.push_back({n.first, n.len, at});
+        } else {
+          const int32_t src = g.off + (int32_t)(a - lo);
+          if (src != at) {
+            if (mv.n > 0 && mv.src[mv.n - 1] + mv.len[mv.n - 1] == src &&
+                mv.dst[mv.n - 1] + mv.len[mv.n - 1] == at) {
+              mv.len[mv.n - 1] += n.len;
+            } else {
+              if (mv.n == AMSKV_MAX_SCALES) return AMSKV_ERR_INVALID_ARG;  // cannot happen: survivors form one run
+              mv.src[mv.n] = src;
+              mv.dst[mv.n] = at;
+              mv.len[mv.n] = n.len;
+              ++mv.n;
+            }
+          }
+        }
+        at += n.len;
+        kept += n.len;
+        next.push_back(n);
+      }
+      if (!is_new && kept < g.len && (evicted.empty() || evicted.back() != g.scale)) evicted.push_back(g.scale);
+      pos = hi;
+    }
+    if (at > L.cap) return AMSKV_ERR_ARENA_TOO_SMALL;  // cannot happen: at <= budget <= c_max
+  }
+
+  if (c->arena && cur.ext_k) {
+    const int bh = c->batch * c->heads;
+    const int row_bytes = c->head_dim * c->elem_bytes;
+    char* kc = c->arena + L.k_off;
+    char* vc = c->arena + L.v_off;
+    if (mv.n > 0) {
+      hipError_t e = amskv::launch_append(kc, vc, nullptr, nullptr, bh, row_bytes, L.cap, mv, 0, 0, 0, 0, st);
+      if (e != hipSuccess) return AMSKV_ERR_HIP;
+    }
+    MoveList none;
+    std::memset(&none, 0, sizeof(none));
+    for (const CopyRange& r : copies) {
+      hipError_t e = amskv::launch_append(kc, vc, cur.ext_k, cur.ext_v, bh, row_bytes, L.cap, none, r.len, r.dst,
+                                          r.src_first, t_new, st);
+      if (e != hipSuccess) return AMSKV_ERR_HIP;
+    }
+  }
+  L.segs.swap(next);
+  L.last_evicted.swap(evicted);
+  L.c_bgt = bgt;
+  L.roll_pending = false;
+  return AMSKV_OK;
+}
+
+// fuse_append: a scale whose attend never came still lives only in the caller's buffers; copy it
+int flush_pending(amskv_cache* c, LayerState& L, hipStream_t st) {
+  const int bh = c->batch * c->heads;
+  const int row_bytes = c->head_dim * c->elem_bytes;
+  for (Segment& g : L.segs) {
+    if (!g.pending) continue;
+    if (g.ext_k) {
+      MoveList none;
+      std::memset(&none, 0, sizeof(none));
+      hipError_t e = amskv::launch_append(c->arena + L.k_off, c->arena + L.v_off, g.ext_k, g.ext_v, bh, row_bytes,
+                                          L.cap, none, g.len, g.off, 0, g.len, st);
+      if (e != hipSuccess) return AMSKV_ERR_HIP;
+    }
+    g.pending = false;
+    g.ext_k = g.ext_v = nullptr;
+  }
+  return AMSKV_OK;
 }
 
 }  // namespace
@@ -270,6 +489,7 @@ int32_t amskv_cache_create(int32_t layers, int32_t heads, int32_t head_dim,
   c->layout = po->layout;
   c->borrow = po->borrow_unretained;
   c->fuse = po->fuse_append;
+  c->mode = po->mode;
   c->elem_bytes = sc->dtype == AMSKV_DTYPE_BF16 ? 2 : 4;
   c->softmax_scale = po->softmax_scale > 0.f ? po->softmax_scale : 1.0f / std::sqrt((float)head_dim);
   for (int i = 0; i < sc->n_scales; ++i) {
@@ -283,7 +503,13 @@ int32_t amskv_cache_create(int32_t layers, int32_t heads, int32_t head_dim,
   c->layer.resize(layers);
   for (int l = 0; l < layers; ++l) {
     LayerState& L = c->layer[l];
-    L.pol = po->layer[l];
+    if (c->mode == AMSKV_MODE_TOKEN_BUDGET) {
+      L.pol = amskv_layer_policy{0, 0, 0};
+      L.bud = po->budget[l];
+      L.c_bgt = L.bud.c_min;
+    } else {
+      L.pol = po->layer[l];
+    }
     L.cap = pl.cap[l];
     L.k_off = pl.k_off[l];
     L.v_off = pl.v_off[l];
@@ -303,19 +529,24 @@ int32_t amskv_append_scale(amskv_cache* c, int32_t layer, int32_t s, const void*
 
   const int bh = c->batch * c->heads;
   const int row_bytes = c->head_dim * c->elem_bytes;
-  // fuse_append: a scale whose attend never came still lives only in the caller's buffers; copy it now
-  for (Segment& g : L.segs) {
-    if (!g.pending) continue;
-    if (g.ext_k) {
-      MoveList none;
-      std::memset(&none, 0, sizeof(none));
-      hipError_t e = amskv::launch_append(c->arena + L.k_off, c->arena + L.v_off, g.ext_k, g.ext_v, bh, row_bytes,
-                                          L.cap, none, g.len, g.off, (hipStream_t)stream);
-      if (e != hipSuccess) return AMSKV_ERR_HIP;
-    }
-    g.pending = false;
-    g.ext_k = g.ext_v = nullptr;
+  if (c->mode == AMSKV_MODE_TOKEN_BUDGET) {
+    // the previous scale's iteration of Algorithm 1, if its attend never came; then scale s is
+    // only recorded: the attention of step s reads it in place, its own iteration follows that
+    int rc = roll_budget(c, L, (hipStream_t)stream);
+    if (rc) return rc;
+    Segment cur;
+    cur.scale = s;
+    cur.len = c->tokens[s];
+    cur.off = -1;
+    cur.ext_k = K_dev;
+    cur.ext_v = V_dev;
+    L.segs.push_back(cur);
+    L.roll_pending = true;
+    L.last_scale = s;
+    return AMSKV_OK;
   }
+  int frc = flush_pending(c, L, (hipStream_t)stream);
+  if (frc) return frc;
 
   // new resident list (ascending scale id) and where each segment goes; a borrowed segment of
   // the previous step is by construction not resident any more and simply drops out
@@ -366,7 +597,7 @@ int32_t amskv_append_scale(amskv_cache* c, int32_t layer, int32_t s, const void*
   if (K_dev && (copy_now || mv.n > 0)) {
     hipError_t e = amskv::launch_append(c->arena + L.k_off, c->arena + L.v_off, copy_now ? K_dev : nullptr,
                                         copy_now ? V_dev : nullptr, bh, row_bytes, L.cap, mv, cur.len,
-                                        copy_now ? cur.off : 0, (hipStream_t)stream);
+                                        copy_now ? cur.off : 0, 0, cur.len, (hipStream_t)stream);
     if (e != hipSuccess) return AMSKV_ERR_HIP;
   }
   L.segs.swap(next);
@@ -381,6 +612,8 @@ int32_t amskv_attend(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev
     return AMSKV_ERR_INVALID_ARG;
   LayerState& L = c->layer[layer];
   if (s != L.last_scale) return AMSKV_ERR_ORDER;
+  // token-budget mode: once the scale's iteration of Algorithm 1 has run it is no longer whole
+  if (c->mode == AMSKV_MODE_TOKEN_BUDGET && !L.roll_pending) return AMSKV_ERR_ORDER;
   if (!c->arena) return AMSKV_ERR_NO_DEVICE_MEMORY;
   ExtKV ext;
   const SegTable t = seg_table(L, &ext);
@@ -402,6 +635,7 @@ int32_t amskv_attend(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev
     newest.pending = false;
     newest.ext_k = newest.ext_v = nullptr;
   }
+  if (c->mode == AMSKV_MODE_TOKEN_BUDGET) return roll_budget(c, L, (hipStream_t)stream);
   return AMSKV_OK;
 }
 
@@ -413,42 +647,16 @@ int32_t amskv_interscale_similarity(amskv_cache* c, int32_t layer, int32_t s, fl
   const Segment* cur = nullptr;
   const Segment* prev = nullptr;
   for (const Segment& g : L.segs) {
-    if (g.scale == s) cur = &g;
-    if (g.scale == s - 1) prev = &g;
+    if (whole_scale(c, g, s)) cur = &g;
+    if (whole_scale(c, g, s - 1)) prev = &g;
   }
   if (!cur || !prev) return AMSKV_ERR_EVICTED;
   if (!c->arena) return AMSKV_ERR_NO_DEVICE_MEMORY;
   if (((cur->off < 0 || cur->pending) && !cur->ext_k) || ((prev->off < 0 || prev->pending) && !prev->ext_k))
     return AMSKV_ERR_NO_DEVICE_MEMORY;
-  const uint64_t bh = (uint64_t)c->batch * c->heads;
-  float* partial = (float*)(c->arena + c->ws_off);
-  float* totals = partial + 2 * bh * 4;
-  hipStream_t st = (hipStream_t)stream;
-  auto ref = [&](const Segment* g) {
-    ScaleRef r;
-    if (g->off < 0 || g->pending) {
-      r.k = g->ext_k;
-      r.v = cosV_host ? g->ext_v : nullptr;
-      r.stride_tokens = g->len;
-      r.off_tokens = 0;
-    } else {
-      r.k = c->arena + L.k_off;
-      r.v = cosV_host ? c->arena + L.v_off : nullptr;
-      r.stride_tokens = L.cap;
-      r.off_tokens = g->off;
-    }
-    return r;
-  };
-  hipError_t e = amskv::launch_similarity(ref(cur), ref(prev), c->batch, c->heads, c->head_dim, c->dtype,
-                                          c->side_h[s], c->side_w[s], c->side_h[s - 1], c->side_w[s - 1],
-                                          partial, totals, st);
-  if (e != hipSuccess) return AMSKV_ERR_HIP;
-  std::vector<float> host(2 * (size_t)c->heads * 4);
-  const size_t n_t = cosV_host ? 2 : 1;
-  e = hipMemcpyAsync(host.data(), totals, n_t * c->heads * 4 * sizeof(float), hipMemcpyDeviceToHost, st);
-  if (e != hipSuccess) return AMSKV_ERR_HIP;
-  e = hipStreamSynchronize(st);
-  if (e != hipSuccess) return AMSKV_ERR_HIP;
+  std::vector<float> host;
+  int rc = similarity_sums(c, L, *cur, *prev, s, cosV_host != nullptr, &host, (hipStream_t)stream);
+  if (rc) return rc;
   const double n_tok = (double)c->batch * c->tokens[s];
   for (int h = 0; h < c->heads; ++h) {
     cosK_host[h] = (float)(host[h * 4 + 0] / n_tok);
@@ -473,6 +681,33 @@ int32_t amskv_cache_layout(const amskv_cache* c, int32_t layer, int32_t* n_seg, 
     if (tok_len) tok_len[i] = L.segs[i].len;
   }
   return AMSKV_OK;
+}
+
+int32_t amskv_cache_segments(const amskv_cache* c, int32_t layer, int32_t* n_seg, int32_t* scale_id,
+                             int32_t* first_token, int64_t* tok_offset, int32_t* tok_len) {
+  if (bad_layer(c, layer) || !n_seg) return AMSKV_ERR_INVALID_ARG;
+  const LayerState& L = c->layer[layer];
+  *n_seg = (int32_t)L.segs.size();
+  for (size_t i = 0; i < L.segs.size(); ++i) {
+    if (scale_id) scale_id[i] = L.segs[i].scale;
+    if (first_token) first_token[i] = L.segs[i].first;
+    if (tok_offset) tok_offset[i] = L.segs[i].off;
+    if (tok_len) tok_len[i] = L.segs[i].len;
+  }
+  return AMSKV_OK;
+}
+
+int64_t amskv_cache_budget_tokens(const amskv_cache* c, int32_t layer) {
+  if (bad_layer(c, layer)) return AMSKV_ERR_INVALID_ARG;
+  const LayerState& L = c->layer[layer];
+  return c->mode == AMSKV_MODE_TOKEN_BUDGET ? (int64_t)L.c_bgt : L.cap;
+}
+
+int32_t amskv_cache_settle(amskv_cache* c, int32_t layer, void* stream) {
+  if (bad_layer(c, layer)) return AMSKV_ERR_INVALID_ARG;
+  LayerState& L = c->layer[layer];
+  if (c->mode == AMSKV_MODE_TOKEN_BUDGET) return roll_budget(c, L, (hipStream_t)stream);
+  return flush_pending(c, L, (hipStream_t)stream);
 }
 
 int32_t amskv_cache_last_evicted(const amskv_cache* c, int32_t layer, int32_t* n_evicted,
@@ -520,6 +755,8 @@ int32_t amskv_cache_reset(amskv_cache* c) {
     L.segs.clear();
     L.last_evicted.clear();
     L.last_scale = -1;
+    L.c_bgt = L.bud.c_min;
+    L.roll_pending = false;
   }
   return AMSKV_OK;
 }

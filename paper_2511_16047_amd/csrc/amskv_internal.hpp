@@ -67,10 +67,11 @@ hipError_t launch_attend_bf16_small(const void* q, void* o, void* kc, void* vc, 
 hipError_t launch_attend_f32(const void* q, void* o, void* kc, void* vc, int bh,
                              int t_q, int head_dim, int64_t cap_tokens, const SegTable& seg,
                              const ExtKV& ext, float softmax_scale, hipStream_t st);
-// k_new == nullptr: compaction only (the new scale is borrowed, nothing to copy)
+// k_new == nullptr: compaction only (the new scale is borrowed, nothing to copy); otherwise tokens
+// [src_first, src_first + t_new) of the new scale ([BH][src_stride][row]) go to offset dst_new
 hipError_t launch_append(void* kc, void* vc, const void* k_new, const void* v_new, int bh,
                          int row_bytes, int64_t cap_tokens, const MoveList& mv, int t_new,
-                         int dst_new, hipStream_t st);
+                         int dst_new, int src_first, int src_stride, hipStream_t st);
 hipError_t launch_export(const void* kc, const void* vc, void* k_out, void* v_out, int bh,
                          int row_bytes, int64_t cap_tokens, const SegTable& seg, const ExtKV& ext,
                          hipStream_t st);

@@ -447,8 +447,8 @@ hipError_t launch_attend_bf16(const void* q, void* o, void* kc, void* vc, int bh
     // eight waves of 32 rows: ~110 registers per lane, so two workgroups (16 waves) share a CU
     return wide ? launch<64, 1, 8, 64, 4>(q, o, kc, vc, bh, t_q, cap_tokens, seg, ext, c, st)
                 : launch<64, 1, 4, 32, 4>(q, o, kc, vc, bh, t_q, cap_tokens, seg, ext, c, st);
-  // head dim 128: 32 query rows per wave keep the kernel at two waves per SIMD and 12 workgroup-waves per CU, which measured
-  // ~14 % faster than 64 rows per wave at one wave per SIMD on the 1024x1024 schedule; 32-key tiles
+  // head dim 128: 32 query rows per wave keep the kernel at two waves per SIMD (two workgroups of
+  // four waves per CU), which measured ~14 % faster than 64 rows per wave at one wave per SIMD on the 1024x1024 schedule; 32-key tiles
   // (16 KB per ring slot) leave room for several workgroups per CU
   (void)wide;
   return launch<128, 1, 4, 32, 2>(q, o, kc, vc, bh, t_q, cap_tokens, seg, ext, c, st);

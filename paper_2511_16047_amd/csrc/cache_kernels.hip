@@ -60,14 +60,17 @@ __global__ __launch_bounds__(kThreads) void compact_kernel(char* __restrict__ kc
   }
 }
 
-// Append: copy the new scale K_s, V_s ([BH][T_s][row], contiguous) into its slot of every (b,h)
-// row of the cache.  Flat over all 16-byte chunks of both tensors, so a one-token scale and a
-// 256-token scale both run full workgroups; the source side is one contiguous stream.
+// Append: copy t_new tokens of the new scale K_s, V_s ([BH][src_stride][row], starting at token
+// src_first of every (b,h) row) into their slot of every (b,h) row of the cache.  Flat over all
+// 16-byte chunks of both tensors, so a one-token scale and a 256-token scale both run full
+// workgroups; for a whole scale (src_first = 0, src_stride = t_new) the source side is one
+// contiguous stream.  The token-granular trim of Algorithm 2 keeps a scale in part, hence the range.
 // Enqueued after compact_kernel: the slot may overlap the old position of a moved segment.
 __global__ __launch_bounds__(kThreads) void append_kernel(char* __restrict__ kc, char* __restrict__ vc,
                                                           const char* __restrict__ k_new,
                                                           const char* __restrict__ v_new, int row_bytes,
                                                           long long cap_tokens, int t_new, int dst_new,
+                                                          int src_first, int src_stride,
                                                           long long chunks_per_tensor) {
   const int cpr = row_bytes >> 4;
   const int per_bh = t_new * cpr;  // chunks of one (b,h) row
@@ -85,7 +88,8 @@ __global__ __launch_bounds__(kThreads) void append_kernel(char* __restrict__ kc,
       const long long bh = c / per_bh;
       const int rem = (int)(c - bh * per_bh);
       dst_off[u] = (bh * cap_tokens + dst_new) * row_bytes + ((long long)rem << 4);
-      buf[u] = *reinterpret_cast<const uint4*>((which[u] ? v_new : k_new) + (c << 4));
+      const long long so = ((bh * src_stride + src_first) * cpr + rem) << 4;
+      buf[u] = *reinterpret_cast<const uint4*>((which[u] ? v_new : k_new) + so);
     }
   }
 #pragma unroll
@@ -117,19 +121,21 @@ __global__ __launch_bounds__(kThreads) void export_kernel(const char* __restrict
 }  // namespace
 
 hipError_t launch_append(void* kc, void* vc, const void* k_new, const void* v_new, int bh, int row_bytes,
-                         int64_t cap_tokens, const MoveList& mv, int t_new, int dst_new, hipStream_t st) {
+                         int64_t cap_tokens, const MoveList& mv, int t_new, int dst_new, int src_first,
+                         int src_stride, hipStream_t st) {
   if (mv.n > 0) {
     hipLaunchKernelGGL(compact_kernel, dim3(bh, 2), dim3(kThreads), 0, st, (char*)kc, (char*)vc, row_bytes,
                        (long long)cap_tokens, mv);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  if (!k_new) return hipSuccess;  // borrowed scale: compaction only
+  if (!k_new || t_new <= 0) return hipSuccess;  // borrowed scale: compaction only
   const long long chunks = (long long)bh * t_new * (row_bytes >> 4);
   const long long per_block = (long long)kThreads * kUnroll;
   const unsigned grid = (unsigned)((2 * chunks + per_block - 1) / per_block);
   hipLaunchKernelGGL(append_kernel, dim3(grid), dim3(kThreads), 0, st, (char*)kc, (char*)vc, (const char*)k_new,
-                     (const char*)v_new, row_bytes, (long long)cap_tokens, t_new, dst_new, chunks);
+                     (const char*)v_new, row_bytes, (long long)cap_tokens, t_new, dst_new, src_first, src_stride,
+                     chunks);
   return hipGetLastError();
 }
 

@@ -197,3 +197,104 @@ def test_status_codes():
     finally:
         amskv.amskv_cache_destroy(h)
     assert amskv.status_string(0) == "ok" and "order" in amskv.status_string(-2)
+
+
+# ------------------------------------------------------------------ token-budget mode (Algorithms 1 and 2, literal)
+def _budget_cache(sides, budgets, B=2, H=3, D=64, dtype=amskv.AMSKV_DTYPE_BF16, **kw):
+    return amskv.amskv_cache_create(len(budgets), H, D, sides, sides, B, dtype, None, 0.0,
+                                    amskv.AMSKV_LAYOUT_COMPACT, budgets=budgets, **kw)
+
+
+def _segment_ids(tokens, segs, cached_only=True):
+    st = orc.scale_starts(tokens)
+    ids, at = [], 0
+    for scale, first, off, ln in segs:
+        if off < 0:
+            if cached_only:
+                continue
+        else:
+            assert off == at, "cached tokens sit back to back from offset 0"
+            at += ln
+        ids += list(range(st[scale] + first, st[scale] + first + ln))
+    return ids
+
+
+@pytest.mark.parametrize("sides", [VAR, INF, (1, 2, 3), (2, 2, 5, 3), (3, 1, 4, 1, 5, 9, 2, 6)])
+def test_token_budget_mode_matches_algorithm_1(sides):
+    import random
+    tokens = [s * s for s in sides]
+    total = sum(tokens)
+    rng = random.Random(1234 + len(sides))
+    budgets = [(174, 274, 5, 2.0), (174, 274, 5, -2.0), (274, 274, 5, 0.0), (174, 255, 5, 2.0), (174, 300, 5, 2.0),
+               (total, total, 0, 0.0), (1, 1, 0, 2.0), (1, 1, 1, 2.0), (7, 7, 7, -2.0)]
+    for _ in range(40):
+        cds = rng.randint(0, max(tokens))
+        cmin = rng.randint(cds, total)
+        cmax = rng.randint(max(cmin, 1), total + 3)
+        budgets.append((cmin, cmax, cds, rng.choice([2.0, -2.0])))
+    B, H, D = 2, 3, 64
+    starts, scale_of = orc.scale_starts(tokens), orc.scale_of_token(tokens)
+    h = _budget_cache(sides, budgets, B=B, H=H, D=D)
+    try:
+        traces = [orc.alg1_cache_trace(tokens, a, b, c, [th > 1] * len(tokens)) for a, b, c, th in budgets]
+        for l, (a, b, c, th) in enumerate(budgets):
+            assert amskv.amskv_cache_capacity_tokens(h, l) == b
+            assert amskv.amskv_cache_budget_tokens(h, l) == a
+        for s in range(len(sides)):
+            for l in range(len(budgets)):
+                amskv.amskv_append_scale(h, l, s)
+                segs = amskv.amskv_cache_segments(h, l)
+                # before the scale's own iteration: the cache of the previous step plus the scale, read in place
+                assert segs[-1] == (s, 0, -1, tokens[s])
+                assert _segment_ids(tokens, segs) == (traces[l][s - 1][0] if s else [])
+                assert amskv.amskv_cache_layout(h, l) == [(a, c, d) for a, _, c, d in segs]
+                if s % 2:
+                    amskv.amskv_cache_settle(h, l)   # odd steps settle explicitly, even ones at the next append
+                    amskv.amskv_cache_settle(h, l)   # and settling twice changes nothing
+                    ids, bgt = traces[l][s]
+                    assert _segment_ids(tokens, amskv.amskv_cache_segments(h, l), cached_only=False) == ids
+                    assert amskv.amskv_cache_budget_tokens(h, l) == bgt
+                    held = amskv.amskv_cache_bytes_held(h, l, True)
+                    assert held == 2 * 2 * B * H * D * len(ids)
+                    # scales that lost cached tokens in this iteration
+                    lost = set(traces[l][s - 1][0]) - set(ids)
+                    assert amskv.amskv_cache_last_evicted(h, l) == sorted({int(scale_of[g]) for g in lost})
+        for l in range(len(budgets)):
+            amskv.amskv_cache_settle(h, l)
+            ids, bgt = traces[l][-1]
+            assert _segment_ids(tokens, amskv.amskv_cache_segments(h, l), cached_only=False) == ids
+            assert amskv.amskv_cache_budget_tokens(h, l) == bgt
+            assert len(ids) <= bgt
+        amskv.amskv_cache_reset(h)
+        for l, (a, b, c, th) in enumerate(budgets):
+            assert amskv.amskv_cache_segments(h, l) == [] and amskv.amskv_cache_budget_tokens(h, l) == a
+    finally:
+        amskv.amskv_cache_destroy(h)
+
+
+def test_token_budget_mode_rejects_bad_configurations():
+    sides = (1, 2, 3)
+    E = amskv.AMSKV_ERR_INVALID_ARG
+    for bad in [(5, 4, 2, 0.0), (1, 4, 2, 0.0), (0, 0, 0, 0.0), (3, 4, -1, 0.0), (3, 4, 1, float("nan"))]:
+        with pytest.raises(amskv.AmskvError) as e:
+            _budget_cache(sides, [bad])
+        assert e.value.status == E
+    for kw in [dict(borrow_unretained=True), dict(fuse_append=True)]:
+        with pytest.raises(amskv.AmskvError) as e:
+            _budget_cache(sides, [(3, 4, 1, 0.0)], **kw)
+        assert e.value.status == E
+    with pytest.raises(amskv.AmskvError) as e:
+        amskv.amskv_cache_create(1, 3, 64, sides, sides, 2, amskv.AMSKV_DTYPE_BF16, None, 0.0,
+                                 amskv.AMSKV_LAYOUT_PLANNED, budgets=[(3, 4, 1, 0.0)])
+    assert e.value.status == E
+    # a threshold inside [-1, 1] needs the keys: a plan-only cache cannot evaluate Eq. 3
+    h = _budget_cache(sides, [(4, 9, 1, 0.0)])
+    try:
+        amskv.amskv_append_scale(h, 0, 0)
+        amskv.amskv_append_scale(h, 0, 1)
+        amskv.amskv_append_scale(h, 0, 2)      # settles scale 1: 1 + 4 > 4 -> the test is due, scale 0 is cached whole
+        assert False, "expected an error"
+    except amskv.AmskvError as e:
+        assert e.status == amskv.AMSKV_ERR_NO_DEVICE_MEMORY
+    finally:
+        amskv.amskv_cache_destroy(h)

@@ -398,3 +398,48 @@ def test_alg1_trace_hand_derived():
     big = orc.alg1_cache_trace(VAR_T, 174, 300, 5, [True] * 10)
     last = big[9][0]
     assert len(last) == 300 and sum(1 for g in last if g >= st[9]) == 256 and sum(1 for g in last if st[8] <= g < st[9]) == 39
+
+
+def test_alg1_mask_closed_forms():
+    tokens = [s * s for s in (1, 2, 3, 4, 5, 6)]
+    st = orc.scale_starts(tokens)
+    n = sum(tokens)
+    # a budget that is never reached: every earlier token stays -> the block-causal mask
+    tr = orc.alg1_cache_trace(tokens, n, n, 3, [False] * len(tokens))
+    assert np.array_equal(orc.alg1_allow_mask(tokens, tr), orc.allow_mask(tokens, (0, 0, True)))
+    # no condensed tokens, one budget k >= every scale: a sliding window of the k newest tokens
+    for k in (36, 40, 57):
+        tr = orc.alg1_cache_trace(tokens, k, k, 0, [False] * len(tokens))
+        m = orc.alg1_allow_mask(tokens, tr)
+        for i, t in enumerate(tokens):
+            want = np.zeros(n, dtype=bool)
+            want[max(0, st[i] - k): st[i] + t] = True
+            assert np.array_equal(m[st[i]], want) and np.array_equal(m[st[i] + t - 1], want)
+    # condensed tokens stay visible to every later scale, own scale always whole
+    tr = orc.alg1_cache_trace(tokens, 30, 30, 5, [False] * len(tokens))
+    m = orc.alg1_allow_mask(tokens, tr)
+    assert m[st[5]:, :5].all() and not m[st[5], 5: st[5] - 25].any() and m[st[5], st[5] - 25:].all()
+    # whole-scale budgets reproduce the scale-window policy at the steps where they line up:
+    # C = condensed(2 scales) + penultimate scale -> step s sees {0, 1, s-1, s} once s-1 fills the tail exactly
+    for s in (4, 5):
+        c = 5 + tokens[s - 1]
+        tr = orc.alg1_cache_trace(tokens, c, c, 5, [False] * len(tokens))
+        assert np.array_equal(orc.alg1_allow_mask(tokens, tr)[st[s]], orc.allow_mask(tokens, (2, 1, False))[st[s]])
+
+
+def test_alg1_theta_test_is_asked_once_and_only_on_overflow():
+    calls = []
+
+    def ask(i, cached):
+        calls.append((i, len(cached)))
+        return True
+
+    tr = orc.alg1_cache_trace(VAR_T, 174, 274, 5, ask)
+    # the first overflow of C_min is at the 100-token scale (155 cached + 100 > 174)
+    assert calls == [(7, 155)]
+    assert tr == orc.alg1_cache_trace(VAR_T, 174, 274, 5, [True] * 10)
+    calls.clear()
+    orc.alg1_cache_trace(VAR_T, 174, 274, 5, lambda i, c: calls.append(i) or False)
+    # a layer that stays at C_min is asked again at every later overflow (the 256-token scale
+    # is within C_max = 274, so it reaches the test too before being skipped for exceeding C_min)
+    assert calls == [7, 8, 9]
