@@ -20,6 +20,8 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+// 16-byte chunk as a native vector: arrays of it stay in registers (HIP's uint4 struct did not)
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kWavesPerGroup = 4;
 
@@ -35,8 +37,10 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
   return r;
 }
 
+// Register budget: three waves per SIMD at head dim 64 and two at 128 are the most that fit without spilling;
+// every step up in resident waves measured faster on these latency-bound launches.
 template <int D>
-__global__ __launch_bounds__(64 * kWavesPerGroup) void attend_bf16_small_kernel(
+__global__ __launch_bounds__(64 * kWavesPerGroup, D == 64 ? 3 : 2) void attend_bf16_small_kernel(
     const __bf16* __restrict__ q, __bf16* __restrict__ o, char* __restrict__ kc, char* __restrict__ vc,
     int t_q, long long cap_tokens, SegTable seg, ExtKV ext_kv, float scale_log2e, int n_qblk, int n_units) {
   constexpr int RB = D * 2;
@@ -72,7 +76,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void attend_bf16_small_kernel(
   }
 
   bf16x8 kf[KS];
-  uint4 vch[VCH];
+  u32x4 vch[VCH];
   auto load_block = [&](int g) {
     const int j0 = 32 * g;
     bool kext;
@@ -85,7 +89,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void attend_bf16_small_kernel(
       const int id = k * 64 + lane, row = id / CPR, c = id % CPR;
       bool vext;
       const long long vrow = (long long)locate_row(seg, min(j0 + row, t_kv - 1), vext) * RB;
-      vch[k] = *reinterpret_cast<const uint4*>((vext ? xv : vb) + vrow + 16 * c);
+      vch[k] = *reinterpret_cast<const u32x4*>((vext ? xv : vb) + vrow + 16 * c);
     }
   };
   load_block(0);
@@ -105,7 +109,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void attend_bf16_small_kernel(
 #pragma unroll
     for (int k = 0; k < VCH; ++k) {
       const int id = k * 64 + lane, row = id / CPR, c = id % CPR;
-      *reinterpret_cast<uint4*>(my_v + row * RB + 16 * (c ^ (row & 7))) = vch[k];
+      *reinterpret_cast<u32x4*>(my_v + row * RB + 16 * (c ^ (row & 7))) = vch[k];
     }
     f32x16 sacc;
 #pragma unroll
@@ -124,7 +128,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void attend_bf16_small_kernel(
       for (int k = 0; k < VCH; ++k) {
         const int id = k * 64 + lane, row = id / CPR, c = id % CPR;
         if (j0 + row >= seg.ext_start && j0 + row < t_kv)
-          *reinterpret_cast<uint4*>(vb + (long long)(ext_kv.wb_off + j0 + row - seg.ext_start) * RB + 16 * c) = vch[k];
+          *reinterpret_cast<u32x4*>(vb + (long long)(ext_kv.wb_off + j0 + row - seg.ext_start) * RB + 16 * c) = vch[k];
       }
     }
     if (g + 1 < n_blocks) load_block(g + 1);  // in flight during the softmax and the second product
