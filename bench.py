@@ -56,7 +56,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="var_d30", choices=["var_d30", "var_d16", "var_d24", "infinity_2b"])
     ap.add_argument("--batch", type=int, default=0, help="0 = the configuration's batch")
-    ap.add_argument("--mode", default="amskv", choices=["amskv", "vanilla"])
+    ap.add_argument("--mode", default="amskv", choices=["amskv", "vanilla", "token_budget"],
+                    help="amskv: per-layer scale windows picked from the similarity probe (the default, the contract's "
+                         "workload); vanilla: every layer keeps everything; token_budget: Algorithms 1 and 2 literally, "
+                         "budgets in tokens, the Eq. 3 test and the budget expansion run inside the step")
     ap.add_argument("--layout", default="planned", choices=["compact", "planned"],
                     help="planned (default): every scale has a fixed slot, eviction moves nothing; compact: kept "
                          "scales stay back to back, eviction slides the survivors down")
@@ -107,6 +110,15 @@ def main():
     layout = amskv.AMSKV_LAYOUT_PLANNED if args.layout == "planned" else amskv.AMSKV_LAYOUT_COMPACT
     borrow = not args.no_borrow
     fuse = not args.no_fuse
+    budgets = None
+    if args.mode == "token_budget":
+        # Section 5 set-up read as token counts: condensed = the first two scales, C_min = condensed + the
+        # penultimate scale, C_max = condensed + the two scales before the last; the cached tokens stay one
+        # contiguous run (COMPACT), the current scale is always read in place
+        c_cds = tokens[0] + tokens[1]
+        budgets = [(c_cds + tokens[-2], c_cds + tokens[-3] + tokens[-2], c_cds, COS_THRESHOLD)] * L
+        layout, borrow, fuse = amskv.AMSKV_LAYOUT_COMPACT, False, False
+        args.layout = "compact"
 
     # ---------------- synthetic inputs, resident in HBM
     t0 = time.time()
@@ -128,7 +140,9 @@ def main():
     # ---------------- policy: cache-demanding layers from the similarity call (VAR-d30 configuration)
     base_pol = list(w.policies)
     cos_layer = None
-    if args.mode == "vanilla":
+    if args.mode == "token_budget":
+        pols = None
+    elif args.mode == "vanilla":
         pols = [(0, 0, True)] * L
     elif args.workload == "var_d30":
         need = amskv.amskv_cache_required_bytes(1, H, D, w.sides, w.sides, B, 1, [(0, 0, True)])
@@ -149,10 +163,10 @@ def main():
     else:
         pols = base_pol
 
-    need = amskv.amskv_cache_required_bytes(L, H, D, w.sides, w.sides, B, 1, pols, 0.0, layout, borrow, fuse)
+    need = amskv.amskv_cache_required_bytes(L, H, D, w.sides, w.sides, B, 1, pols, 0.0, layout, borrow, fuse, budgets=budgets)
     arena = torch.empty(need, dtype=torch.uint8, device=dev)
     cache = amskv.amskv_cache_create(L, H, D, w.sides, w.sides, B, 1, pols, 0.0, layout, arena=arena,
-                                     borrow_unretained=borrow, fuse_append=fuse)
+                                     borrow_unretained=borrow, fuse_append=fuse, budgets=budgets)
     probe_layers = list(range(L))
     probe = PROBE_SCALE if S > PROBE_SCALE else S - 1
 
@@ -178,7 +192,7 @@ def main():
                     amskv.amskv_attend(cache, l, s, Qp[l][s], Op[s], stream)
                     e[2].record()
                     timers.append((l, s, e))
-            if s == probe and probe >= 1:
+            if s == probe and probe >= 1 and budgets is None:
                 for l in probe_layers:
                     amskv.amskv_interscale_similarity(cache, l, s, H, want_v=False, want_sums=False, stream=stream)
 
@@ -193,7 +207,32 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
-    flops = sum(4.0 * B * H * tokens[s] * kept_tokens(tokens, pols[l], s) * D for l in range(L) for s in range(S))
+    # tokens each step attends to, and (token-budget mode) what its iteration of Algorithm 1 moved and copied
+    if budgets is None:
+        kv_len = [[kept_tokens(tokens, pols[l], s) for s in range(S)] for l in range(L)]
+        rolled = None
+        expanded = []
+    else:
+        # which layers the Eq. 3 test expanded is read back from the cache; the per-step token counts then come
+        # from the library's own host logic on a plan-only cache with the same decisions forced
+        expanded = [amskv.amskv_cache_budget_tokens(cache, l) == budgets[l][1] for l in range(L)]
+        forced = [(a, b, c, 2.0 if expanded[l] else -2.0) for l, (a, b, c, _) in enumerate(budgets)]
+        plan = amskv.amskv_cache_create(L, H, D, w.sides, w.sides, B, 1, None, budgets=forced)
+        kv_len = [[0] * S for _ in range(L)]
+        rolled = [[0] * S for _ in range(L)]
+        for l in range(L):
+            for s in range(S):
+                amskv.amskv_append_scale(plan, l, s)
+                before = amskv.amskv_cache_segments(plan, l)
+                kv_len[l][s] = sum(x[3] for x in before)
+                amskv.amskv_cache_settle(plan, l)
+                old = {(sc, first + i): off + i for sc, first, off, ln in before if off >= 0 for i in range(ln)}
+                for sc, first, off, ln in amskv.amskv_cache_segments(plan, l):
+                    rolled[l][s] += sum(1 for i in range(ln) if old.get((sc, first + i)) != off + i)
+            assert amskv.amskv_cache_bytes_held(plan, l, True) == amskv.amskv_cache_bytes_held(cache, l, True)
+        amskv.amskv_cache_destroy(plan)
+        log("layers whose budget the Eq. 3 test expanded:", [l for l in range(L) if expanded[l]])
+    flops = sum(4.0 * B * H * tokens[s] * kv_len[l][s] * D for l in range(L) for s in range(S))
     held = sum(amskv.amskv_cache_bytes_held(cache, l, True) for l in range(L))
     held_paper = sum(amskv.amskv_cache_bytes_held(cache, l, False) for l in range(L))
     vanilla_held = 2 * eb * B * H * D * sum(tokens) * L
@@ -210,9 +249,18 @@ def main():
     per_scale = [[0.0, 0.0, 0.0, 0.0] for _ in range(S)]
     for l, s, e in timers:
         ta, tt = e[0].elapsed_time(e[1]) * 1e-3, e[1].elapsed_time(e[2]) * 1e-3
-        tkv = kept_tokens(tokens, pols[l], s)
+        tkv = kv_len[l][s]
         by = (2 * tokens[s] + 2 * tkv) * D * eb * B * H
         fl = 4.0 * B * H * tokens[s] * tkv * D
+        if budgets is not None:
+            # the attend call also runs the step's iteration of Algorithm 1: tokens that slid or were copied in
+            # are read and written once, K and V (the append call itself only records pointers)
+            by += 2 * 2 * rolled[l][s] * D * eb * B * H
+            att_t += tt; app_t += ta; att_bytes += by
+            per_scale[s][0] += ta; per_scale[s][1] += tt; per_scale[s][2] += fl; per_scale[s][3] += by
+            if tokens[s] > dom_rows:
+                dom_t += tt; dom_bytes += by; dom_flops += fl; dom_n += 1
+            continue
         # append: moved tokens (COMPACT) read+written, new scale read+written, K and V
         prev = [k for k in range(s) if pols[l][2] or k < pols[l][0] or (s - 1) - k <= pols[l][1]]
         now = [k for k in prev if pols[l][2] or k < pols[l][0] or s - k <= pols[l][1]]
@@ -243,9 +291,10 @@ def main():
 
     # ---------------- the stand-alone evict + compact + append kernels: one instrumented pass over a second
     # cache in the copying configuration (COMPACT layout, nothing borrowed or fused), for their HBM rate
-    need2 = amskv.amskv_cache_required_bytes(L, H, D, w.sides, w.sides, B, 1, pols)
+    sa_pols = pols if pols is not None else list(w.policies)   # token-budget mode: the configuration's scale windows
+    need2 = amskv.amskv_cache_required_bytes(L, H, D, w.sides, w.sides, B, 1, sa_pols)
     arena2 = torch.empty(need2, dtype=torch.uint8, device=dev)
-    cache2 = amskv.amskv_cache_create(L, H, D, w.sides, w.sides, B, 1, pols, arena=arena2)
+    cache2 = amskv.amskv_cache_create(L, H, D, w.sides, w.sides, B, 1, sa_pols, arena=arena2)
     ev = []
     for s in range(S):
         for l in range(L):
@@ -257,8 +306,8 @@ def main():
     torch.cuda.synchronize()
     sa_t = sa_b = 0.0
     for l, s, e0, e1 in ev:
-        prev = [k for k in range(s) if pols[l][2] or k < pols[l][0] or (s - 1) - k <= pols[l][1]]
-        now = [k for k in prev if pols[l][2] or k < pols[l][0] or s - k <= pols[l][1]]
+        prev = [k for k in range(s) if sa_pols[l][2] or k < sa_pols[l][0] or (s - 1) - k <= sa_pols[l][1]]
+        now = [k for k in prev if sa_pols[l][2] or k < sa_pols[l][0] or s - k <= sa_pols[l][1]]
         moved = 0
         if len(now) != len(prev):
             first_gone = min(k for k in prev if k not in now)
@@ -270,6 +319,8 @@ def main():
     del arena2
 
     dom_name = "attend_bf16_kernel<%d,%s>" % (D, "1,8,64,4" if D == 64 else "1,4,32,2")
+    if budgets is not None:   # the timed interval of an attend call holds the step's Algorithm 1 iteration too
+        dom_name += " + Algorithm 1 iteration (similarity, compact, copy kernels)"
     ai = dom_flops / dom_bytes
     hbm_bound = ai < PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
     if hbm_bound:
@@ -291,7 +342,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "mode": args.mode, "layout": args.layout, "borrow_unretained": int(borrow), "fuse_append": int(fuse), "layers": L, "heads": H,
                    "head_dim": D, "batch": B, "tokens": sum(tokens), "scales": S,
-                   "cache_demanding_layers": sum(1 for p in pols if p[2]), "probe_scale": probe},
+                   "cache_demanding_layers": sum(expanded) if budgets is not None else sum(1 for p in pols if p[2]),
+                   "probe_scale": probe,
+                   **({"budgets_c_min_c_max_c_cds_theta": list(budgets[0])} if budgets is not None else {})},
         "ms_per_image": ms_per_step / B,
         "kv_bytes_held": held, "kv_bytes_held_excluding_current_scale": held_paper,
         "kv_bytes_vanilla": vanilla_held, "kv_reduction": 1.0 - held / vanilla_held,
@@ -308,12 +361,13 @@ def main():
 
     # ---------------- the oracle, timed on the host cores, on a bounded sample of the same workload
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, pols, K, V, Q, tokens, H, D)
+        out["cpu_baseline"] = cpu_baseline(w, pols, K, V, Q, tokens, H, D, kv_len[0],
+                                           None if budgets is None else (budgets[0], expanded[0]))
     print(json.dumps(out), flush=True)
     amskv.amskv_cache_destroy(cache)
 
 
-def cpu_baseline(w, pols, K, V, Q, tokens, H, D):
+def cpu_baseline(w, pols, K, V, Q, tokens, H, D, kv_len0, budget0=None):
     """The oracle as it stands, on (layer 0, the first few batch rows, all heads, all scales)."""
     import numpy as np
     from oracle import amskv_oracle as orc
@@ -333,15 +387,21 @@ def cpu_baseline(w, pols, K, V, Q, tokens, H, D):
         k = [x[b:b + nb_now].double().cpu().numpy() for x in K[l]]
         v = [x[b:b + nb_now].double().cpu().numpy() for x in V[l]]
         t0 = time.perf_counter()
-        orc.attend_all_steps(q, k, v, tokens, pols[l])
-        for s in range(S):
-            orc.cache_contents(k, pols[l], s)
-            orc.cache_contents(v, pols[l], s)
+        if budget0 is not None:
+            (c_min, c_max, c_cds, _), grew = budget0
+            trace = orc.alg1_cache_trace(tokens, c_min, c_max, c_cds, [grew] * S)
+            cat = lambda xs: np.concatenate(xs, axis=-2)
+            orc.masked_attention(cat(q), cat(k), cat(v), orc.alg1_allow_mask(tokens, trace))
+        else:
+            orc.attend_all_steps(q, k, v, tokens, pols[l])
+            for s in range(S):
+                orc.cache_contents(k, pols[l], s)
+                orc.cache_contents(v, pols[l], s)
         if S > PROBE_SCALE:
             sd = (w.sides[PROBE_SCALE],) * 2, (w.sides[PROBE_SCALE - 1],) * 2
             orc.interscale_similarity(k[PROBE_SCALE], k[PROBE_SCALE - 1], sd[0], sd[1])
         elapsed += time.perf_counter() - t0
-        done_flops += sum(4.0 * nb_now * H * tokens[s] * kept_tokens(tokens, pols[l], s) * D for s in range(S))
+        done_flops += sum(4.0 * nb_now * H * tokens[s] * kv_len0[s] * D for s in range(S))
         b += nb_now
         nb += nb_now
     return {"value": done_flops / elapsed / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
