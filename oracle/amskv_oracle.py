@@ -28,7 +28,9 @@ tiny schedules, equality with plain block-causal attention when the window cover
 every scale, library attention on the gathered kept keys, rows of P summing to one,
 O = V at scale 0, NaN-poisoned evicted scales, pure-Python triple loops on a 3-scale
 schedule, library bilinear resize, affine-ramp reproduction, cos = +-1 cases, and the
-integer-list simulation of Algorithms 1 and 2.  No function here is "parity unpinned";
+integer-list simulation of Algorithms 1 and 2 (hand-derived traces, closed-form masks), and
+for the attention density: mass summing to T_s, an element-by-element brute force, the
+uniform and the one-dominant-key cases.  No function here is "parity unpinned";
 the paper's printed GB and percent figures are unpinned (its Tables 3 and 5 disagree
 with each other and with Eq. 4) and are quoted, never asserted.
 """
@@ -346,3 +348,27 @@ def alg1_allow_mask(tokens: Sequence[int], trace: Sequence[Tuple[List[int], int]
         if i > 0:
             allow[rows, np.asarray(trace[i - 1][0], dtype=np.int64)] = True
     return allow
+
+
+# --------------------------------------------------------------------------- attention density
+def attention_density(q_s: np.ndarray, k_all: np.ndarray, allow_rows: np.ndarray,
+                      pieces: Sequence[Tuple[int, int]], softmax_scale: float | None = None):
+    """Attention density of Section 4.1 for the queries of one scale.
+
+    q_s: [B, H, T_s, D] queries of the scale being generated; k_all: [B, H, T, D] keys of the
+    whole sequence; allow_rows: [T_s, T] mask rows of those queries; pieces: (first global token,
+    length) of each group of keys (a scale, or the part of a scale that is cached).
+    Returns (density[H, n_pieces], mass[H, n_pieces]): mass is the attention matrix summed over
+    the queries of the scale and the keys of the piece, averaged over the batch; density divides
+    it by the number of key tokens of the piece.  Reading of the printed definition: A^(j->i) has
+    one row per query of scale j and one column per key of scale i, so T_i counts key tokens and
+    the density is attention mass per cached token.  mass / T_s (the other reading) follows from
+    the second output.
+    """
+    q = np.asarray(q_s, dtype=np.float64)
+    zeros_v = np.zeros(np.asarray(k_all).shape, dtype=np.float64)
+    _, p = masked_attention(q, k_all, zeros_v, allow_rows, softmax_scale, return_probs=True)
+    mass = np.stack([p[..., a: a + n].sum(axis=(-1, -2)) for a, n in pieces], axis=-1)  # [B, H, n_pieces]
+    mass = mass.mean(axis=0)
+    dens = mass / np.asarray([n for _, n in pieces], dtype=np.float64)
+    return dens, mass

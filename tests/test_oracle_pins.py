@@ -443,3 +443,45 @@ def test_alg1_theta_test_is_asked_once_and_only_on_overflow():
     # a layer that stays at C_min is asked again at every later overflow (the 256-token scale
     # is within C_max = 274, so it reaches the test too before being skipped for exceeding C_min)
     assert calls == [7, 8, 9]
+
+
+# ------------------------------------------------------------------ attention density (Section 4.1)
+def test_attention_density_invariants_and_closed_forms():
+    rng = np.random.default_rng(5)
+    tokens = [1, 4, 9, 16]
+    st = orc.scale_starts(tokens)
+    B, H, D = 2, 3, 8
+    k_all = rng.standard_normal((B, H, sum(tokens), D))
+    s = 3
+    q = rng.standard_normal((B, H, tokens[s], D))
+    pol = (1, 1, False)                       # step 3 sees scales {0, 2, 3}
+    rows = orc.allow_mask(tokens, pol)[st[s]: st[s] + tokens[s]]
+    pieces = [(st[k], tokens[k]) for k in orc.kept_scales(pol, s)]
+    dens, mass = orc.attention_density(q, k_all, rows, pieces)
+    # every query spends exactly one unit of attention on what it can see
+    assert np.allclose(mass.sum(axis=-1), tokens[s], rtol=0, atol=1e-12)
+    assert np.allclose(dens * [n for _, n in pieces], mass)
+    # brute force, element by element
+    for h in range(H):
+        want = np.zeros(len(pieces))
+        for b in range(B):
+            for qi in range(tokens[s]):
+                vis = [j for j in range(sum(tokens)) if rows[qi, j]]
+                e = [math.exp(float(q[b, h, qi] @ k_all[b, h, j]) / math.sqrt(D)) for j in vis]
+                z = sum(e)
+                for pi, (a, n) in enumerate(pieces):
+                    want[pi] += sum(x for x, j in zip(e, vis) if a <= j < a + n) / z / B
+        assert np.allclose(mass[h], want, rtol=1e-12, atol=1e-12)
+    # uniform attention (all-zero queries): every visible token receives T_s / T_kv
+    dens0, _ = orc.attention_density(np.zeros_like(q), k_all, rows, pieces)
+    assert np.allclose(dens0, tokens[s] / sum(n for _, n in pieces))
+    # one key that dominates: its piece takes (almost) all of the mass
+    k_big = k_all.copy()
+    k_big[..., st[2] + 4, :] = 50.0 * np.sign(q.mean(axis=-2))     # aligned with the mean query of each (b, h)
+    q_pos = np.abs(q) * np.sign(q.mean(axis=-2, keepdims=True))
+    _, m_big = orc.attention_density(q_pos, k_big, rows, pieces)
+    assert (m_big[:, 1] > tokens[s] - 1e-6).all()
+    # partial pieces of one scale add up to the scale
+    halves = [(st[2], 4), (st[2] + 4, 5)]
+    _, m_halves = orc.attention_density(q, k_all, rows, halves)
+    assert np.allclose(m_halves.sum(axis=-1), mass[:, 1])
