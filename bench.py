@@ -318,6 +318,22 @@ def main():
     amskv.amskv_cache_destroy(cache2)
     del arena2
 
+    # ---------------- the attention-density by-product (Section 4.1) of the last step, one call per layer
+    dens = None
+    if budgets is None:
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        amskv.amskv_attention_density(cache, 0, S - 1, Qp[0][S - 1], H, stream=stream)   # warm-up
+        e0.record()
+        for l in range(L):
+            dl, _ = amskv.amskv_attention_density(cache, l, S - 1, Qp[l][S - 1], H, stream=stream)
+        e1.record()
+        torch.cuda.synchronize()
+        d_ms = e0.elapsed_time(e1) / L
+        d_fl = sum(2.0 * B * H * tokens[S - 1] * kv_len[l][S - 1] * D for l in range(L)) / L
+        dens = {"what": "per-head softmax mass per cached token of each kept scale, last step, one call per layer "
+                        "(kernels + result copy + wait)", "ms_per_call": d_ms, "tflops_qk": d_fl / (d_ms * 1e-3) / 1e12,
+                "last_layer_head0_density_per_kept_scale": [round(x, 4) for x in dl[0]]}
+
     dom_name = "attend_bf16_kernel<%d,%s>" % (D, "1,8,64,4" if D == 64 else "1,4,32,2")
     if budgets is not None:   # the timed interval of an attend call holds the step's Algorithm 1 iteration too
         dom_name += " + Algorithm 1 iteration (similarity, compact, copy kernels)"
@@ -354,6 +370,7 @@ def main():
         "standalone_append": {"what": "evict + compact + append kernels, COMPACT layout, nothing borrowed or fused, "
                                       "scales with T_s >= 64, read+write bytes", "gbs": sa_b / max(sa_t, 1e-9) / 1e9,
                               "frac_of_hbm_peak": sa_b / max(sa_t, 1e-9) / 1e9 / PEAK_HBM_GBS, "ms": sa_t * 1e3},
+        "attention_density": dens,
         "roofline": roof,
         "paper_context": {"kv_reduction_up_to": 0.8483, "self_attention_latency_reduction": 0.6048,
                           "var_d30_b256": "44.94 GB KV, 23.88 img/s whole model", "hardware": "NVIDIA A100-80GB, FlashAttention-2"},

@@ -138,7 +138,8 @@ typedef struct {
 
 /* Bytes the arena must have for this configuration: for every layer the K and V regions
  * sized for the largest kept set the policy ever reaches (Section 4.3: capacity is fixed
- * per layer), plus a small reduction workspace for amskv_interscale_similarity.
+ * per layer), plus small reduction workspaces for amskv_interscale_similarity and
+ * amskv_attention_density.
  * Host only. */
 int32_t amskv_cache_required_bytes(int32_t layers, int32_t heads, int32_t head_dim,
                                    const amskv_schedule* schedule, const amskv_policy* policy,
@@ -188,6 +189,23 @@ int32_t amskv_attend(amskv_cache* cache, int32_t layer, int32_t s,
 int32_t amskv_interscale_similarity(amskv_cache* cache, int32_t layer, int32_t s,
                                     float* cosK_host, float* cosV_host, float* sums_host,
                                     void* stream);
+
+/* Attention density (Section 4.1): of the softmax mass that the queries Q of scale s spread over
+ * the keys they attend to, how much lands on each group of keys of layer `layer` -- the groups
+ * being the entries of amskv_cache_segments, in that order (whole scales in scale-window mode).
+ * Call it where amskv_attend(layer, s) may be called (in token-budget mode before it, since
+ * that call ends by trimming the cache).  Outputs, host arrays of heads * AMSKV_MAX_SCALES floats,
+ * entry [h * AMSKV_MAX_SCALES + i] for group i < *n_seg, either may be NULL:
+ *   mass_host     attention matrix summed over the T_s queries and the keys of the group, mean
+ *                 over the batch; the groups of a head add up to T_s
+ *   density_host  mass divided by the number of key tokens of the group: the printed definition
+ *                 read with A^(j->i) holding one row per query of scale j and one column per key
+ *                 of scale i (mass / T_s, the other reading, follows from mass_host)
+ * bf16 caches only; at most AMSKV_MAX_SCALES groups; fp32 arithmetic on the exact bf16 products,
+ * fixed reduction order (deterministic).  Reads Q, the cache and a borrowed scale; writes only its
+ * workspace inside the arena.  Waits for `stream` before returning. */
+int32_t amskv_attention_density(amskv_cache* cache, int32_t layer, int32_t s, const void* Q_dev,
+                                float* density_host, float* mass_host, int32_t* n_seg, void* stream);
 
 /* Resident segments of a layer, ascending scale id: n_seg entries written to each
  * caller array of at least AMSKV_MAX_SCALES elements.  tok_offset is the position of the

@@ -32,7 +32,7 @@ EXPORTED = [
     "amskv_interscale_similarity", "amskv_cache_layout", "amskv_cache_last_evicted",
     "amskv_cache_bytes_held", "amskv_cache_capacity_tokens", "amskv_cache_export",
     "amskv_cache_reset", "amskv_cache_destroy", "amskv_status_string",
-    "amskv_cache_segments", "amskv_cache_budget_tokens", "amskv_cache_settle",
+    "amskv_cache_segments", "amskv_cache_budget_tokens", "amskv_cache_settle", "amskv_attention_density",
 ]
 
 
@@ -111,6 +111,8 @@ def load_library() -> C.CDLL:
     lib.amskv_cache_budget_tokens.restype = i64
     lib.amskv_cache_settle.argtypes = [vp, i32, vp]
     lib.amskv_cache_settle.restype = i32
+    lib.amskv_attention_density.argtypes = [vp, i32, i32, vp, pf, pf, C.POINTER(i32), vp]
+    lib.amskv_attention_density.restype = i32
     _lib = lib
     return lib
 
@@ -205,6 +207,17 @@ def amskv_interscale_similarity(cache, layer, s, heads, want_v=True, want_sums=T
            "amskv_interscale_similarity")
     return (list(ck), list(cv) if want_v else None,
             [[sm[3 * h + i] for i in range(3)] for h in range(heads)] if want_sums else None)
+
+
+def amskv_attention_density(cache, layer, s, Q, heads, stream=None):
+    """Returns (density[H][n_seg], mass[H][n_seg]) as nested Python lists of floats."""
+    d = (C.c_float * (heads * AMSKV_MAX_SCALES))()
+    m = (C.c_float * (heads * AMSKV_MAX_SCALES))()
+    n = C.c_int32(0)
+    _check(load_library().amskv_attention_density(cache, layer, s, _ptr(Q), d, m, C.byref(n), _stream(stream)),
+           "amskv_attention_density")
+    rows = lambda a: [[a[h * AMSKV_MAX_SCALES + i] for i in range(n.value)] for h in range(heads)]
+    return rows(d), rows(m)
 
 
 def amskv_cache_layout(cache, layer) -> List[Tuple[int, int, int]]:

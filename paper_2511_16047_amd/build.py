@@ -18,7 +18,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libamskv.so")
 OBJ = os.path.join(HERE, "_build")
 
-SOURCES = ["amskv_api.cpp", "cache_kernels.hip", "similarity_kernels.hip", "attend_f32.hip", "attend_bf16.hip", "attend_bf16_small.hip"]
+SOURCES = ["amskv_api.cpp", "cache_kernels.hip", "similarity_kernels.hip", "attend_f32.hip", "attend_bf16.hip", "attend_bf16_small.hip", "density_kernels.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip", "-Wno-inline-asm",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

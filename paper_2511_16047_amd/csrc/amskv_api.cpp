@@ -2,6 +2,7 @@
 // tables, status codes, and the C ABI declared in amskv.h.  All policy decisions are made
 // here on the host; the kernels only see token offsets.
 #include <algorithm>
+#include <climits>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -51,7 +52,8 @@ struct amskv_cache {
   int32_t elem_bytes;
   char* arena = nullptr;
   uint64_t arena_bytes = 0;
-  uint64_t ws_off = 0;  // similarity workspace
+  uint64_t ws_off = 0;    // similarity workspace
+  uint64_t dens_off = 0;  // attention-density workspace
   std::vector<LayerState> layer;
 };
 
@@ -171,7 +173,7 @@ struct Plan {
   std::vector<int64_t> cap;
   std::vector<uint64_t> k_off, v_off;
   std::vector<std::vector<int32_t>> slot;
-  uint64_t ws_off = 0, total = 0;
+  uint64_t ws_off = 0, dens_off = 0, total = 0;
 };
 
 void build_plan(int32_t layers, int32_t heads, int32_t head_dim, const amskv_schedule* sc,
@@ -204,6 +206,12 @@ void build_plan(int32_t layers, int32_t heads, int32_t head_dim, const amskv_sch
   pl->ws_off = at;
   // similarity workspace: per (tensor, b, h) four partial sums, then per (tensor, h) four totals
   at = align_up(at + (2 * bh * 4 + 2 * (uint64_t)heads * 4) * sizeof(float));
+  // attention-density workspace: per (b, h, block of 32 query rows) one partial sum per group of keys,
+  // then per head one total per group
+  int32_t t_max = 0;
+  for (int i = 0; i < sc->n_scales; ++i) t_max = std::max(t_max, tokens[i]);
+  pl->dens_off = at;
+  at = align_up(at + (bh * (uint64_t)((t_max + 31) / 32) + (uint64_t)heads) * AMSKV_MAX_SCALES * sizeof(float));
   pl->total = at;
 }
 
@@ -213,7 +221,7 @@ inline bool bad_layer(const amskv_cache* c, int32_t layer) {
 
 // Segment table for the kernels; a borrowed segment (always the newest scale, hence last)
 // becomes the external tail of the virtual concatenation.
-SegTable seg_table(const LayerState& L, ExtKV* ext) {
+SegTable seg_table(const LayerState& L, ExtKV* ext, bool merge = true) {
   SegTable t;
   std::memset(&t, 0, sizeof(t));
   ext->k = ext->v = nullptr;
@@ -226,7 +234,7 @@ SegTable seg_table(const LayerState& L, ExtKV* ext) {
     // neighbours that are also back to back in memory form one run for the kernels (in the
     // COMPACT layout the whole cached part is one run; token-budget mode relies on that to
     // stay within the table however many partial scales it holds)
-    if (!outside && n > 0 && ext_start < 0 && t.phys_off[n - 1] + t.len[n - 1] == g.off) {
+    if (merge && !outside && n > 0 && ext_start < 0 && t.phys_off[n - 1] + t.len[n - 1] == g.off) {
       t.len[n - 1] += g.len;
     } else {
       t.virt_start[n] = v;
@@ -500,6 +508,7 @@ int32_t amskv_cache_create(int32_t layers, int32_t heads, int32_t head_dim,
   c->arena = (char*)arena_dev;
   c->arena_bytes = arena_bytes;
   c->ws_off = pl.ws_off;
+  c->dens_off = pl.dens_off;
   c->layer.resize(layers);
   for (int l = 0; l < layers; ++l) {
     LayerState& L = c->layer[l];
@@ -667,6 +676,42 @@ int32_t amskv_interscale_similarity(amskv_cache* c, int32_t layer, int32_t s, fl
     }
     if (cosV_host) cosV_host[h] = (float)(host[(c->heads + h) * 4 + 0] / n_tok);
   }
+  return AMSKV_OK;
+}
+
+int32_t amskv_attention_density(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev, float* density_host,
+                                float* mass_host, int32_t* n_seg, void* stream) {
+  if (bad_layer(c, layer) || s < 0 || s >= c->n_scales || !Q_dev || (!density_host && !mass_host))
+    return AMSKV_ERR_INVALID_ARG;
+  if (c->dtype != AMSKV_DTYPE_BF16) return AMSKV_ERR_INVALID_ARG;
+  LayerState& L = c->layer[layer];
+  if (s != L.last_scale) return AMSKV_ERR_ORDER;
+  if (c->mode == AMSKV_MODE_TOKEN_BUDGET && !L.roll_pending) return AMSKV_ERR_ORDER;
+  if (L.segs.size() > (size_t)AMSKV_MAX_SCALES) return AMSKV_ERR_INVALID_ARG;
+  if (!c->arena) return AMSKV_ERR_NO_DEVICE_MEMORY;
+  ExtKV ext;
+  const SegTable t = seg_table(L, &ext, false);  // one entry per group of keys, nothing merged
+  if (t.ext_start < t.total && !ext.k) return AMSKV_ERR_NO_DEVICE_MEMORY;
+  const int64_t n_qblk = (c->tokens[s] + 31) / 32;
+  if ((int64_t)c->batch * c->heads * n_qblk > INT32_MAX) return AMSKV_ERR_INVALID_ARG;
+  float* partial = (float*)(c->arena + c->dens_off);
+  float* totals = partial + (uint64_t)c->batch * c->heads * n_qblk * AMSKV_MAX_SCALES;
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = amskv::launch_density(Q_dev, c->arena + L.k_off, c->batch, c->heads, c->tokens[s], c->head_dim, L.cap,
+                                       t, ext, c->softmax_scale, partial, totals, st);
+  if (e != hipSuccess) return AMSKV_ERR_HIP;
+  std::vector<float> host((size_t)c->heads * AMSKV_MAX_SCALES);
+  e = hipMemcpyAsync(host.data(), totals, host.size() * sizeof(float), hipMemcpyDeviceToHost, st);
+  if (e != hipSuccess) return AMSKV_ERR_HIP;
+  e = hipStreamSynchronize(st);
+  if (e != hipSuccess) return AMSKV_ERR_HIP;
+  for (int h = 0; h < c->heads; ++h)
+    for (int p = 0; p < t.n; ++p) {
+      const float m = host[(size_t)h * AMSKV_MAX_SCALES + p];
+      if (mass_host) mass_host[h * AMSKV_MAX_SCALES + p] = m;
+      if (density_host) density_host[h * AMSKV_MAX_SCALES + p] = m / (float)t.len[p];
+    }
+  if (n_seg) *n_seg = t.n;
   return AMSKV_OK;
 }
 

@@ -87,4 +87,10 @@ hipError_t launch_similarity(const ScaleRef& cur, const ScaleRef& prev, int batc
                              int head_dim, int dtype, int h_cur, int w_cur, int h_prev, int w_prev,
                              float* partial_ws, float* out_dev, hipStream_t st);
 
+// attention density: pieces = one table entry per group of keys (nothing merged); partial_ws holds
+// batch*heads*ceil(t_q/32)*AMSKV_MAX_SCALES floats, out_dev heads*AMSKV_MAX_SCALES floats; bf16 only
+hipError_t launch_density(const void* q, const void* kc, int batch, int heads, int t_q, int head_dim,
+                          int64_t cap_tokens, const SegTable& pieces, const ExtKV& ext, float softmax_scale,
+                          float* partial_ws, float* out_dev, hipStream_t st);
+
 }  // namespace amskv

@@ -1,0 +1,131 @@
+"""GPU parity of the attention density (Section 4.1) against the oracle: fp32 arithmetic on exact bf16
+products versus fp64, so mass and density agree to rtol 2e-4 / atol 1e-5; the group list is bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import amskv_inputs as inp
+import paper_2511_16047_amd as amskv
+from oracle import amskv_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+VAR = (1, 2, 3, 4, 5, 6, 8, 10, 13, 16)
+BF16 = amskv.AMSKV_DTYPE_BF16
+
+
+def _f64(t):
+    return t.detach().to("cpu", torch.float64).numpy()
+
+
+def _check(h, layer, s, tokens, q_dev, k_all, H, softmax_scale=None):
+    """Compare the library's density of step s with the oracle's over the library's own group list."""
+    st = orc.scale_starts(tokens)
+    segs = amskv.amskv_cache_segments(h, layer)
+    pieces = [(st[sc] + first, ln) for sc, first, _, ln in segs]
+    rows = np.zeros((tokens[s], sum(tokens)), dtype=bool)
+    for a, n in pieces:
+        rows[:, a: a + n] = True
+    want_d, want_m = orc.attention_density(_f64(q_dev), k_all, rows, pieces, softmax_scale)
+    got_d, got_m = amskv.amskv_attention_density(h, layer, s, q_dev, H)
+    got_d, got_m = np.asarray(got_d), np.asarray(got_m)
+    assert got_m.shape == want_m.shape
+    assert np.allclose(got_m, want_m, rtol=2e-4, atol=1e-5), np.abs(got_m - want_m).max()
+    assert np.allclose(got_d, want_d, rtol=2e-4, atol=1e-5)
+    assert np.allclose(got_m.sum(axis=-1), tokens[s], rtol=1e-4)
+    return got_d
+
+
+@pytest.mark.parametrize("flags", [dict(), dict(layout=amskv.AMSKV_LAYOUT_PLANNED, borrow_unretained=True, fuse_append=True)],
+                         ids=["compact", "planned_borrow_fuse"])
+@pytest.mark.parametrize("D", [64, 128])
+def test_density_scale_window(D, flags):
+    B, H = 2, 3
+    tokens = [x * x for x in VAR]
+    pols = [(2, 2, False), (0, 0, True), (1, 0, False)]
+    q, k, v = inp.correlated_qkv(VAR, B, H, D, "bf16", inp.layer_seed(8, D), 0.7)
+    k_all = np.concatenate([_f64(x) for x in k], axis=-2)
+    qd, kd, vd = ([x.cuda() for x in t] for t in (q, k, v))
+    kw = dict(flags)
+    layout = kw.pop("layout", amskv.AMSKV_LAYOUT_COMPACT)
+    need = amskv.amskv_cache_required_bytes(len(pols), H, D, VAR, VAR, B, BF16, pols, 0.0, layout, **kw)
+    arena = torch.empty(need, dtype=torch.uint8, device="cuda")
+    arena.fill_(0xFF)
+    h = amskv.amskv_cache_create(len(pols), H, D, VAR, VAR, B, BF16, pols, 0.0, layout, arena=arena, **kw)
+    try:
+        for s in range(len(VAR)):
+            for l, pol in enumerate(pols):
+                amskv.amskv_append_scale(h, l, s, kd[s], vd[s])
+                assert [x[0] for x in amskv.amskv_cache_segments(h, l)] == orc.kept_scales(pol, s)
+                _check(h, l, s, tokens, qd[s], k_all, H)           # before the attention of the step ...
+                o = torch.empty_like(qd[s])
+                amskv.amskv_attend(h, l, s, qd[s], o)
+                if s in (4, 9):
+                    _check(h, l, s, tokens, qd[s], k_all, H)       # ... and after it (fused append has filled the slot)
+    finally:
+        amskv.amskv_cache_destroy(h)
+
+
+def test_density_token_budget_partial_groups():
+    sides = (6, 3, 4, 5, 2, 7)
+    tokens = [x * x for x in sides]
+    B, H, D = 2, 2, 64
+    q, k, v = inp.correlated_qkv(sides, B, H, D, "bf16", inp.layer_seed(8, 1), 0.6)
+    k_all = np.concatenate([_f64(x) for x in k], axis=-2)
+    qd, kd, vd = ([x.cuda() for x in t] for t in (q, k, v))
+    budgets = [(40, 40, 10, -2.0), (30, 60, 20, 2.0)]   # the first keeps head and tail of the 6x6 scale apart
+    need = amskv.amskv_cache_required_bytes(2, H, D, sides, sides, B, BF16, None, 0.3, budgets=budgets)
+    arena = torch.empty(need, dtype=torch.uint8, device="cuda")
+    h = amskv.amskv_cache_create(2, H, D, sides, sides, B, BF16, None, 0.3, arena=arena, budgets=budgets)
+    try:
+        split = False
+        for s in range(len(sides)):
+            for l in range(2):
+                amskv.amskv_append_scale(h, l, s, kd[s], vd[s])
+                segs = amskv.amskv_cache_segments(h, l)
+                split |= len({x[0] for x in segs}) < len(segs)     # one scale present as head and tail
+                _check(h, l, s, tokens, qd[s], k_all, H, 0.3)
+                o = torch.empty_like(qd[s])
+                amskv.amskv_attend(h, l, s, qd[s], o)
+                with pytest.raises(amskv.AmskvError) as e:          # the step's trim has run: no longer the step's view
+                    amskv.amskv_attention_density(h, l, s, qd[s], H)
+                assert e.value.status == amskv.AMSKV_ERR_ORDER
+        assert split
+    finally:
+        amskv.amskv_cache_destroy(h)
+
+
+def test_density_uniform_queries_and_errors():
+    # all-zero queries attend uniformly: every visible token receives T_s / T_kv, whatever the keys
+    B, H, D = 1, 4, 64
+    tokens = [x * x for x in VAR]
+    q, k, v = inp.iid_qkv(VAR, B, H, D, "bf16", inp.layer_seed(8, 2))
+    qd, kd, vd = ([x.cuda() for x in t] for t in (q, k, v))
+    pol = (2, 1, False)
+    need = amskv.amskv_cache_required_bytes(1, H, D, VAR, VAR, B, BF16, [pol])
+    arena = torch.empty(need, dtype=torch.uint8, device="cuda")
+    h = amskv.amskv_cache_create(1, H, D, VAR, VAR, B, BF16, [pol], arena=arena)
+    try:
+        for s in range(len(VAR)):
+            amskv.amskv_append_scale(h, 0, s, kd[s], vd[s])
+        s = len(VAR) - 1
+        dens, mass = amskv.amskv_attention_density(h, 0, s, torch.zeros_like(qd[s]), H)
+        t_kv = orc.kept_token_count(tokens, pol, s)
+        assert np.allclose(np.asarray(dens), tokens[s] / t_kv, rtol=1e-5)
+        with pytest.raises(amskv.AmskvError) as e:
+            amskv.amskv_attention_density(h, 0, s - 1, qd[s - 1], H)
+        assert e.value.status == amskv.AMSKV_ERR_ORDER
+    finally:
+        amskv.amskv_cache_destroy(h)
+    # fp32 caches are not covered
+    need = amskv.amskv_cache_required_bytes(1, H, D, (1, 2), (1, 2), B, amskv.AMSKV_DTYPE_F32, [pol])
+    arena = torch.empty(need, dtype=torch.uint8, device="cuda")
+    h = amskv.amskv_cache_create(1, H, D, (1, 2), (1, 2), B, amskv.AMSKV_DTYPE_F32, [pol], arena=arena)
+    try:
+        x = torch.zeros(B, H, 1, D, device="cuda")
+        amskv.amskv_append_scale(h, 0, 0, x, x)
+        with pytest.raises(amskv.AmskvError) as e:
+            amskv.amskv_attention_density(h, 0, 0, x, H)
+        assert e.value.status == amskv.AMSKV_ERR_INVALID_ARG
+    finally:
+        amskv.amskv_cache_destroy(h)
