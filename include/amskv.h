@@ -18,7 +18,7 @@
  *
  * Tensor layouts (all row-major, contiguous):
  *   Q, K, V, O of scale s : [B][H][T_s][D],  T_s = side_h[s]*side_w[s], tokens of a scale
- *                           in row-major grid order
+ *                           in row-major grid order (or token-major, amskv_cache_set_io_layout)
  *   cache of layer l      : K[B][H][cap_l][D] followed by V[B][H][cap_l][D] inside the
  *                           arena; the kept scales sit back to back in ascending scale
  *                           order (AMSKV_LAYOUT_COMPACT) or at offsets fixed at create
@@ -50,6 +50,7 @@ typedef enum {
 enum { AMSKV_DTYPE_F32 = 0, AMSKV_DTYPE_BF16 = 1 };
 enum { AMSKV_LAYOUT_COMPACT = 0, AMSKV_LAYOUT_PLANNED = 1 };
 enum { AMSKV_MODE_SCALE_WINDOW = 0, AMSKV_MODE_TOKEN_BUDGET = 1 };
+enum { AMSKV_IO_HEAD_MAJOR = 0, AMSKV_IO_TOKEN_MAJOR = 1 };
 enum { AMSKV_MAX_SCALES = 16 };
 
 typedef struct amskv_cache amskv_cache; /* opaque, host memory, owned by the library */
@@ -155,6 +156,21 @@ int32_t amskv_cache_required_bytes(int32_t layers, int32_t heads, int32_t head_d
 int32_t amskv_cache_create(int32_t layers, int32_t heads, int32_t head_dim,
                            const amskv_schedule* schedule, const amskv_policy* policy,
                            void* arena_dev, uint64_t arena_bytes, amskv_cache** out);
+
+/* Layout of the caller's per-scale tensors Q, K, V and O (Section 3.1's attention sits between
+ * the QKV projection and the output projection, whose activations are token-major).
+ *   AMSKV_IO_HEAD_MAJOR (default)  every tensor is [B][H][T_s][D], contiguous
+ *   AMSKV_IO_TOKEN_MAJOR           element (b, t, h, d) of a tensor sits at
+ *                                  base + ((b*T_s + t) * token_stride + h*D + d) elements
+ * with one token stride for Q, one for K and V, one for O (elements; each >= H*D and a multiple
+ * of 16 bytes).  A fused projection output [B][T_s][3][H][D] is passed without any copy as
+ * Q_dev = p, K_dev = p + H*D, V_dev = p + 2*H*D with q and kv strides 3*H*D; O in [B][T_s][H*D]
+ * has stride H*D.  The cache itself stays [B][H][cap][D] per layer, and amskv_cache_export
+ * writes head-major.  All device pointers must be 16-byte aligned in either layout.
+ * Allowed only while no scale has been appended to any layer (after create or reset), else
+ * AMSKV_ERR_ORDER.  Host only. */
+int32_t amskv_cache_set_io_layout(amskv_cache* cache, int32_t io_layout, int64_t q_token_stride,
+                                  int64_t kv_token_stride, int64_t o_token_stride);
 
 /* Append scale s to layer `layer` (Algorithm 1's append + rolling step, Algorithm 2's
  * eviction at scale granularity): scales that fall outside the policy are evicted, the

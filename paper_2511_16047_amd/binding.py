@@ -24,6 +24,7 @@ AMSKV_ERR_NO_DEVICE_MEMORY = -6
 AMSKV_DTYPE_F32, AMSKV_DTYPE_BF16 = 0, 1
 AMSKV_LAYOUT_COMPACT, AMSKV_LAYOUT_PLANNED = 0, 1
 AMSKV_MODE_SCALE_WINDOW, AMSKV_MODE_TOKEN_BUDGET = 0, 1
+AMSKV_IO_HEAD_MAJOR, AMSKV_IO_TOKEN_MAJOR = 0, 1
 AMSKV_MAX_SCALES = 16
 _MAX_SEGMENTS = AMSKV_MAX_SCALES + 2
 
@@ -33,6 +34,7 @@ EXPORTED = [
     "amskv_cache_bytes_held", "amskv_cache_capacity_tokens", "amskv_cache_export",
     "amskv_cache_reset", "amskv_cache_destroy", "amskv_status_string",
     "amskv_cache_segments", "amskv_cache_budget_tokens", "amskv_cache_settle", "amskv_attention_density",
+    "amskv_cache_set_io_layout",
 ]
 
 
@@ -113,6 +115,8 @@ def load_library() -> C.CDLL:
     lib.amskv_cache_settle.restype = i32
     lib.amskv_attention_density.argtypes = [vp, i32, i32, vp, pf, pf, C.POINTER(i32), vp]
     lib.amskv_attention_density.restype = i32
+    lib.amskv_cache_set_io_layout.argtypes = [vp, i32, i64, i64, i64]
+    lib.amskv_cache_set_io_layout.restype = i32
     _lib = lib
     return lib
 
@@ -276,6 +280,11 @@ def amskv_cache_capacity_tokens(cache, layer) -> int:
 def amskv_cache_export(cache, layer, K_out=None, V_out=None, stream=None):
     _check(load_library().amskv_cache_export(cache, layer, _ptr(K_out), _ptr(V_out), _stream(stream)),
            "amskv_cache_export")
+
+
+def amskv_cache_set_io_layout(cache, io_layout, q_token_stride=0, kv_token_stride=0, o_token_stride=0):
+    _check(load_library().amskv_cache_set_io_layout(cache, int(io_layout), int(q_token_stride), int(kv_token_stride),
+                                                    int(o_token_stride)), "amskv_cache_set_io_layout")
 
 
 def amskv_cache_reset(cache):

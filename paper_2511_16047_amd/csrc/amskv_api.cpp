@@ -12,8 +12,10 @@
 
 namespace {
 
+using amskv::CallerIo;
 using amskv::ExtKV;
 using amskv::MoveList;
+using amskv::RowMap;
 using amskv::ScaleRef;
 using amskv::SegTable;
 
@@ -54,6 +56,8 @@ struct amskv_cache {
   uint64_t arena_bytes = 0;
   uint64_t ws_off = 0;    // similarity workspace
   uint64_t dens_off = 0;  // attention-density workspace
+  int32_t io_layout = AMSKV_IO_HEAD_MAJOR;
+  int64_t q_tok = 0, kv_tok = 0, o_tok = 0;  // token strides in elements (token-major tensors only)
   std::vector<LayerState> layer;
 };
 
@@ -215,6 +219,22 @@ void build_plan(int32_t layers, int32_t heads, int32_t head_dim, const amskv_sch
   pl->total = at;
 }
 
+// Rows of a tensor of the caller's that holds t tokens per (b,h): head-major [B][H][t][D], or
+// token-major [B][t][..] with `tok_stride` elements from one token to the next.
+inline RowMap caller_map(const amskv_cache* c, int64_t t, int64_t tok_stride) {
+  const int64_t row = (int64_t)c->head_dim * c->elem_bytes;
+  if (c->io_layout == AMSKV_IO_HEAD_MAJOR) return RowMap{c->heads * t * row, t * row, row};
+  return RowMap{t * tok_stride * c->elem_bytes, row, tok_stride * c->elem_bytes};
+}
+
+// Rows of a layer's K (or V) region: [B][H][cap][D].
+inline RowMap arena_map(const amskv_cache* c, const LayerState& L) {
+  const int64_t row = (int64_t)c->head_dim * c->elem_bytes;
+  return RowMap{c->heads * L.cap * row, L.cap * row, row};
+}
+
+inline bool misaligned(const void* p) { return ((uintptr_t)p & 15) != 0; }
+
 inline bool bad_layer(const amskv_cache* c, int32_t layer) {
   return !c || layer < 0 || layer >= c->layers;
 }
@@ -272,12 +292,12 @@ int similarity_sums(amskv_cache* c, const LayerState& L, const Segment& cur, con
     if (g.off < 0 || g.pending) {
       r.k = g.ext_k;
       r.v = want_v ? g.ext_v : nullptr;
-      r.stride_tokens = g.len;
+      r.map = caller_map(c, g.len, c->kv_tok);
       r.off_tokens = 0;
     } else {
       r.k = c->arena + L.k_off;
       r.v = want_v ? c->arena + L.v_off : nullptr;
-      r.stride_tokens = L.cap;
+      r.map = arena_map(c, L);
       r.off_tokens = g.off;
     }
     return r;
@@ -407,14 +427,15 @@ int roll_budget(amskv_cache* c, LayerState& L, hipStream_t st) {
     char* kc = c->arena + L.k_off;
     char* vc = c->arena + L.v_off;
     if (mv.n > 0) {
-      hipError_t e = amskv::launch_append(kc, vc, nullptr, nullptr, bh, row_bytes, L.cap, mv, 0, 0, 0, 0, st);
+      hipError_t e = amskv::launch_append(kc, vc, nullptr, nullptr, bh, row_bytes, L.cap, mv, 0, 0, 0, RowMap{0, 0, 0},
+                                          c->heads, st);
       if (e != hipSuccess) return AMSKV_ERR_HIP;
     }
     MoveList none;
     std::memset(&none, 0, sizeof(none));
     for (const CopyRange& r : copies) {
       hipError_t e = amskv::launch_append(kc, vc, cur.ext_k, cur.ext_v, bh, row_bytes, L.cap, none, r.len, r.dst,
-                                          r.src_first, t_new, st);
+                                          r.src_first, caller_map(c, t_new, c->kv_tok), c->heads, st);
       if (e != hipSuccess) return AMSKV_ERR_HIP;
     }
   }
@@ -435,7 +456,7 @@ int flush_pending(amskv_cache* c, LayerState& L, hipStream_t st) {
       MoveList none;
       std::memset(&none, 0, sizeof(none));
       hipError_t e = amskv::launch_append(c->arena + L.k_off, c->arena + L.v_off, g.ext_k, g.ext_v, bh, row_bytes,
-                                          L.cap, none, g.len, g.off, 0, g.len, st);
+                                          L.cap, none, g.len, g.off, 0, caller_map(c, g.len, c->kv_tok), c->heads, st);
       if (e != hipSuccess) return AMSKV_ERR_HIP;
     }
     g.pending = false;
@@ -531,7 +552,7 @@ int32_t amskv_cache_create(int32_t layers, int32_t heads, int32_t head_dim,
 int32_t amskv_append_scale(amskv_cache* c, int32_t layer, int32_t s, const void* K_dev,
                            const void* V_dev, void* stream) {
   if (bad_layer(c, layer) || s < 0 || s >= c->n_scales) return AMSKV_ERR_INVALID_ARG;
-  if ((K_dev == nullptr) != (V_dev == nullptr)) return AMSKV_ERR_INVALID_ARG;
+  if ((K_dev == nullptr) != (V_dev == nullptr) || misaligned(K_dev) || misaligned(V_dev)) return AMSKV_ERR_INVALID_ARG;
   LayerState& L = c->layer[layer];
   if (s != L.last_scale + 1) return AMSKV_ERR_ORDER;
   if (K_dev && !c->arena) return AMSKV_ERR_NO_DEVICE_MEMORY;
@@ -606,7 +627,8 @@ int32_t amskv_append_scale(amskv_cache* c, int32_t layer, int32_t s, const void*
   if (K_dev && (copy_now || mv.n > 0)) {
     hipError_t e = amskv::launch_append(c->arena + L.k_off, c->arena + L.v_off, copy_now ? K_dev : nullptr,
                                         copy_now ? V_dev : nullptr, bh, row_bytes, L.cap, mv, cur.len,
-                                        copy_now ? cur.off : 0, 0, cur.len, (hipStream_t)stream);
+                                        copy_now ? cur.off : 0, 0, caller_map(c, cur.len, c->kv_tok), c->heads,
+                                        (hipStream_t)stream);
     if (e != hipSuccess) return AMSKV_ERR_HIP;
   }
   L.segs.swap(next);
@@ -617,7 +639,7 @@ int32_t amskv_append_scale(amskv_cache* c, int32_t layer, int32_t s, const void*
 
 int32_t amskv_attend(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev, void* O_dev,
                      void* stream) {
-  if (bad_layer(c, layer) || s < 0 || s >= c->n_scales || !Q_dev || !O_dev)
+  if (bad_layer(c, layer) || s < 0 || s >= c->n_scales || !Q_dev || !O_dev || misaligned(Q_dev) || misaligned(O_dev))
     return AMSKV_ERR_INVALID_ARG;
   LayerState& L = c->layer[layer];
   if (s != L.last_scale) return AMSKV_ERR_ORDER;
@@ -630,14 +652,17 @@ int32_t amskv_attend(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev
   Segment& newest = L.segs.back();
   if (newest.pending) ext.wb_off = newest.off;  // fused append: this launch also fills the slot
   const int bh = c->batch * c->heads;
+  // the scale read in place, if any, is the newest one
+  const CallerIo io{caller_map(c, c->tokens[s], c->q_tok), caller_map(c, c->tokens[s], c->o_tok),
+                    caller_map(c, newest.len, c->kv_tok), c->heads};
   hipError_t e;
   if (c->dtype == AMSKV_DTYPE_BF16)
     e = amskv::launch_attend_bf16(Q_dev, O_dev, c->arena + L.k_off, c->arena + L.v_off, bh,
-                                  c->tokens[s], c->head_dim, L.cap, t, ext, c->softmax_scale,
+                                  c->tokens[s], c->head_dim, L.cap, t, ext, io, c->softmax_scale,
                                   (hipStream_t)stream);
   else
     e = amskv::launch_attend_f32(Q_dev, O_dev, c->arena + L.k_off, c->arena + L.v_off, bh,
-                                 c->tokens[s], c->head_dim, L.cap, t, ext, c->softmax_scale,
+                                 c->tokens[s], c->head_dim, L.cap, t, ext, io, c->softmax_scale,
                                  (hipStream_t)stream);
   if (e != hipSuccess) return AMSKV_ERR_HIP;
   if (newest.pending) {  // from here on (in stream order) the slot holds the scale
@@ -681,7 +706,7 @@ int32_t amskv_interscale_similarity(amskv_cache* c, int32_t layer, int32_t s, fl
 
 int32_t amskv_attention_density(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev, float* density_host,
                                 float* mass_host, int32_t* n_seg, void* stream) {
-  if (bad_layer(c, layer) || s < 0 || s >= c->n_scales || !Q_dev || (!density_host && !mass_host))
+  if (bad_layer(c, layer) || s < 0 || s >= c->n_scales || !Q_dev || misaligned(Q_dev) || (!density_host && !mass_host))
     return AMSKV_ERR_INVALID_ARG;
   if (c->dtype != AMSKV_DTYPE_BF16) return AMSKV_ERR_INVALID_ARG;
   LayerState& L = c->layer[layer];
@@ -697,8 +722,10 @@ int32_t amskv_attention_density(amskv_cache* c, int32_t layer, int32_t s, const 
   float* partial = (float*)(c->arena + c->dens_off);
   float* totals = partial + (uint64_t)c->batch * c->heads * n_qblk * AMSKV_MAX_SCALES;
   hipStream_t st = (hipStream_t)stream;
+  const CallerIo io{caller_map(c, c->tokens[s], c->q_tok), RowMap{0, 0, 0}, caller_map(c, L.segs.back().len, c->kv_tok),
+                    c->heads};
   hipError_t e = amskv::launch_density(Q_dev, c->arena + L.k_off, c->batch, c->heads, c->tokens[s], c->head_dim, L.cap,
-                                       t, ext, c->softmax_scale, partial, totals, st);
+                                       t, ext, io, c->softmax_scale, partial, totals, st);
   if (e != hipSuccess) return AMSKV_ERR_HIP;
   std::vector<float> host((size_t)c->heads * AMSKV_MAX_SCALES);
   e = hipMemcpyAsync(host.data(), totals, host.size() * sizeof(float), hipMemcpyDeviceToHost, st);
@@ -790,8 +817,27 @@ int32_t amskv_cache_export(const amskv_cache* c, int32_t layer, void* K_out_dev,
   if (t.ext_start < t.total && !ext.k) return AMSKV_ERR_NO_DEVICE_MEMORY;
   hipError_t e = amskv::launch_export(c->arena + L.k_off, c->arena + L.v_off, K_out_dev, V_out_dev,
                                       c->batch * c->heads, c->head_dim * c->elem_bytes, L.cap, t, ext,
-                                      (hipStream_t)stream);
+                                      caller_map(c, L.segs.back().len, c->kv_tok), c->heads, (hipStream_t)stream);
   return e == hipSuccess ? AMSKV_OK : AMSKV_ERR_HIP;
+}
+
+int32_t amskv_cache_set_io_layout(amskv_cache* c, int32_t io_layout, int64_t q_token_stride, int64_t kv_token_stride,
+                                  int64_t o_token_stride) {
+  if (!c || (io_layout != AMSKV_IO_HEAD_MAJOR && io_layout != AMSKV_IO_TOKEN_MAJOR)) return AMSKV_ERR_INVALID_ARG;
+  for (const LayerState& L : c->layer)
+    if (L.last_scale >= 0) return AMSKV_ERR_ORDER;  // recorded K/V pointers would change meaning
+  if (io_layout == AMSKV_IO_TOKEN_MAJOR) {
+    const int64_t width = (int64_t)c->heads * c->head_dim, per16 = 16 / c->elem_bytes;
+    for (int64_t st : {q_token_stride, kv_token_stride, o_token_stride})
+      if (st < width || st % per16 != 0 || st > ((int64_t)1 << 40)) return AMSKV_ERR_INVALID_ARG;
+    c->q_tok = q_token_stride;
+    c->kv_tok = kv_token_stride;
+    c->o_tok = o_token_stride;
+  } else {
+    c->q_tok = c->kv_tok = c->o_tok = 0;
+  }
+  c->io_layout = io_layout;
+  return AMSKV_OK;
 }
 
 int32_t amskv_cache_reset(amskv_cache* c) {

@@ -23,13 +23,29 @@ struct SegTable {
   int32_t len[AMSKV_MAX_SCALES];
 };
 
-// External (borrowed) K and V of the current scale: [BH][ext_len][row], or null pointers.
+// External (borrowed) K and V of the current scale in the caller's buffers (rows located by
+// CallerIo::kv), or null pointers.
 // wb_off >= 0 asks the attention kernel to also write the scale it streams from k/v into the
 // layer's K/V regions at that token offset (the append fused into the attention of its step).
 struct ExtKV {
   const void* k;
   const void* v;
   int32_t wb_off;
+};
+
+// Where the rows of a tensor owned by the caller sit: row t of unit (b, h) starts, in bytes from
+// the tensor's base, at b*batch + h*head + t*tok (the D channels of a row are contiguous).
+// Head-major [B][H][T][D] gives {H*T*D, T*D, D} * element size; token-major [B][T][..H*D..] with a
+// token stride of `tok` elements gives {T*tok, D, tok} * element size.
+struct RowMap {
+  int64_t batch, head, tok;
+};
+
+// Maps of the tensors one attention call touches besides the cache: Q, O and the current scale's
+// own K/V when it is read in place (ExtKV); `heads` splits the unit index bh into (b, h).
+struct CallerIo {
+  RowMap q, o, kv;
+  int32_t heads;
 };
 
 // Token ranges that slide toward lower offsets when scales are evicted (COMPACT layout),
@@ -42,6 +58,12 @@ struct MoveList {
 };
 
 #if defined(__HIPCC__)
+// Byte offset of row 0 of unit bh = b*heads + h inside a caller tensor.
+__device__ __forceinline__ long long unit_offset(const RowMap& m, long long bh, int heads) {
+  const long long b = bh / heads;
+  return b * m.batch + (bh - b * heads) * m.head;
+}
+
 // Virtual row j of K~/V~ -> row index inside the layer's cache region of this (b,h), or, for a
 // row of the borrowed segment, row index inside the external tensor of this (b,h) (ext = true).
 __device__ __forceinline__ int locate_row(const SegTable& seg, int j, bool& ext) {
@@ -60,27 +82,29 @@ __device__ __forceinline__ int locate_row(const SegTable& seg, int j, bool& ext)
 // kc/vc are written only when ext.wb_off >= 0 (fused append)
 hipError_t launch_attend_bf16(const void* q, void* o, void* kc, void* vc, int bh,
                               int t_q, int head_dim, int64_t cap_tokens, const SegTable& seg,
-                              const ExtKV& ext, float softmax_scale, hipStream_t st);
+                              const ExtKV& ext, const CallerIo& io, float softmax_scale, hipStream_t st);
 hipError_t launch_attend_bf16_small(const void* q, void* o, void* kc, void* vc, int bh,
                                     int t_q, int head_dim, int64_t cap_tokens, const SegTable& seg,
-                                    const ExtKV& ext, float softmax_scale, hipStream_t st);
+                                    const ExtKV& ext, const CallerIo& io, float softmax_scale, hipStream_t st);
 hipError_t launch_attend_f32(const void* q, void* o, void* kc, void* vc, int bh,
                              int t_q, int head_dim, int64_t cap_tokens, const SegTable& seg,
-                             const ExtKV& ext, float softmax_scale, hipStream_t st);
+                             const ExtKV& ext, const CallerIo& io, float softmax_scale, hipStream_t st);
 // k_new == nullptr: compaction only (the new scale is borrowed, nothing to copy); otherwise tokens
-// [src_first, src_first + t_new) of the new scale ([BH][src_stride][row]) go to offset dst_new
+// [src_first, src_first + t_new) of the new scale (rows located by src_map) go to offset dst_new
 hipError_t launch_append(void* kc, void* vc, const void* k_new, const void* v_new, int bh,
                          int row_bytes, int64_t cap_tokens, const MoveList& mv, int t_new,
-                         int dst_new, int src_first, int src_stride, hipStream_t st);
+                         int dst_new, int src_first, const RowMap& src_map, int heads, hipStream_t st);
+// k_out/v_out are head-major [BH][T_kept][row]; ext_map locates the rows of a borrowed scale
 hipError_t launch_export(const void* kc, const void* vc, void* k_out, void* v_out, int bh,
                          int row_bytes, int64_t cap_tokens, const SegTable& seg, const ExtKV& ext,
-                         hipStream_t st);
-// cur_k/cur_v, prev_k/prev_v: base of the tensor holding the scale ([BH][stride tokens][row]),
-// token offset of the scale inside each (b,h) row; v pointers may be null (keys only)
+                         const RowMap& ext_map, int heads, hipStream_t st);
+// A whole scale, wherever it lives: base pointers of the tensor holding it (the layer's cache
+// regions or the caller's K/V), the map of that tensor's rows, and the token offset of the scale
+// inside each (b,h) row range; v may be null (keys only)
 struct ScaleRef {
   const void* k;
   const void* v;
-  int64_t stride_tokens;
+  RowMap map;
   int32_t off_tokens;
 };
 hipError_t launch_similarity(const ScaleRef& cur, const ScaleRef& prev, int batch, int heads,
@@ -90,7 +114,7 @@ hipError_t launch_similarity(const ScaleRef& cur, const ScaleRef& prev, int batc
 // attention density: pieces = one table entry per group of keys (nothing merged); partial_ws holds
 // batch*heads*ceil(t_q/32)*AMSKV_MAX_SCALES floats, out_dev heads*AMSKV_MAX_SCALES floats; bf16 only
 hipError_t launch_density(const void* q, const void* kc, int batch, int heads, int t_q, int head_dim,
-                          int64_t cap_tokens, const SegTable& pieces, const ExtKV& ext, float softmax_scale,
-                          float* partial_ws, float* out_dev, hipStream_t st);
+                          int64_t cap_tokens, const SegTable& pieces, const ExtKV& ext, const CallerIo& io,
+                          float softmax_scale, float* partial_ws, float* out_dev, hipStream_t st);
 
 }  // namespace amskv

@@ -85,6 +85,13 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
   return r;
 }
 
+// The compiler tracks the wait states a matrix instruction needs before an ordinary vector
+// instruction may read its result, but not for a read from inside inline assembly (max3 above).
+// Called on the accumulator between the two, this holds the wave for the 11 wait states that an
+// 8-pass v_mfma_f32_32x32x16_bf16 requires (one to spare); taking the accumulator as an in/out operand pins
+// it after the matrix instructions and before every later use.
+__device__ __forceinline__ void settle_mfma(f32x16& acc) { asm volatile("s_nop 11" : "+v"(acc)); }
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
@@ -100,8 +107,9 @@ struct TileLoader {
   static_assert(kLoadsPerWave >= 1 && kLoadsPerWave * kRowsPerLoad * kWaves == kTileKeys, "tile/wave split");
 
   // Issue the loads of tile rows j0..j0+kTileKeys-1 of the virtual concatenation into one ring slot.
-  __device__ static __forceinline__ void issue(const char* kb, const char* vb, const char* xk, const char* xv, char* lds_k, char* lds_v, int j0,
-                                               int t_kv, const SegTable& seg, int wave, int lane) {
+  // x_tok: byte stride between the rows of the borrowed scale in the caller's tensors.
+  __device__ static __forceinline__ void issue(const char* kb, const char* vb, const char* xk, const char* xv, long long x_tok,
+                                               char* lds_k, char* lds_v, int j0, int t_kv, const SegTable& seg, int wave, int lane) {
 #pragma unroll
     for (int i = 0; i < kLoadsPerWave; ++i) {
       const int blk = wave * kLoadsPerWave + i;  // which 1 KB block of the tile
@@ -109,7 +117,7 @@ struct TileLoader {
       const int cpos = lane % CPR;
       bool ext;
       const int row_at = locate_row(seg, min(j0 + row, t_kv - 1), ext);
-      const long long off = (long long)row_at * RB + 16 * (cpos ^ (row & 7));
+      const long long off = (long long)row_at * (ext ? x_tok : (long long)RB) + 16 * (cpos ^ (row & 7));
       lds_dma16((ext ? xk : kb) + off, lds_k + blk * 1024);
       lds_dma16((ext ? xv : vb) + off, lds_v + blk * 1024);
     }
@@ -141,7 +149,7 @@ struct TileLoader {
 template <int D, int NQ, int kWaves, int kTileKeys, int kMinWavesPerSimd>
 __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_kernel(
     const __bf16* __restrict__ q, __bf16* __restrict__ o, char* __restrict__ kc, char* __restrict__ vc,
-    int t_q, long long cap_tokens, SegTable seg, ExtKV ext_kv, float scale_log2e, int n_bh, int n_qtiles) {
+    int t_q, long long cap_tokens, SegTable seg, ExtKV ext_kv, CallerIo io, float scale_log2e, int n_bh, int n_qtiles) {
   using Loader = TileLoader<D, kWaves, kTileKeys>;
   constexpr int RB = D * 2;   // bytes per token row
   constexpr int KS = D / 16;  // K-steps of the first product
@@ -173,10 +181,12 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
   const int n_blocks = (t_kv + 31) / 32;
   char* kb = kc + bh * cap_tokens * RB;
   char* vb = vc + bh * cap_tokens * RB;
-  // the borrowed current scale, if any: [BH][T_s][D] in the caller's buffers
-  const long long ext_rows = bh * (long long)(seg.total - seg.ext_start);
-  const char* xk = (const char*)ext_kv.k + ext_rows * RB;
-  const char* xv = (const char*)ext_kv.v + ext_rows * RB;
+  // the borrowed current scale, if any, in the caller's buffers; Q and O rows of this (b,h)
+  const long long x_unit = unit_offset(io.kv, bh, io.heads);
+  const char* xk = (const char*)ext_kv.k + x_unit;
+  const char* xv = (const char*)ext_kv.v + x_unit;
+  const long long x_tok = io.kv.tok;
+  const char* q_unit = (const char*)q + unit_offset(io.q, bh, io.heads);
   // fused append: the workgroup of the first query tile also fills the current scale's slot
   const bool write_back = ext_kv.wb_off >= 0 && (within >> 3) == 0;
 
@@ -189,12 +199,12 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
   for (int n = 0; n < NQ; ++n) {
     const int row = min(q_base + 32 * n + r, t_q - 1);
 #pragma unroll
-    for (int t = 0; t < KS; ++t) qf[n][t] = *reinterpret_cast<const bf16x8*>(q + (bh * t_q + row) * D + 16 * t + 8 * h);
+    for (int t = 0; t < KS; ++t) qf[n][t] = *reinterpret_cast<const bf16x8*>(q_unit + row * io.q.tok + 32 * t + 16 * h);
   }
 #pragma unroll
   for (int st = 0; st < 2; ++st)
     if (st < n_tiles)
-      Loader::issue(kb, vb, xk, xv, lds_k + st * kTileBytes, lds_v + st * kTileBytes, st * kTileKeys, t_kv, seg, wave, lane);
+      Loader::issue(kb, vb, xk, xv, x_tok, lds_k + st * kTileBytes, lds_v + st * kTileBytes, st * kTileKeys, t_kv, seg, wave, lane);
 
 #pragma unroll
   for (int n = 0; n < NQ; ++n)
@@ -259,8 +269,8 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
                            it * kTileKeys, t_kv, seg, ext_kv.wb_off, wave, lane);
       if (it + 2 < n_tiles) {
         const int slot = (it + 2) % kStages;
-        Loader::issue(kb, vb, xk, xv, lds_k + slot * kTileBytes, lds_v + slot * kTileBytes, (it + 2) * kTileKeys, t_kv, seg,
-                      wave, lane);
+        Loader::issue(kb, vb, xk, xv, x_tok, lds_k + slot * kTileBytes, lds_v + slot * kTileBytes, (it + 2) * kTileKeys, t_kv,
+                      seg, wave, lane);
       }
     }
     if (!wave_active) return;
@@ -306,6 +316,7 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
     any_rescale = false;
 #pragma unroll
     for (int n = 0; n < NQ; ++n) {
+      settle_mfma(sacc[n]);
       float mx = max3(sacc[n][0], sacc[n][1], sacc[n][2]);
 #pragma unroll
       for (int v = 3; v < 15; v += 2) mx = max3(mx, sacc[n][v], sacc[n][v + 1]);
@@ -397,13 +408,14 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
   }
 
   // ---- O[row][d] = O^T[d][row] / l ; lane (r,h) holds d = 32*db + 8*(v/4) + 4h + v%4 of row r
+  char* o_unit = (char*)o + unit_offset(io.o, bh, io.heads);
 #pragma unroll
   for (int n = 0; n < NQ; ++n) {
     const float total = run_sum[n] + __shfl_xor(run_sum[n], 32, 64);
     const float inv = 1.0f / total;
     const int row = q_base + 32 * n + r;
     if (row < t_q) {
-      __bf16* dst = o + (bh * t_q + row) * D;
+      __bf16* dst = reinterpret_cast<__bf16*>(o_unit + row * io.o.tok);
 #pragma unroll
       for (int d = 0; d < DB; ++d)
 #pragma unroll
@@ -419,12 +431,12 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
 
 template <int D, int NQ, int kWaves, int kTileKeys, int kMinWavesPerSimd>
 hipError_t launch(const void* q, void* o, void* kc, void* vc, int bh, int t_q, int64_t cap_tokens,
-                  const SegTable& seg, const ExtKV& ext, float c, hipStream_t st) {
+                  const SegTable& seg, const ExtKV& ext, const CallerIo& io, float c, hipStream_t st) {
   constexpr int BM = kWaves * 32 * NQ;
   const int n_qtiles = (t_q + BM - 1) / BM;
   dim3 grid((unsigned)(((bh + 7) / 8) * 8 * n_qtiles)), block(64 * kWaves);
   hipLaunchKernelGGL((attend_bf16_kernel<D, NQ, kWaves, kTileKeys, kMinWavesPerSimd>), grid, block, 0, st,
-                     (const __bf16*)q, (__bf16*)o, (char*)kc, (char*)vc, t_q, (long long)cap_tokens, seg, ext, c,
+                     (const __bf16*)q, (__bf16*)o, (char*)kc, (char*)vc, t_q, (long long)cap_tokens, seg, ext, io, c,
                      bh, n_qtiles);
   return hipGetLastError();
 }
@@ -432,26 +444,26 @@ hipError_t launch(const void* q, void* o, void* kc, void* vc, int bh, int t_q, i
 }  // namespace
 
 hipError_t launch_attend_bf16(const void* q, void* o, void* kc, void* vc, int bh, int t_q,
-                              int head_dim, int64_t cap_tokens, const SegTable& seg, const ExtKV& ext, float softmax_scale,
-                              hipStream_t st) {
+                              int head_dim, int64_t cap_tokens, const SegTable& seg, const ExtKV& ext, const CallerIo& io,
+                              float softmax_scale, hipStream_t st) {
 #if defined(AMSKV_TUNE_ENV)
   static const int small_tq = getenv("AMSKV_SMALL_TQ") ? atoi(getenv("AMSKV_SMALL_TQ")) : kSmallTq;
 #else
   constexpr int small_tq = kSmallTq;
 #endif
   // coarse scales: latency-bound, one independent wave per 32 query rows
-  if (t_q <= small_tq) return launch_attend_bf16_small(q, o, kc, vc, bh, t_q, head_dim, cap_tokens, seg, ext, softmax_scale, st);
+  if (t_q <= small_tq) return launch_attend_bf16_small(q, o, kc, vc, bh, t_q, head_dim, cap_tokens, seg, ext, io, softmax_scale, st);
   const float c = softmax_scale * 1.4426950408889634f;
   const bool wide = t_q > 128;  // 256 query rows per workgroup keeps K/V single-pass up to T_q = 256
   if (head_dim == 64)
     // eight waves of 32 rows: ~110 registers per lane, so two workgroups (16 waves) share a CU
-    return wide ? launch<64, 1, 8, 64, 4>(q, o, kc, vc, bh, t_q, cap_tokens, seg, ext, c, st)
-                : launch<64, 1, 4, 32, 4>(q, o, kc, vc, bh, t_q, cap_tokens, seg, ext, c, st);
+    return wide ? launch<64, 1, 8, 64, 4>(q, o, kc, vc, bh, t_q, cap_tokens, seg, ext, io, c, st)
+                : launch<64, 1, 4, 32, 4>(q, o, kc, vc, bh, t_q, cap_tokens, seg, ext, io, c, st);
   // head dim 128: 32 query rows per wave keep the kernel at two waves per SIMD (two workgroups of
   // four waves per CU), which measured ~14 % faster than 64 rows per wave at one wave per SIMD on the 1024x1024 schedule; 32-key tiles
   // (16 KB per ring slot) leave room for several workgroups per CU
   (void)wide;
-  return launch<128, 1, 4, 32, 2>(q, o, kc, vc, bh, t_q, cap_tokens, seg, ext, c, st);
+  return launch<128, 1, 4, 32, 2>(q, o, kc, vc, bh, t_q, cap_tokens, seg, ext, io, c, st);
 }
 
 }  // namespace amskv

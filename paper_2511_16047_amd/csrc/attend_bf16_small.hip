@@ -37,12 +37,19 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
   return r;
 }
 
+// The compiler tracks the wait states a matrix instruction needs before an ordinary vector
+// instruction may read its result, but not for a read from inside inline assembly (max3 above).
+// Called on the accumulator between the two, this holds the wave for the 11 wait states that an
+// 8-pass v_mfma_f32_32x32x16_bf16 requires (one to spare); taking the accumulator as an in/out operand pins
+// it after the matrix instructions and before every later use.
+__device__ __forceinline__ void settle_mfma(f32x16& acc) { asm volatile("s_nop 11" : "+v"(acc)); }
+
 // Register budget: three waves per SIMD at head dim 64 and two at 128 are the most that fit without spilling;
 // every step up in resident waves measured faster on these latency-bound launches.
 template <int D>
 __global__ __launch_bounds__(64 * kWavesPerGroup, D == 64 ? 3 : 2) void attend_bf16_small_kernel(
     const __bf16* __restrict__ q, __bf16* __restrict__ o, char* __restrict__ kc, char* __restrict__ vc,
-    int t_q, long long cap_tokens, SegTable seg, ExtKV ext_kv, float scale_log2e, int n_qblk, int n_units) {
+    int t_q, long long cap_tokens, SegTable seg, ExtKV ext_kv, CallerIo io, float scale_log2e, int n_qblk, int n_units) {
   constexpr int RB = D * 2;
   constexpr int CPR = D / 8;
   constexpr int KS = D / 16;
@@ -62,9 +69,12 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, D == 64 ? 3 : 2) void attend_b
   const int n_blocks = (t_kv + 31) / 32;
   char* kb = kc + bh * cap_tokens * RB;
   char* vb = vc + bh * cap_tokens * RB;
-  const long long ext_rows = bh * (long long)(seg.total - seg.ext_start);  // borrowed current scale, if any
-  const char* xk = (const char*)ext_kv.k + ext_rows * RB;
-  const char* xv = (const char*)ext_kv.v + ext_rows * RB;
+  const long long x_unit = unit_offset(io.kv, bh, io.heads);  // borrowed current scale, if any
+  const char* xk = (const char*)ext_kv.k + x_unit;
+  const char* xv = (const char*)ext_kv.v + x_unit;
+  const long long x_tok = io.kv.tok;
+  const char* q_unit = (const char*)q + unit_offset(io.q, bh, io.heads);
+  char* o_unit = (char*)o + unit_offset(io.o, bh, io.heads);
   char* my_v = lds_v[wave];
   const bool write_back = ext_kv.wb_off >= 0 && q_base == 0;
 
@@ -72,7 +82,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, D == 64 ? 3 : 2) void attend_b
   {
     const int row = min(q_base + r, t_q - 1);
 #pragma unroll
-    for (int t = 0; t < KS; ++t) qf[t] = *reinterpret_cast<const bf16x8*>(q + (bh * t_q + row) * D + 16 * t + 8 * h);
+    for (int t = 0; t < KS; ++t) qf[t] = *reinterpret_cast<const bf16x8*>(q_unit + row * io.q.tok + 32 * t + 16 * h);
   }
 
   bf16x8 kf[KS];
@@ -80,16 +90,16 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, D == 64 ? 3 : 2) void attend_b
   auto load_block = [&](int g) {
     const int j0 = 32 * g;
     bool kext;
-    const long long krow = (long long)locate_row(seg, min(j0 + r, t_kv - 1), kext) * RB;
-    const char* kp = (kext ? xk : kb) + krow;
+    const long long krow = locate_row(seg, min(j0 + r, t_kv - 1), kext);
+    const char* kp = kext ? xk + krow * x_tok : kb + krow * RB;
 #pragma unroll
     for (int t = 0; t < KS; ++t) kf[t] = *reinterpret_cast<const bf16x8*>(kp + 32 * t + 16 * h);
 #pragma unroll
     for (int k = 0; k < VCH; ++k) {
       const int id = k * 64 + lane, row = id / CPR, c = id % CPR;
       bool vext;
-      const long long vrow = (long long)locate_row(seg, min(j0 + row, t_kv - 1), vext) * RB;
-      vch[k] = *reinterpret_cast<const u32x4*>((vext ? xv : vb) + vrow + 16 * c);
+      const long long vrow = locate_row(seg, min(j0 + row, t_kv - 1), vext);
+      vch[k] = *reinterpret_cast<const u32x4*>((vext ? xv + vrow * x_tok : vb + vrow * RB) + 16 * c);
     }
   };
   load_block(0);
@@ -139,6 +149,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, D == 64 ? 3 : 2) void attend_b
       for (int v = 0; v < 16; ++v)
         if (8 * (v >> 2) + 4 * h + (v & 3) >= valid) sacc[v] = -INFINITY;
     }
+    settle_mfma(sacc);
     float mx = max3(sacc[0], sacc[1], sacc[2]);
 #pragma unroll
     for (int v = 3; v < 15; v += 2) mx = max3(mx, sacc[v], sacc[v + 1]);
@@ -186,7 +197,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, D == 64 ? 3 : 2) void attend_b
   const float inv = 1.0f / total;
   const int row = q_base + r;
   if (row < t_q) {
-    __bf16* dst = o + (bh * t_q + row) * D;
+    __bf16* dst = reinterpret_cast<__bf16*>(o_unit + row * io.o.tok);
 #pragma unroll
     for (int d = 0; d < DB; ++d)
 #pragma unroll
@@ -203,18 +214,17 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, D == 64 ? 3 : 2) void attend_b
 
 hipError_t launch_attend_bf16_small(const void* q, void* o, void* kc, void* vc, int bh, int t_q,
                                     int head_dim, int64_t cap_tokens, const SegTable& seg, const ExtKV& ext,
-                                    float softmax_scale,
-                                    hipStream_t st) {
+                                    const CallerIo& io, float softmax_scale, hipStream_t st) {
   const float c = softmax_scale * 1.4426950408889634f;
   const int n_qblk = (t_q + 31) / 32;
   const long long n_units = (long long)bh * n_qblk;
   dim3 grid((unsigned)((n_units + kWavesPerGroup - 1) / kWavesPerGroup)), block(64 * kWavesPerGroup);
   if (head_dim == 64)
     hipLaunchKernelGGL(attend_bf16_small_kernel<64>, grid, block, 0, st, (const __bf16*)q, (__bf16*)o, (char*)kc,
-                       (char*)vc, t_q, (long long)cap_tokens, seg, ext, c, n_qblk, (int)n_units);
+                       (char*)vc, t_q, (long long)cap_tokens, seg, ext, io, c, n_qblk, (int)n_units);
   else
     hipLaunchKernelGGL(attend_bf16_small_kernel<128>, grid, block, 0, st, (const __bf16*)q, (__bf16*)o, (char*)kc,
-                       (char*)vc, t_q, (long long)cap_tokens, seg, ext, c, n_qblk, (int)n_units);
+                       (char*)vc, t_q, (long long)cap_tokens, seg, ext, io, c, n_qblk, (int)n_units);
   return hipGetLastError();
 }
 

@@ -18,7 +18,7 @@ __global__ __launch_bounds__(kThreads) void attend_f32_kernel(const float* __res
                                                               float* __restrict__ kc,
                                                               float* __restrict__ vc, int t_q,
                                                               long long cap_tokens, SegTable seg,
-                                                              ExtKV ext_kv, float scale_log2e) {
+                                                              ExtKV ext_kv, CallerIo io, float scale_log2e) {
   constexpr int M = D / 16;  // float4 pieces per lane
   __shared__ __align__(16) float lds_k[kTileKeys * D];
   __shared__ __align__(16) float lds_v[kTileKeys * D];
@@ -30,15 +30,17 @@ __global__ __launch_bounds__(kThreads) void attend_f32_kernel(const float* __res
   const bool row_ok = row < t_q;
   float* kb = kc + bh * cap_tokens * D;
   float* vb = vc + bh * cap_tokens * D;
-  const long long ext_rows = bh * (long long)(seg.total - seg.ext_start);  // borrowed current scale, if any
-  const float* xk = (const float*)ext_kv.k + ext_rows * D;
-  const float* xv = (const float*)ext_kv.v + ext_rows * D;
+  const long long x_unit = unit_offset(io.kv, bh, io.heads);  // borrowed current scale, if any
+  const char* xk = (const char*)ext_kv.k + x_unit;
+  const char* xv = (const char*)ext_kv.v + x_unit;
+  const char* q_row = (const char*)q + unit_offset(io.q, bh, io.heads) + (long long)row * io.q.tok;
+  char* o_row = (char*)o + unit_offset(io.o, bh, io.heads) + (long long)row * io.o.tok;
   const int t_kv = seg.total;
 
   float4 qv[M], acc[M];
 #pragma unroll
   for (int m = 0; m < M; ++m) {
-    qv[m] = row_ok ? *reinterpret_cast<const float4*>(q + (bh * t_q + row) * D + 16 * m + 4 * g)
+    qv[m] = row_ok ? *reinterpret_cast<const float4*>(q_row + 4 * (16 * m + 4 * g))
                    : make_float4(0.f, 0.f, 0.f, 0.f);
     acc[m] = make_float4(0.f, 0.f, 0.f, 0.f);
   }
@@ -53,9 +55,15 @@ __global__ __launch_bounds__(kThreads) void attend_f32_kernel(const float* __res
       float4 kk = make_float4(0.f, 0.f, 0.f, 0.f), vv = kk;
       if (j < t_kv) {
         bool ext;
-        const long long off = (long long)locate_row(seg, j, ext) * D + 4 * c;
-        kk = *reinterpret_cast<const float4*>((ext ? xk : kb) + off);
-        vv = *reinterpret_cast<const float4*>((ext ? xv : vb) + off);
+        const long long at = locate_row(seg, j, ext);
+        const long long off = at * D + 4 * c;
+        if (ext) {
+          kk = *reinterpret_cast<const float4*>(xk + at * io.kv.tok + 16 * c);
+          vv = *reinterpret_cast<const float4*>(xv + at * io.kv.tok + 16 * c);
+        } else {
+          kk = *reinterpret_cast<const float4*>(kb + off);
+          vv = *reinterpret_cast<const float4*>(vb + off);
+        }
         if (ext && ext_kv.wb_off >= 0 && blockIdx.y == 0) {  // fused append: fill the scale's slot while streaming it
           const long long dst = (long long)ext_kv.wb_off * D + off;
           *reinterpret_cast<float4*>(kb + dst) = kk;
@@ -112,7 +120,7 @@ __global__ __launch_bounds__(kThreads) void attend_f32_kernel(const float* __res
 #pragma unroll
     for (int m = 0; m < M; ++m) {
       float4 r = make_float4(acc[m].x * inv, acc[m].y * inv, acc[m].z * inv, acc[m].w * inv);
-      *reinterpret_cast<float4*>(o + (bh * t_q + row) * D + 16 * m + 4 * g) = r;
+      *reinterpret_cast<float4*>(o_row + 4 * (16 * m + 4 * g)) = r;
     }
   }
 }
@@ -121,15 +129,15 @@ __global__ __launch_bounds__(kThreads) void attend_f32_kernel(const float* __res
 
 hipError_t launch_attend_f32(const void* q, void* o, void* kc, void* vc, int bh, int t_q,
                              int head_dim, int64_t cap_tokens, const SegTable& seg, const ExtKV& ext,
-                             float softmax_scale, hipStream_t st) {
+                             const CallerIo& io, float softmax_scale, hipStream_t st) {
   const float c = softmax_scale * 1.4426950408889634f;
   dim3 grid(bh, (t_q + kRowsPerBlock - 1) / kRowsPerBlock), block(kThreads);
   if (head_dim == 64)
     hipLaunchKernelGGL(attend_f32_kernel<64>, grid, block, 0, st, (const float*)q, (float*)o, (float*)kc,
-                       (float*)vc, t_q, (long long)cap_tokens, seg, ext, c);
+                       (float*)vc, t_q, (long long)cap_tokens, seg, ext, io, c);
   else
     hipLaunchKernelGGL(attend_f32_kernel<128>, grid, block, 0, st, (const float*)q, (float*)o, (float*)kc,
-                       (float*)vc, t_q, (long long)cap_tokens, seg, ext, c);
+                       (float*)vc, t_q, (long long)cap_tokens, seg, ext, io, c);
   return hipGetLastError();
 }
 

@@ -60,17 +60,16 @@ __global__ __launch_bounds__(kThreads) void compact_kernel(char* __restrict__ kc
   }
 }
 
-// Append: copy t_new tokens of the new scale K_s, V_s ([BH][src_stride][row], starting at token
-// src_first of every (b,h) row) into their slot of every (b,h) row of the cache.  Flat over all
-// 16-byte chunks of both tensors, so a one-token scale and a 256-token scale both run full
-// workgroups; for a whole scale (src_first = 0, src_stride = t_new) the source side is one
-// contiguous stream.  The token-granular trim of Algorithm 2 keeps a scale in part, hence the range.
+// Append: copy t_new tokens of the new scale K_s, V_s (the caller's tensors, rows located by
+// src_map, starting at token src_first of every (b,h)) into their slot of every (b,h) row of the
+// cache.  Flat over all 16-byte chunks of both tensors, so a one-token scale and a 256-token scale
+// both run full workgroups; for a whole head-major scale the source side is one contiguous stream.  The token-granular trim of Algorithm 2 keeps a scale in part, hence the range.
 // Enqueued after compact_kernel: the slot may overlap the old position of a moved segment.
 __global__ __launch_bounds__(kThreads) void append_kernel(char* __restrict__ kc, char* __restrict__ vc,
                                                           const char* __restrict__ k_new,
                                                           const char* __restrict__ v_new, int row_bytes,
                                                           long long cap_tokens, int t_new, int dst_new,
-                                                          int src_first, int src_stride,
+                                                          int src_first, RowMap src_map, int heads,
                                                           long long chunks_per_tensor) {
   const int cpr = row_bytes >> 4;
   const int per_bh = t_new * cpr;  // chunks of one (b,h) row
@@ -88,7 +87,8 @@ __global__ __launch_bounds__(kThreads) void append_kernel(char* __restrict__ kc,
       const long long bh = c / per_bh;
       const int rem = (int)(c - bh * per_bh);
       dst_off[u] = (bh * cap_tokens + dst_new) * row_bytes + ((long long)rem << 4);
-      const long long so = ((bh * src_stride + src_first) * cpr + rem) << 4;
+      const int tok = rem / cpr;
+      const long long so = unit_offset(src_map, bh, heads) + (src_first + tok) * src_map.tok + ((rem - tok * cpr) << 4);
       buf[u] = *reinterpret_cast<const uint4*>((which[u] ? v_new : k_new) + so);
     }
   }
@@ -101,10 +101,11 @@ __global__ __launch_bounds__(kThreads) void append_kernel(char* __restrict__ kc,
 __global__ __launch_bounds__(kThreads) void export_kernel(const char* __restrict__ kc,
                                                           const char* __restrict__ vc, char* __restrict__ k_out,
                                                           char* __restrict__ v_out, int row_bytes,
-                                                          long long cap_tokens, SegTable seg, ExtKV ext_kv) {
+                                                          long long cap_tokens, SegTable seg, ExtKV ext_kv,
+                                                          RowMap ext_map, int heads) {
   const long long bh = blockIdx.x;
   const char* base = (blockIdx.y ? vc : kc) + bh * cap_tokens * row_bytes;
-  const char* xbase = (const char*)(blockIdx.y ? ext_kv.v : ext_kv.k) + bh * (long long)(seg.total - seg.ext_start) * row_bytes;
+  const char* xbase = (const char*)(blockIdx.y ? ext_kv.v : ext_kv.k) + unit_offset(ext_map, bh, heads);
   char* out = blockIdx.y ? v_out : k_out;
   if (!out) return;
   out += bh * (long long)seg.total * row_bytes;
@@ -113,8 +114,9 @@ __global__ __launch_bounds__(kThreads) void export_kernel(const char* __restrict
   for (int c = threadIdx.x; c < n; c += kThreads) {
     const int tok = c / cpr, piece = c - tok * cpr;
     bool ext;
-    const long long so = (long long)locate_row(seg, tok, ext) * row_bytes + (piece << 4);
-    *reinterpret_cast<uint4*>(out + ((long long)c << 4)) = *reinterpret_cast<const uint4*>((ext ? xbase : base) + so);
+    const long long at = locate_row(seg, tok, ext);
+    const char* src = ext ? xbase + at * ext_map.tok : base + at * row_bytes;
+    *reinterpret_cast<uint4*>(out + ((long long)c << 4)) = *reinterpret_cast<const uint4*>(src + (piece << 4));
   }
 }
 
@@ -122,7 +124,7 @@ __global__ __launch_bounds__(kThreads) void export_kernel(const char* __restrict
 
 hipError_t launch_append(void* kc, void* vc, const void* k_new, const void* v_new, int bh, int row_bytes,
                          int64_t cap_tokens, const MoveList& mv, int t_new, int dst_new, int src_first,
-                         int src_stride, hipStream_t st) {
+                         const RowMap& src_map, int heads, hipStream_t st) {
   if (mv.n > 0) {
     hipLaunchKernelGGL(compact_kernel, dim3(bh, 2), dim3(kThreads), 0, st, (char*)kc, (char*)vc, row_bytes,
                        (long long)cap_tokens, mv);
@@ -134,16 +136,17 @@ hipError_t launch_append(void* kc, void* vc, const void* k_new, const void* v_ne
   const long long per_block = (long long)kThreads * kUnroll;
   const unsigned grid = (unsigned)((2 * chunks + per_block - 1) / per_block);
   hipLaunchKernelGGL(append_kernel, dim3(grid), dim3(kThreads), 0, st, (char*)kc, (char*)vc, (const char*)k_new,
-                     (const char*)v_new, row_bytes, (long long)cap_tokens, t_new, dst_new, src_first, src_stride,
+                     (const char*)v_new, row_bytes, (long long)cap_tokens, t_new, dst_new, src_first, src_map, heads,
                      chunks);
   return hipGetLastError();
 }
 
 hipError_t launch_export(const void* kc, const void* vc, void* k_out, void* v_out, int bh, int row_bytes,
-                         int64_t cap_tokens, const SegTable& seg, const ExtKV& ext, hipStream_t st) {
+                         int64_t cap_tokens, const SegTable& seg, const ExtKV& ext, const RowMap& ext_map, int heads,
+                         hipStream_t st) {
   dim3 grid(bh, 2), block(kThreads);
   hipLaunchKernelGGL(export_kernel, grid, block, 0, st, (const char*)kc, (const char*)vc, (char*)k_out,
-                     (char*)v_out, row_bytes, (long long)cap_tokens, seg, ext);
+                     (char*)v_out, row_bytes, (long long)cap_tokens, seg, ext, ext_map, heads);
   return hipGetLastError();
 }
 

@@ -24,7 +24,7 @@ constexpr int kWavesPerGroup = 4;
 template <int D>
 __global__ __launch_bounds__(64 * kWavesPerGroup) void density_partial_kernel(
     const __bf16* __restrict__ q, const char* __restrict__ kc, int t_q, long long cap_tokens, SegTable seg,
-    ExtKV ext_kv, float scale_log2e, int n_qblk, int n_units, float* __restrict__ partial) {
+    ExtKV ext_kv, CallerIo io, float scale_log2e, int n_qblk, int n_units, float* __restrict__ partial) {
   constexpr int RB = D * 2;
   constexpr int KS = D / 16;
   __shared__ float park_sum[kWavesPerGroup][AMSKV_MAX_SCALES][64];
@@ -38,23 +38,26 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void density_partial_kernel(
   const long long bh = unit / n_qblk;
   const int q_base = (unit % n_qblk) * 32;
   const char* kb = kc + bh * cap_tokens * RB;
-  const char* xk = (const char*)ext_kv.k + bh * (long long)(seg.total - seg.ext_start) * RB;
+  const char* xk = (const char*)ext_kv.k + unit_offset(io.kv, bh, io.heads);
+  const char* q_unit = (const char*)q + unit_offset(io.q, bh, io.heads);
 
   bf16x8 qf[KS];
   {
     const int row = min(q_base + r, t_q - 1);  // rows past T_q re-read the last row and are masked at the end
 #pragma unroll
-    for (int t = 0; t < KS; ++t) qf[t] = *reinterpret_cast<const bf16x8*>(q + (bh * t_q + row) * D + 16 * t + 8 * h);
+    for (int t = 0; t < KS; ++t) qf[t] = *reinterpret_cast<const bf16x8*>(q_unit + row * io.q.tok + 32 * t + 16 * h);
   }
 
   float run_max = -INFINITY;
   for (int p = 0; p < seg.n; ++p) {
     const int len = seg.len[p];
     const int vs = seg.virt_start[p];
-    const char* base = vs >= seg.ext_start ? xk + (long long)(vs - seg.ext_start) * RB : kb + (long long)seg.phys_off[p] * RB;
+    const bool outside = vs >= seg.ext_start;  // the current scale, read in place from the caller's tensor
+    const long long tok = outside ? io.kv.tok : (long long)RB;
+    const char* base = outside ? xk + (vs - seg.ext_start) * tok : kb + (long long)seg.phys_off[p] * RB;
     float ssum = 0.f;
     for (int j0 = 0; j0 < len; j0 += 32) {
-      const char* kp = base + (long long)min(j0 + r, len - 1) * RB + 16 * h;
+      const char* kp = base + min(j0 + r, len - 1) * tok + 16 * h;
       f32x16 sacc;
 #pragma unroll
       for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
@@ -119,18 +122,18 @@ __global__ __launch_bounds__(64) void density_total_kernel(const float* __restri
 }  // namespace
 
 hipError_t launch_density(const void* q, const void* kc, int batch, int heads, int t_q, int head_dim,
-                          int64_t cap_tokens, const SegTable& pieces, const ExtKV& ext, float softmax_scale,
-                          float* partial_ws, float* out_dev, hipStream_t st) {
+                          int64_t cap_tokens, const SegTable& pieces, const ExtKV& ext, const CallerIo& io,
+                          float softmax_scale, float* partial_ws, float* out_dev, hipStream_t st) {
   const float c = softmax_scale * 1.4426950408889634f;
   const int n_qblk = (t_q + 31) / 32;
   const long long n_units = (long long)batch * heads * n_qblk;
   dim3 grid((unsigned)((n_units + kWavesPerGroup - 1) / kWavesPerGroup)), block(64 * kWavesPerGroup);
   if (head_dim == 64)
     hipLaunchKernelGGL(density_partial_kernel<64>, grid, block, 0, st, (const __bf16*)q, (const char*)kc, t_q,
-                       (long long)cap_tokens, pieces, ext, c, n_qblk, (int)n_units, partial_ws);
+                       (long long)cap_tokens, pieces, ext, io, c, n_qblk, (int)n_units, partial_ws);
   else
     hipLaunchKernelGGL(density_partial_kernel<128>, grid, block, 0, st, (const __bf16*)q, (const char*)kc, t_q,
-                       (long long)cap_tokens, pieces, ext, c, n_qblk, (int)n_units, partial_ws);
+                       (long long)cap_tokens, pieces, ext, io, c, n_qblk, (int)n_units, partial_ws);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(density_total_kernel, dim3(heads), dim3(64), 0, st, partial_ws, batch, heads, n_qblk, pieces.n,

@@ -52,13 +52,14 @@ __device__ __forceinline__ void taps(int dst, int n_in, int n_out, int& i0, int&
 // partial[(tensor*BH + bh)*4 + {0,1,2,3}] = sum_t cos_t, sum a.b, sum |a|^2, sum |b|^2.
 template <bool BF16>
 __global__ __launch_bounds__(kThreads) void similarity_partial_kernel(
-    ScaleRef cur_ref, ScaleRef prev_ref, int row_bytes, int h_cur, int w_cur, int h_prev, int w_prev,
+    ScaleRef cur_ref, ScaleRef prev_ref, int row_bytes, int heads, int h_cur, int w_cur, int h_prev, int w_prev,
     float* __restrict__ partial) {
   const long long bh = blockIdx.x;
-  const char* cur = (const char*)(blockIdx.y ? cur_ref.v : cur_ref.k) +
-                    (bh * cur_ref.stride_tokens + cur_ref.off_tokens) * row_bytes;
-  const char* prev = (const char*)(blockIdx.y ? prev_ref.v : prev_ref.k) +
-                     (bh * prev_ref.stride_tokens + prev_ref.off_tokens) * row_bytes;
+  const char* cur = (const char*)(blockIdx.y ? cur_ref.v : cur_ref.k) + unit_offset(cur_ref.map, bh, heads) +
+                    cur_ref.off_tokens * cur_ref.map.tok;
+  const char* prev = (const char*)(blockIdx.y ? prev_ref.v : prev_ref.k) + unit_offset(prev_ref.map, bh, heads) +
+                     prev_ref.off_tokens * prev_ref.map.tok;
+  const long long cur_tok = cur_ref.map.tok, prev_tok = prev_ref.map.tok;
   const int lpt = row_bytes >> 4;          // lanes per token: 8, 16 or 32
   const int sub = threadIdx.x % lpt;       // which 16-byte piece of the row
   const int slot = threadIdx.x / lpt;
@@ -76,11 +77,11 @@ __global__ __launch_bounds__(kThreads) void similarity_partial_kernel(
       taps(i, h_prev, h_cur, r0, r1, lr);
       taps(j, w_prev, w_cur, c0, c1, lc);
       Chunk<BF16> a, p00, p01, p10, p11;
-      a.load(cur + (long long)t * row_bytes + (sub << 4));
-      p00.load(prev + (long long)(r0 * w_prev + c0) * row_bytes + (sub << 4));
-      p01.load(prev + (long long)(r0 * w_prev + c1) * row_bytes + (sub << 4));
-      p10.load(prev + (long long)(r1 * w_prev + c0) * row_bytes + (sub << 4));
-      p11.load(prev + (long long)(r1 * w_prev + c1) * row_bytes + (sub << 4));
+      a.load(cur + t * cur_tok + (sub << 4));
+      p00.load(prev + (r0 * w_prev + c0) * prev_tok + (sub << 4));
+      p01.load(prev + (r0 * w_prev + c1) * prev_tok + (sub << 4));
+      p10.load(prev + (r1 * w_prev + c0) * prev_tok + (sub << 4));
+      p11.load(prev + (r1 * w_prev + c1) * prev_tok + (sub << 4));
 #pragma unroll
       for (int e = 0; e < Chunk<BF16>::N; ++e) {
         const float left = p00.v[e] * (1.f - lr) + p10.v[e] * lr;    // rows first,
@@ -148,11 +149,11 @@ hipError_t launch_similarity(const ScaleRef& cur, const ScaleRef& prev, int batc
   const int bh = batch * heads;
   dim3 grid(bh, tensors), block(kThreads);
   if (dtype == AMSKV_DTYPE_BF16) {
-    hipLaunchKernelGGL(similarity_partial_kernel<true>, grid, block, 0, st, cur, prev, head_dim * 2, h_cur, w_cur,
-                       h_prev, w_prev, partial_ws);
+    hipLaunchKernelGGL(similarity_partial_kernel<true>, grid, block, 0, st, cur, prev, head_dim * 2, heads, h_cur,
+                       w_cur, h_prev, w_prev, partial_ws);
   } else {
-    hipLaunchKernelGGL(similarity_partial_kernel<false>, grid, block, 0, st, cur, prev, head_dim * 4, h_cur, w_cur,
-                       h_prev, w_prev, partial_ws);
+    hipLaunchKernelGGL(similarity_partial_kernel<false>, grid, block, 0, st, cur, prev, head_dim * 4, heads, h_cur,
+                       w_cur, h_prev, w_prev, partial_ws);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;

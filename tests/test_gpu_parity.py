@@ -391,3 +391,31 @@ def test_config5_policy_sweep_sampled_units():
         return inp.iid_qkv(w.sides, w.batch, w.heads, w.head_dim, "bf16", inp.layer_seed(5, layer), device="cuda")
 
     _full_size_layers(w, layers, 16, gen, pols)
+
+
+# ------------------------------------------------------------------ run-to-run reproducibility
+@pytest.mark.parametrize("D", [64, 128])
+def test_attend_bf16_is_bit_reproducible(D):
+    """Same inputs, same bits, launch after launch, for every kernel variant of the schedule (coarse, mid and
+    wide scales).  A read of a matrix-instruction result before the instruction has finished writing it shows
+    up here as last-bit differences between runs long before it exceeds the parity tolerance."""
+    sides = (1, 2, 3, 4, 5, 6, 8, 10, 13, 16)
+    B, H = 2, 5
+    q, k, v = inp.iid_qkv(sides, B, H, D, "bf16", inp.layer_seed(6, D))
+    q, k, v = ([x.cuda() for x in t] for t in (q, k, v))
+    runs = []
+    for rep in range(3):
+        r = Runner(sides, sides, B, H, D, "bf16", [(0, 0, True)], layout=amskv.AMSKV_LAYOUT_PLANNED, borrow=True, fuse=True)
+        try:
+            outs = []
+            for s in range(len(sides)):
+                amskv.amskv_append_scale(r.h, 0, s, k[s], v[s])
+                o = torch.full_like(q[s], float("nan"))
+                amskv.amskv_attend(r.h, 0, s, q[s], o)
+                outs.append(o)
+            torch.cuda.synchronize()
+            runs.append([_bits(o) for o in outs])
+        finally:
+            r.close()
+    for s in range(len(sides)):
+        assert np.array_equal(runs[0][s], runs[1][s]) and np.array_equal(runs[0][s], runs[2][s]), "scale %d" % s
