@@ -36,7 +36,7 @@ COS_THRESHOLD = 0.5
 MEASURED_TRAFFIC_BYTES = {
     # profiles/var_d30_b256_hbm_traffic.txt: (FETCH_SIZE*2.0000 + WRITE_SIZE*1.0000) KiB per launch, mean over the
     # dominant kernel's launches of one step; key = (kernel, workload, mode, layout, borrow, fuse)
-    ("attend_bf16_kernel<64,1,8,64,4>", "var_d30_bf16_b256", "amskv", "planned", 1, 1): 1592007379,
+    ("attend_bf16_kernel<64,1,8,64,4>", "var_d30_bf16_b256", "amskv", "planned", 1, 1): 1592013252,
 }
 
 

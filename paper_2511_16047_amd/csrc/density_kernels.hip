@@ -101,22 +101,29 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void density_partial_kernel(
 }
 
 // out[h][p] = (1/B) * sum over batch and query blocks of partial[(b,h), block][p], fixed order:
-// lane = p + 16*part walks every fourth unit of the head, then a two-step tree over the parts.
-__global__ __launch_bounds__(64) void density_total_kernel(const float* __restrict__ partial, int batch, int heads,
-                                                           int n_qblk, int n_seg, float* __restrict__ out) {
+// thread = p + 16*part walks every kParts-th unit of the head, then a tree over the parts in LDS.
+constexpr int kParts = 16;
+__global__ __launch_bounds__(16 * kParts) void density_total_kernel(const float* __restrict__ partial, int batch,
+                                                                    int heads, int n_qblk, int n_seg,
+                                                                    float* __restrict__ out) {
+  __shared__ float red[kParts][16];
   const int hd = blockIdx.x;
   const int p = threadIdx.x & 15, part = threadIdx.x >> 4;
   float acc = 0.f;
   if (p < n_seg) {
     const int per_head = batch * n_qblk;
-    for (int i = part; i < per_head; i += 4) {
+    for (int i = part; i < per_head; i += kParts) {
       const int b = i / n_qblk, blk = i - b * n_qblk;
       acc += partial[(((long long)b * heads + hd) * n_qblk + blk) * AMSKV_MAX_SCALES + p];
     }
   }
-  acc += __shfl_xor(acc, 16, 64);
-  acc += __shfl_xor(acc, 32, 64);
-  if (threadIdx.x < 16) out[hd * AMSKV_MAX_SCALES + p] = p < n_seg ? acc / (float)batch : 0.f;
+  red[part][p] = acc;
+  __syncthreads();
+  for (int m = kParts / 2; m > 0; m >>= 1) {
+    if (part < m) red[part][p] += red[part + m][p];
+    __syncthreads();
+  }
+  if (part == 0) out[hd * AMSKV_MAX_SCALES + p] = p < n_seg ? red[0][p] / (float)batch : 0.f;
 }
 
 }  // namespace
@@ -136,7 +143,7 @@ hipError_t launch_density(const void* q, const void* kc, int batch, int heads, i
                        (long long)cap_tokens, pieces, ext, io, c, n_qblk, (int)n_units, partial_ws);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(density_total_kernel, dim3(heads), dim3(64), 0, st, partial_ws, batch, heads, n_qblk, pieces.n,
+  hipLaunchKernelGGL(density_total_kernel, dim3(heads), dim3(16 * kParts), 0, st, partial_ws, batch, heads, n_qblk, pieces.n,
                      out_dev);
   return hipGetLastError();
 }
