@@ -26,7 +26,8 @@
  * Element type: float (dtype 0) or bfloat16 (dtype 1), the same for every tensor.
  *
  * Every function returns an amskv_status (0 = ok, negative = error) unless stated.
- * On error nothing has been enqueued and the cache state is unchanged.
+ * On error nothing has been enqueued and the cache state is unchanged; the one exception is
+ * AMSKV_ERR_HIP (a failed launch or copy may follow work already enqueued by the same call).
  */
 #ifndef AMSKV_H
 #define AMSKV_H
