@@ -103,6 +103,12 @@ int validate(int32_t layers, int32_t heads, int32_t head_dim, const amskv_schedu
   }
   if (total > (1 << 22)) return AMSKV_ERR_INVALID_ARG;
   if ((int64_t)sc->batch * heads > (1 << 24)) return AMSKV_ERR_INVALID_ARG;
+  // launch grids count (b, h, block of >= 32 query rows) units and 16-byte chunks of a scale in 32 bits
+  for (int i = 0; i < sc->n_scales; ++i) {
+    const int64_t t = (int64_t)sc->side_h[i] * sc->side_w[i];
+    if ((int64_t)sc->batch * heads * ((t + 31) / 32) > (1 << 30)) return AMSKV_ERR_INVALID_ARG;
+    if ((int64_t)sc->batch * heads * t * (head_dim / 4) > ((int64_t)1 << 39)) return AMSKV_ERR_INVALID_ARG;
+  }
   if (po->n_layers != layers) return AMSKV_ERR_INVALID_ARG;
   if (po->layout != AMSKV_LAYOUT_COMPACT && po->layout != AMSKV_LAYOUT_PLANNED)
     return AMSKV_ERR_INVALID_ARG;

@@ -299,3 +299,34 @@ def test_token_budget_mode_rejects_bad_configurations():
         assert e.status == amskv.AMSKV_ERR_NO_DEVICE_MEMORY
     finally:
         amskv.amskv_cache_destroy(h)
+
+
+def test_io_layout_validation_on_plan_only_cache():
+    H, D = 3, 64
+    h = _plan_cache((1, 2, 3), [(1, 1, False)], H=H, D=D)
+    try:
+        TM, HM = amskv.AMSKV_IO_TOKEN_MAJOR, amskv.AMSKV_IO_HEAD_MAJOR
+        amskv.amskv_cache_set_io_layout(h, TM, 3 * H * D, 3 * H * D + 8, H * D)      # padded strides are fine
+        amskv.amskv_cache_set_io_layout(h, HM)
+        for bad in [(H * D - 8, H * D, H * D), (H * D, H * D + 1, H * D), (H * D, H * D, 0), (1 << 41, H * D, H * D)]:
+            with pytest.raises(amskv.AmskvError) as e:
+                amskv.amskv_cache_set_io_layout(h, TM, *bad)
+            assert e.value.status == amskv.AMSKV_ERR_INVALID_ARG
+        with pytest.raises(amskv.AmskvError) as e:
+            amskv.amskv_cache_set_io_layout(h, 2, H * D, H * D, H * D)
+        assert e.value.status == amskv.AMSKV_ERR_INVALID_ARG
+        amskv.amskv_append_scale(h, 0, 0)
+        with pytest.raises(amskv.AmskvError) as e:                                   # a scale is resident
+            amskv.amskv_cache_set_io_layout(h, TM, H * D, H * D, H * D)
+        assert e.value.status == amskv.AMSKV_ERR_ORDER
+        amskv.amskv_cache_reset(h)
+        amskv.amskv_cache_set_io_layout(h, TM, H * D, H * D, H * D)
+    finally:
+        amskv.amskv_cache_destroy(h)
+
+
+def test_oversized_launches_are_rejected_at_create():
+    # units (b, h, 32-row query block) and 16-byte chunks of a scale must fit the 32-bit launch grids
+    with pytest.raises(amskv.AmskvError) as e:
+        amskv.amskv_cache_required_bytes(1, 4096, 64, (1024,), (1024,), 4096, amskv.AMSKV_DTYPE_BF16, [(0, 0, True)])
+    assert e.value.status == amskv.AMSKV_ERR_INVALID_ARG
