@@ -190,3 +190,56 @@ def test_side_stream_and_softmax_scale():
     with torch.cuda.stream(st):
         _run((2, 3, 5, 7, 11), 1, 5, 64, "f32", (25, 70, 4), _theta_above, inp.layer_seed(7, 4), softmax_scale=0.2)
     st.synchronize()
+
+
+def test_full_batch_sampled_units():
+    """The benchmark's token-budget configuration (VAR-d30 shape, batch 256, budgets 174/274/5): one layer per
+    outcome of the Eq. 3 test, 16 sampled (b,h) each against the oracle -- attention within tolerance, cached
+    tokens and contents bit for bit."""
+    w = inp.config3(batch=256)
+    sides, B, H, D = w.sides, w.batch, w.heads, w.head_dim
+    tokens = [s * s for s in sides]
+    st = orc.scale_starts(tokens)
+    c_min, c_max, c_cds = 174, 274, 5
+    for layer, grow in ((0, True), (1, False)):
+        q, k, v = inp.correlated_qkv(sides, B, H, D, "bf16", inp.layer_seed(3, layer), 0.6, device="cuda")
+        budgets = [(c_min, c_max, c_cds, 2.0 if grow else -2.0)]
+        need = amskv.amskv_cache_required_bytes(1, H, D, sides, sides, B, DT["bf16"], None, budgets=budgets)
+        arena = torch.empty(need, dtype=torch.uint8, device="cuda")
+        arena.fill_(0xFF)
+        h = amskv.amskv_cache_create(1, H, D, sides, sides, B, DT["bf16"], None, arena=arena, budgets=budgets)
+        try:
+            outs = []
+            for s in range(len(sides)):
+                amskv.amskv_append_scale(h, 0, s, k[s], v[s])
+                o = torch.full_like(q[s], float("nan"))
+                amskv.amskv_attend(h, 0, s, q[s], o)
+                outs.append(o)
+            torch.cuda.synchronize()
+            trace = orc.alg1_cache_trace(tokens, c_min, c_max, c_cds, [grow] * len(sides))
+            ids = trace[-1][0]
+            assert _segment_ids(tokens, amskv.amskv_cache_segments(h, 0)) == ids
+            assert amskv.amskv_cache_budget_tokens(h, 0) == trace[-1][1] == (c_max if grow else c_min)
+            ko = torch.empty(B, H, len(ids), D, dtype=torch.bfloat16, device="cuda")
+            vo = torch.empty_like(ko)
+            amskv.amskv_cache_export(h, 0, ko, vo)
+            torch.cuda.synchronize()
+            allow = orc.alg1_allow_mask(tokens, trace)
+            units = sorted({(b, hh) for (_, b, hh) in inp.sample_units(1, B, H, 16, 91 + layer)})
+            worst = 0.0
+            for b, hh in units:
+                pick = lambda xs: np.concatenate([_f64(x[b:b + 1, hh:hh + 1]) for x in xs], axis=-2)
+                want = orc.masked_attention(pick(q), pick(k), pick(v), allow)
+                for s in range(len(sides)):
+                    got = _f64(outs[s][b:b + 1, hh:hh + 1])
+                    assert np.isfinite(got).all()
+                    worst = max(worst, float(np.abs(got - want[..., st[s]: st[s] + tokens[s], :]).max()))
+                kb = np.concatenate([_bits(x[b:b + 1, hh:hh + 1]) for x in k], axis=-2)[..., ids, :]
+                vb = np.concatenate([_bits(x[b:b + 1, hh:hh + 1]) for x in v], axis=-2)[..., ids, :]
+                assert np.array_equal(_bits(ko[b:b + 1, hh:hh + 1]), kb) and np.array_equal(_bits(vo[b:b + 1, hh:hh + 1]), vb)
+            assert worst <= TOL["bf16"], worst
+            print("token-budget full batch, layer %d (expanded: %s): worst max-abs %.3e over %d units" % (layer, grow, worst, len(units)))
+        finally:
+            amskv.amskv_cache_destroy(h)
+            del q, k, v, arena
+            torch.cuda.empty_cache()
