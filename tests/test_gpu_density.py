@@ -129,3 +129,42 @@ def test_density_uniform_queries_and_errors():
         assert e.value.status == amskv.AMSKV_ERR_INVALID_ARG
     finally:
         amskv.amskv_cache_destroy(h)
+
+
+def test_density_full_batch_launch_configuration():
+    """Batch 256 x 30 heads at the last scale of the 256x256 schedule (the launch the benchmark times).  The batch
+    repeats two distinct samples, so the batch mean equals the oracle's over those two; the masses of a head
+    add up to T_s whatever the size."""
+    B, B0, H, D = 256, 2, 30, 64
+    tokens = [x * x for x in VAR]
+    q0, k0, v0 = inp.correlated_qkv(VAR, B0, H, D, "bf16", inp.layer_seed(8, 3), 0.7)
+    rep = lambda t: t.repeat(B // B0, 1, 1, 1).cuda()
+    pol = (2, 2, False)
+    need = amskv.amskv_cache_required_bytes(1, H, D, VAR, VAR, B, BF16, [pol], 0.0, amskv.AMSKV_LAYOUT_PLANNED, True, True)
+    arena = torch.empty(need, dtype=torch.uint8, device="cuda")
+    h = amskv.amskv_cache_create(1, H, D, VAR, VAR, B, BF16, [pol], 0.0, amskv.AMSKV_LAYOUT_PLANNED, arena=arena,
+                                 borrow_unretained=True, fuse_append=True)
+    try:
+        keep = []
+        for s in range(len(VAR)):
+            kd, vd = rep(k0[s]), rep(v0[s])
+            keep += [kd, vd]
+            amskv.amskv_append_scale(h, 0, s, kd, vd)
+            if s < len(VAR) - 1:
+                qd = rep(q0[s])
+                o = torch.empty_like(qd)
+                amskv.amskv_attend(h, 0, s, qd, o)
+        s = len(VAR) - 1
+        qd = rep(q0[s])
+        got_d, got_m = amskv.amskv_attention_density(h, 0, s, qd, H)
+        st = orc.scale_starts(tokens)
+        kept = orc.kept_scales(pol, s)
+        pieces = [(st[k], tokens[k]) for k in kept]
+        rows = orc.allow_mask(tokens, pol)[st[s]: st[s] + tokens[s]]
+        k_all = np.concatenate([_f64(x) for x in k0], axis=-2)
+        want_d, want_m = orc.attention_density(_f64(q0[s]), k_all, rows, pieces)
+        assert np.allclose(np.asarray(got_m), want_m, rtol=2e-4, atol=1e-5)
+        assert np.allclose(np.asarray(got_d), want_d, rtol=2e-4, atol=1e-5)
+        assert np.allclose(np.asarray(got_m).sum(axis=-1), tokens[s], rtol=1e-4)
+    finally:
+        amskv.amskv_cache_destroy(h)
