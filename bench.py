@@ -194,7 +194,9 @@ def main():
                     timers.append((l, s, e))
             if s == probe and probe >= 1 and budgets is None:
                 for l in probe_layers:
-                    amskv.amskv_interscale_similarity(cache, l, s, H, want_v=False, want_sums=False, stream=stream)
+                    amskv.amskv_interscale_similarity_enqueue(cache, l, s, want_v=False, stream=stream)
+        if probe >= 1 and budgets is None:   # the scores of all layers: one transfer, one wait per step
+            amskv.amskv_interscale_similarity_collect(cache, L, H, want_v=False, want_sums=False, stream=stream)
 
     # ---------------- timed region
     for _ in range(args.warmup):

@@ -207,6 +207,19 @@ int32_t amskv_interscale_similarity(amskv_cache* cache, int32_t layer, int32_t s
                                     float* cosK_host, float* cosV_host, float* sums_host,
                                     void* stream);
 
+/* The same computation without the wait, for callers that probe many layers: _enqueue only
+ * launches the kernels of (layer, s) on `stream` (want_v != 0 includes the values); the sums stay
+ * in a per-layer slot inside the arena until the next _enqueue on that layer.  _collect copies
+ * the slots of ALL layers to the host with one transfer and one wait for `stream`, and converts
+ * them as above: cosK_host[l*H + h], cosV_host[l*H + h] (or NULL), sums_host[(l*H + h)*3 + i]
+ * (or NULL).  Layers with nothing enqueued since create / reset, and cosV of a layer enqueued
+ * without the values, read NaN.  Same status codes as the call above; all calls of one cache
+ * must be ordered on one stream (the partial-sum workspace is shared by the layers). */
+int32_t amskv_interscale_similarity_enqueue(amskv_cache* cache, int32_t layer, int32_t s,
+                                            int32_t want_v, void* stream);
+int32_t amskv_interscale_similarity_collect(amskv_cache* cache, float* cosK_host, float* cosV_host,
+                                            float* sums_host, void* stream);
+
 /* Attention density (Section 4.1): of the softmax mass that the queries Q of scale s spread over
  * the keys they attend to, how much lands on each group of keys of layer `layer` -- the groups
  * being the entries of amskv_cache_segments, in that order (whole scales in scale-window mode).

@@ -34,7 +34,7 @@ EXPORTED = [
     "amskv_cache_bytes_held", "amskv_cache_capacity_tokens", "amskv_cache_export",
     "amskv_cache_reset", "amskv_cache_destroy", "amskv_status_string",
     "amskv_cache_segments", "amskv_cache_budget_tokens", "amskv_cache_settle", "amskv_attention_density",
-    "amskv_cache_set_io_layout",
+    "amskv_cache_set_io_layout", "amskv_interscale_similarity_enqueue", "amskv_interscale_similarity_collect",
 ]
 
 
@@ -117,6 +117,10 @@ def load_library() -> C.CDLL:
     lib.amskv_attention_density.restype = i32
     lib.amskv_cache_set_io_layout.argtypes = [vp, i32, i64, i64, i64]
     lib.amskv_cache_set_io_layout.restype = i32
+    lib.amskv_interscale_similarity_enqueue.argtypes = [vp, i32, i32, i32, vp]
+    lib.amskv_interscale_similarity_enqueue.restype = i32
+    lib.amskv_interscale_similarity_collect.argtypes = [vp, pf, pf, pf, vp]
+    lib.amskv_interscale_similarity_collect.restype = i32
     _lib = lib
     return lib
 
@@ -222,6 +226,23 @@ def amskv_attention_density(cache, layer, s, Q, heads, stream=None):
            "amskv_attention_density")
     rows = lambda a: [[a[h * AMSKV_MAX_SCALES + i] for i in range(n.value)] for h in range(heads)]
     return rows(d), rows(m)
+
+
+def amskv_interscale_similarity_enqueue(cache, layer, s, want_v=True, stream=None):
+    _check(load_library().amskv_interscale_similarity_enqueue(cache, layer, s, int(bool(want_v)), _stream(stream)),
+           "amskv_interscale_similarity_enqueue")
+
+
+def amskv_interscale_similarity_collect(cache, layers, heads, want_v=True, want_sums=True, stream=None):
+    """Returns (cosK[L][H], cosV[L][H] or None, sums[L][H][3] or None) as nested Python lists."""
+    ck = (C.c_float * (layers * heads))()
+    cv = (C.c_float * (layers * heads))() if want_v else None
+    sm = (C.c_float * (3 * layers * heads))() if want_sums else None
+    _check(load_library().amskv_interscale_similarity_collect(cache, ck, cv, sm, _stream(stream)),
+           "amskv_interscale_similarity_collect")
+    rows = lambda a: [[a[l * heads + h] for h in range(heads)] for l in range(layers)]
+    return (rows(ck), rows(cv) if want_v else None,
+            [[[sm[(l * heads + h) * 3 + i] for i in range(3)] for h in range(heads)] for l in range(layers)] if want_sums else None)
 
 
 def amskv_cache_layout(cache, layer) -> List[Tuple[int, int, int]]:

@@ -40,6 +40,9 @@ struct LayerState {
   int32_t planned_off[AMSKV_MAX_SCALES];  // PLANNED layout: fixed slot of every scale
   // token-budget mode (Algorithm 1): budgets, the budget in force, and whether the newest scale
   // (last segment, read in place) still awaits its iteration of the algorithm
+  // similarity results waiting in the layer's device slot: scale they belong to (-1: none), whether V was included
+  int32_t sim_scale = -1;
+  bool sim_has_v = false;
   amskv_layer_budget bud = {0, 0, 0, 0.f};
   int32_t c_bgt = 0;
   bool roll_pending = false;
@@ -214,8 +217,8 @@ void build_plan(int32_t layers, int32_t heads, int32_t head_dim, const amskv_sch
     at = align_up(at + bh * (uint64_t)cap * row);
   }
   pl->ws_off = at;
-  // similarity workspace: per (tensor, b, h) four partial sums, then per (tensor, h) four totals
-  at = align_up(at + (2 * bh * 4 + 2 * (uint64_t)heads * 4) * sizeof(float));
+  // similarity workspace: per (tensor, b, h) four partial sums, then per (layer, tensor, h) four totals
+  at = align_up(at + (2 * bh * 4 + (uint64_t)layers * 2 * heads * 4) * sizeof(float));
   // attention-density workspace: per (b, h, block of 32 query rows) one partial sum per group of keys,
   // then per head one total per group
   int32_t t_max = 0;
@@ -285,14 +288,16 @@ inline bool whole_scale(const amskv_cache* c, const Segment& g, int s) {
   return g.scale == s && g.first == 0 && g.len == c->tokens[s];
 }
 
-// Eq. 3 between scale s (segment cur) and the upsampled scale s-1 (segment prev), both held
-// whole: per head four sums (cosine total, k.k^, |k|^2, |k^|^2) of K into host[0 .. 4H) and,
-// when want_v, of V into host[4H .. 8H).  Waits for the stream.
-int similarity_sums(amskv_cache* c, const LayerState& L, const Segment& cur, const Segment& prev, int s,
-                    bool want_v, std::vector<float>* host, hipStream_t st) {
-  const uint64_t bh = (uint64_t)c->batch * c->heads;
+inline float* similarity_slot(const amskv_cache* c, int layer) {
   float* partial = (float*)(c->arena + c->ws_off);
-  float* totals = partial + 2 * bh * 4;
+  return partial + 2 * (uint64_t)c->batch * c->heads * 4 + (uint64_t)layer * 2 * c->heads * 4;
+}
+
+// Eq. 3 between scale s (segment cur) and the upsampled scale s-1 (segment prev), both held
+// whole: enqueue the kernels that leave, in the layer's result slot, per head four sums (cosine
+// total, k.k^, |k|^2, |k^|^2) of K at [0 .. 4H) and, when want_v, of V at [4H .. 8H).
+int similarity_launch(amskv_cache* c, LayerState& L, int layer, const Segment& cur, const Segment& prev, int s,
+                      bool want_v, hipStream_t st) {
   auto ref = [&](const Segment& g) {
     ScaleRef r;
     if (g.off < 0 || g.pending) {
@@ -310,11 +315,22 @@ int similarity_sums(amskv_cache* c, const LayerState& L, const Segment& cur, con
   };
   hipError_t e = amskv::launch_similarity(ref(cur), ref(prev), c->batch, c->heads, c->head_dim, c->dtype,
                                           c->side_h[s], c->side_w[s], c->side_h[s - 1], c->side_w[s - 1],
-                                          partial, totals, st);
+                                          (float*)(c->arena + c->ws_off), similarity_slot(c, layer), st);
   if (e != hipSuccess) return AMSKV_ERR_HIP;
+  L.sim_scale = s;
+  L.sim_has_v = want_v;
+  return AMSKV_OK;
+}
+
+// The same, then the sums brought to host[0 .. 8H).  Waits for the stream.
+int similarity_sums(amskv_cache* c, LayerState& L, int layer, const Segment& cur, const Segment& prev, int s,
+                    bool want_v, std::vector<float>* host, hipStream_t st) {
+  int rc = similarity_launch(c, L, layer, cur, prev, s, want_v, st);
+  if (rc) return rc;
   host->assign(2 * (size_t)c->heads * 4, 0.f);
   const size_t n_t = want_v ? 2 : 1;
-  e = hipMemcpyAsync(host->data(), totals, n_t * c->heads * 4 * sizeof(float), hipMemcpyDeviceToHost, st);
+  hipError_t e = hipMemcpyAsync(host->data(), similarity_slot(c, layer), n_t * c->heads * 4 * sizeof(float),
+                                hipMemcpyDeviceToHost, st);
   if (e != hipSuccess) return AMSKV_ERR_HIP;
   e = hipStreamSynchronize(st);
   return e == hipSuccess ? AMSKV_OK : AMSKV_ERR_HIP;
@@ -322,7 +338,7 @@ int similarity_sums(amskv_cache* c, const LayerState& L, const Segment& cur, con
 
 // Algorithm 1's test for a cache-demanding layer: Eq. 3 (cosine form, mean over heads) of the
 // newest scale against the scale before it, compared with theta.
-int below_theta(amskv_cache* c, const LayerState& L, const Segment& cur, hipStream_t st, bool* below) {
+int below_theta(amskv_cache* c, LayerState& L, const Segment& cur, hipStream_t st, bool* below) {
   *below = false;
   if (L.bud.theta > 1.f) {
     *below = true;
@@ -335,7 +351,7 @@ int below_theta(amskv_cache* c, const LayerState& L, const Segment& cur, hipStre
   if (!prev) return AMSKV_OK;  // the earlier scale is not cached whole: no score, no expansion
   if (!c->arena || !cur.ext_k) return AMSKV_ERR_NO_DEVICE_MEMORY;
   std::vector<float> host;
-  int rc = similarity_sums(c, L, cur, *prev, cur.scale, false, &host, st);
+  int rc = similarity_sums(c, L, (int)(&L - c->layer.data()), cur, *prev, cur.scale, false, &host, st);
   if (rc) return rc;
   double mean = 0.0;
   const double n_tok = (double)c->batch * c->tokens[cur.scale];
@@ -679,33 +695,82 @@ int32_t amskv_attend(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev
   return AMSKV_OK;
 }
 
-int32_t amskv_interscale_similarity(amskv_cache* c, int32_t layer, int32_t s, float* cosK_host,
-                                    float* cosV_host, float* sums_host, void* stream) {
-  if (bad_layer(c, layer) || s < 1 || s >= c->n_scales || !cosK_host) return AMSKV_ERR_INVALID_ARG;
+// Checks shared by the two ways of asking for Eq. 3; on success cur/prev point at the two whole scales.
+static int similarity_operands(amskv_cache* c, int32_t layer, int32_t s, const Segment** cur, const Segment** prev) {
+  if (bad_layer(c, layer) || s < 1 || s >= c->n_scales) return AMSKV_ERR_INVALID_ARG;
   LayerState& L = c->layer[layer];
   if (s > L.last_scale) return AMSKV_ERR_ORDER;
-  const Segment* cur = nullptr;
-  const Segment* prev = nullptr;
+  *cur = *prev = nullptr;
   for (const Segment& g : L.segs) {
-    if (whole_scale(c, g, s)) cur = &g;
-    if (whole_scale(c, g, s - 1)) prev = &g;
+    if (whole_scale(c, g, s)) *cur = &g;
+    if (whole_scale(c, g, s - 1)) *prev = &g;
   }
-  if (!cur || !prev) return AMSKV_ERR_EVICTED;
+  if (!*cur || !*prev) return AMSKV_ERR_EVICTED;
   if (!c->arena) return AMSKV_ERR_NO_DEVICE_MEMORY;
-  if (((cur->off < 0 || cur->pending) && !cur->ext_k) || ((prev->off < 0 || prev->pending) && !prev->ext_k))
+  if ((((*cur)->off < 0 || (*cur)->pending) && !(*cur)->ext_k) || (((*prev)->off < 0 || (*prev)->pending) && !(*prev)->ext_k))
     return AMSKV_ERR_NO_DEVICE_MEMORY;
-  std::vector<float> host;
-  int rc = similarity_sums(c, L, *cur, *prev, s, cosV_host != nullptr, &host, (hipStream_t)stream);
-  if (rc) return rc;
+  return AMSKV_OK;
+}
+
+static void similarity_outputs(const amskv_cache* c, int s, bool has_v, const float* sums, float* cosK, float* cosV,
+                               float* sums_out) {
   const double n_tok = (double)c->batch * c->tokens[s];
   for (int h = 0; h < c->heads; ++h) {
-    cosK_host[h] = (float)(host[h * 4 + 0] / n_tok);
-    if (sums_host) {
-      sums_host[h * 3 + 0] = host[h * 4 + 1];
-      sums_host[h * 3 + 1] = host[h * 4 + 2];
-      sums_host[h * 3 + 2] = host[h * 4 + 3];
+    if (cosK) cosK[h] = (float)(sums[h * 4 + 0] / n_tok);
+    if (sums_out) {
+      sums_out[h * 3 + 0] = sums[h * 4 + 1];
+      sums_out[h * 3 + 1] = sums[h * 4 + 2];
+      sums_out[h * 3 + 2] = sums[h * 4 + 3];
     }
-    if (cosV_host) cosV_host[h] = (float)(host[(c->heads + h) * 4 + 0] / n_tok);
+    if (cosV) cosV[h] = has_v ? (float)(sums[(c->heads + h) * 4 + 0] / n_tok) : NAN;
+  }
+}
+
+int32_t amskv_interscale_similarity(amskv_cache* c, int32_t layer, int32_t s, float* cosK_host,
+                                    float* cosV_host, float* sums_host, void* stream) {
+  if (!cosK_host) return AMSKV_ERR_INVALID_ARG;
+  const Segment *cur, *prev;
+  int rc = similarity_operands(c, layer, s, &cur, &prev);
+  if (rc) return rc;
+  std::vector<float> host;
+  rc = similarity_sums(c, c->layer[layer], layer, *cur, *prev, s, cosV_host != nullptr, &host, (hipStream_t)stream);
+  if (rc) return rc;
+  similarity_outputs(c, s, cosV_host != nullptr, host.data(), cosK_host, cosV_host, sums_host);
+  return AMSKV_OK;
+}
+
+int32_t amskv_interscale_similarity_enqueue(amskv_cache* c, int32_t layer, int32_t s, int32_t want_v, void* stream) {
+  const Segment *cur, *prev;
+  int rc = similarity_operands(c, layer, s, &cur, &prev);
+  if (rc) return rc;
+  return similarity_launch(c, c->layer[layer], layer, *cur, *prev, s, want_v != 0, (hipStream_t)stream);
+}
+
+int32_t amskv_interscale_similarity_collect(amskv_cache* c, float* cosK_host, float* cosV_host, float* sums_host,
+                                            void* stream) {
+  if (!c || !cosK_host) return AMSKV_ERR_INVALID_ARG;
+  if (!c->arena) return AMSKV_ERR_NO_DEVICE_MEMORY;
+  const size_t per_layer = 2 * (size_t)c->heads * 4;
+  std::vector<float> host(per_layer * c->layers);
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = hipMemcpyAsync(host.data(), similarity_slot(c, 0), host.size() * sizeof(float), hipMemcpyDeviceToHost, st);
+  if (e != hipSuccess) return AMSKV_ERR_HIP;
+  e = hipStreamSynchronize(st);
+  if (e != hipSuccess) return AMSKV_ERR_HIP;
+  for (int l = 0; l < c->layers; ++l) {
+    const LayerState& L = c->layer[l];
+    float* ck = cosK_host + (size_t)l * c->heads;
+    float* cv = cosV_host ? cosV_host + (size_t)l * c->heads : nullptr;
+    float* sm = sums_host ? sums_host + (size_t)l * c->heads * 3 : nullptr;
+    if (L.sim_scale < 1) {  // nothing enqueued on this layer since create / reset
+      for (int h = 0; h < c->heads; ++h) {
+        ck[h] = NAN;
+        if (cv) cv[h] = NAN;
+        if (sm) sm[h * 3] = sm[h * 3 + 1] = sm[h * 3 + 2] = NAN;
+      }
+      continue;
+    }
+    similarity_outputs(c, L.sim_scale, L.sim_has_v, host.data() + per_layer * l, ck, cv, sm);
   }
   return AMSKV_OK;
 }
@@ -854,6 +919,7 @@ int32_t amskv_cache_reset(amskv_cache* c) {
     L.last_scale = -1;
     L.c_bgt = L.bud.c_min;
     L.roll_pending = false;
+    L.sim_scale = -1;
   }
   return AMSKV_OK;
 }

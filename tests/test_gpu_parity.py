@@ -419,3 +419,46 @@ def test_attend_bf16_is_bit_reproducible(D):
             r.close()
     for s in range(len(sides)):
         assert np.array_equal(runs[0][s], runs[1][s]) and np.array_equal(runs[0][s], runs[2][s]), "scale %d" % s
+
+
+# ------------------------------------------------------------------ similarity without the per-call wait
+def test_similarity_enqueue_collect_matches_the_waiting_call():
+    sides = (2, 3, 5, 8, 6)
+    B, H, D, L = 2, 3, 64, 4
+    pols = [(1, 2, False), (0, 0, True), (2, 1, False), (0, 1, False)]
+    r = Runner(sides, sides, B, H, D, "bf16", pols, layout=amskv.AMSKV_LAYOUT_PLANNED, borrow=True, fuse=True)
+    try:
+        data = [inp.correlated_qkv(sides, B, H, D, "bf16", inp.layer_seed(6, 50 + l), 0.3 + 0.2 * l) for l in range(L)]
+        dev = [[[x.cuda() for x in t] for t in d] for d in data]
+        nan = lambda rows: all(all(math.isnan(x) for x in row) for row in rows)
+        ck, cv, sm = amskv.amskv_interscale_similarity_collect(r.h, L, H)
+        assert nan(ck) and nan(cv)                                    # nothing enqueued yet
+        want = {}
+        for s in range(len(sides)):
+            for l in range(L):
+                amskv.amskv_append_scale(r.h, l, s, dev[l][1][s], dev[l][2][s])
+            if s == 3:
+                for l in range(L):
+                    want[l] = amskv.amskv_interscale_similarity(r.h, l, s, H)          # waits every time
+                for l in range(L):
+                    amskv.amskv_interscale_similarity_enqueue(r.h, l, s, want_v=(l != 2))
+                ck, cv, sm = amskv.amskv_interscale_similarity_collect(r.h, L, H)       # one wait for all
+                for l in range(L):
+                    assert ck[l] == want[l][0] and sm[l] == want[l][2]
+                    if l != 2:
+                        assert cv[l] == want[l][1]
+                    else:
+                        assert all(math.isnan(x) for x in cv[l])                        # enqueued without the values
+                    wk, _ = orc.interscale_similarity(_f64(data[l][1][s]), _f64(data[l][1][s - 1]), (sides[s],) * 2, (sides[s - 1],) * 2)
+                    assert np.abs(np.array(ck[l]) - wk).max() < 1e-5
+            for l in range(L):
+                o = torch.empty_like(dev[l][0][s])
+                amskv.amskv_attend(r.h, l, s, dev[l][0][s], o)
+        with pytest.raises(amskv.AmskvError) as e:                     # policy (0,1): scale 2 is gone at step 4
+            amskv.amskv_interscale_similarity_enqueue(r.h, 3, 3)
+        assert e.value.status == amskv.AMSKV_ERR_EVICTED
+        amskv.amskv_cache_reset(r.h)
+        ck, _, _ = amskv.amskv_interscale_similarity_collect(r.h, L, H)
+        assert nan(ck)
+    finally:
+        r.close()

@@ -129,7 +129,7 @@ def test_required_bytes_closed_form():
     pols = [(2, 2, False), (0, 0, True)]
     need = amskv.amskv_cache_required_bytes(2, H, D, VAR, VAR, B, amskv.AMSKV_DTYPE_BF16, pols)
     kv = sum(2 * B * H * cap * D * 2 for cap in (530, 680))
-    ws = (2 * B * H * 4 + 2 * H * 4) * 4                     # similarity: four sums per (tensor, b, h) and per (tensor, h)
+    ws = (2 * B * H * 4 + 2 * 2 * H * 4) * 4                 # similarity: four sums per (tensor, b, h) and per (layer, tensor, h)
     ws += (B * H * ((256 + 31) // 32) + H) * 16 * 4           # density: 16 groups per (b, h, 32-row query block) and per head
     assert kv + ws <= need <= kv + ws + 6 * 256
     need32 = amskv.amskv_cache_required_bytes(2, H, D, VAR, VAR, B, amskv.AMSKV_DTYPE_F32, pols)
