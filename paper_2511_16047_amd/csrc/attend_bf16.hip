@@ -28,15 +28,16 @@
 // needs it: the running max may lag the true max by up to 2^kMaxLag.
 //
 // Memory.  The kernel is HBM-bound at VAR shapes (arithmetic intensity T_q*T_kv/(T_q+T_kv)
-// flop/byte, below the chip's ridge), so the tile loop keeps two tiles in flight:
+// flop/byte, below the chip's ridge), so the tile loop keeps tiles in flight (two at head dim 64):
 // global_load_lds_dwordx4 writes 64 lanes x 16 bytes straight into LDS with no register staging,
 // and the wave only waits (s_waitcnt vmcnt) for the tile it is about to use.  A direct-to-LDS load
 // puts lane i's 16 bytes at base + 16*i, so the XOR swizzle that keeps the 16-byte fragment reads
 // conflict-free (chunk ^= row & 7) is applied on the global side: the lane that fills LDS chunk
 // position c' of row r fetches global chunk c' ^ (r & 7).  Rows past the end of K~ re-read the
 // last valid row (finite data) and their scores are set to -inf.  A borrowed current scale is the
-// tail of the virtual concatenation and its rows are fetched from the caller's K/V instead.  The ring has four slots: tile
-// t-1 (its last block's V is still being multiplied), t (in use), t+1 and t+2 (in flight).
+// tail of the virtual concatenation and its rows are fetched from the caller's K/V instead.
+// The ring holds tile t-1 (its last block's V is still being multiplied), t (in use) and the tiles in
+// flight: t+1 and t+2 at head dim 64, t+1 alone at head dim 128 (see kAhead).
 #include <cstdlib>
 
 #include "amskv_internal.hpp"
@@ -49,7 +50,6 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int kStages = 4;
 // query-token count up to which the latency-oriented kernel of attend_bf16_small.hip is used
 constexpr int kSmallTq = 32;
 // the online softmax lets the running max lag by up to this many powers of two before the
@@ -157,6 +157,13 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
   constexpr int BM = kWaves * 32 * NQ;
   constexpr int kTileBytes = kTileKeys * RB;
   constexpr int kBlocksPerTile = kTileKeys / 32;
+  // Ring of tiles in LDS: the tile in use, the one before it (the V rows of its last block are still being
+  // multiplied) and kAhead tiles in flight.  Head dim 64 keeps two in flight (its launches are bound by the
+  // memory pipeline and register count, not by LDS).  Head dim 128 is bound by latency at two waves per SIMD:
+  // one tile in flight makes the ring 48 KB, so three workgroups fit a CU -- three waves per SIMD, which
+  // measured 15 % faster on the 1024x1024 schedule than two waves with two tiles in flight.
+  constexpr int kAhead = D == 128 ? 1 : 2;
+  constexpr int kStages = kAhead + 2;
   constexpr int VM = Loader::kVmPerTile;
 
   __shared__ __align__(1024) char lds_k[kStages * kTileBytes];
@@ -202,7 +209,7 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
     for (int t = 0; t < KS; ++t) qf[n][t] = *reinterpret_cast<const bf16x8*>(q_unit + row * io.q.tok + 32 * t + 16 * h);
   }
 #pragma unroll
-  for (int st = 0; st < 2; ++st)
+  for (int st = 0; st < kAhead; ++st)
     if (st < n_tiles)
       Loader::issue(kb, vb, xk, xv, x_tok, lds_k + st * kTileBytes, lds_v + st * kTileBytes, st * kTileKeys, t_kv, seg, wave, lane);
 
@@ -260,16 +267,16 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
     const int it = g / kBlocksPerTile;
     const int sub = g % kBlocksPerTile;
     if (sub == 0) {
-      // wait for tile `it`; one younger tile may stay in flight
-      if (it + 1 < n_tiles) wait_vmcnt<VM>();
+      // wait for tile `it`; the kAhead - 1 younger tiles may stay in flight
+      if (kAhead > 1 && it + 1 < n_tiles) wait_vmcnt<VM*(kAhead - 1)>();
       else wait_vmcnt<0>();
       __syncthreads();  // every wave's part of tile `it` has landed; every wave is done with tile it-2
       if (write_back && (it + 1) * kTileKeys > seg.ext_start)
         Loader::write_back(kb, vb, lds_k + (it % kStages) * kTileBytes, lds_v + (it % kStages) * kTileBytes,
                            it * kTileKeys, t_kv, seg, ext_kv.wb_off, wave, lane);
-      if (it + 2 < n_tiles) {
-        const int slot = (it + 2) % kStages;
-        Loader::issue(kb, vb, xk, xv, x_tok, lds_k + slot * kTileBytes, lds_v + slot * kTileBytes, (it + 2) * kTileKeys, t_kv,
+      if (it + kAhead < n_tiles) {  // into the slot of tile it-2, which the barrier above has just retired
+        const int slot = (it + kAhead) % kStages;
+        Loader::issue(kb, vb, xk, xv, x_tok, lds_k + slot * kTileBytes, lds_v + slot * kTileBytes, (it + kAhead) * kTileKeys, t_kv,
                       seg, wave, lane);
       }
     }
@@ -459,11 +466,10 @@ hipError_t launch_attend_bf16(const void* q, void* o, void* kc, void* vc, int bh
     // eight waves of 32 rows: ~110 registers per lane, so two workgroups (16 waves) share a CU
     return wide ? launch<64, 1, 8, 64, 4>(q, o, kc, vc, bh, t_q, cap_tokens, seg, ext, io, c, st)
                 : launch<64, 1, 4, 32, 4>(q, o, kc, vc, bh, t_q, cap_tokens, seg, ext, io, c, st);
-  // head dim 128: 32 query rows per wave keep the kernel at two waves per SIMD (two workgroups of
-  // four waves per CU), which measured ~14 % faster than 64 rows per wave at one wave per SIMD on the 1024x1024 schedule; 32-key tiles
-  // (16 KB per ring slot) leave room for several workgroups per CU
+  // head dim 128: 32 query rows per wave (~160 registers) and a three-slot ring give three waves per SIMD,
+  // i.e. three workgroups of four waves per CU; 64 rows per wave would halve that
   (void)wide;
-  return launch<128, 1, 4, 32, 2>(q, o, kc, vc, bh, t_q, cap_tokens, seg, ext, io, c, st);
+  return launch<128, 1, 4, 32, 3>(q, o, kc, vc, bh, t_q, cap_tokens, seg, ext, io, c, st);
 }
 
 }  // namespace amskv
