@@ -367,7 +367,9 @@ int below_theta(amskv_cache* c, LayerState& L, const Segment& cur, hipStream_t s
 // (cached tokens followed by the new scale): the first c_cds tokens and the last
 // (budget - c_cds) tokens stay.  Survivors slide toward offset 0; what stays of the new scale
 // is copied behind them.
-int roll_budget(amskv_cache* c, LayerState& L, hipStream_t st) {
+// appended_at >= 0: the attention kernel of this step has already written the whole scale into the cache at that
+// token offset (possible whenever the scale fits the budget without trimming), so nothing is left to copy.
+int roll_budget(amskv_cache* c, LayerState& L, hipStream_t st, int32_t appended_at = -1) {
   if (!L.roll_pending) return AMSKV_OK;
   const Segment cur = L.segs.back();
   const int32_t t_new = cur.len;
@@ -443,7 +445,10 @@ int roll_budget(amskv_cache* c, LayerState& L, hipStream_t st) {
     if (at > L.cap) return AMSKV_ERR_ARENA_TOO_SMALL;  // cannot happen: at <= budget <= c_max
   }
 
-  if (c->arena && cur.ext_k) {
+  const bool copied_already = appended_at >= 0 && mv.n == 0 && copies.size() == 1 && copies[0].src_first == 0 &&
+                              copies[0].len == t_new && copies[0].dst == appended_at;
+  if (appended_at >= 0 && !copied_already) return AMSKV_ERR_INVALID_ARG;  // cannot happen: the caller used the same rule
+  if (c->arena && cur.ext_k && !copied_already) {
     const int bh = c->batch * c->heads;
     const int row_bytes = c->head_dim * c->elem_bytes;
     char* kc = c->arena + L.k_off;
@@ -673,6 +678,14 @@ int32_t amskv_attend(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev
   if (t.ext_start < t.total && !ext.k) return AMSKV_ERR_NO_DEVICE_MEMORY;  // borrowed scale appended without data
   Segment& newest = L.segs.back();
   if (newest.pending) ext.wb_off = newest.off;  // fused append: this launch also fills the slot
+  // token-budget mode: when the scale fits the budget in force next to what is cached, Algorithm 1 keeps all of
+  // it, untrimmed, right behind the cached tokens -- known before the step runs, so the same launch writes it there
+  int32_t appended_at = -1;
+  if (c->mode == AMSKV_MODE_TOKEN_BUDGET) {
+    int64_t n_old = 0;
+    for (size_t i = 0; i + 1 < L.segs.size(); ++i) n_old += L.segs[i].len;
+    if (newest.len <= L.bud.c_max && n_old + newest.len <= L.c_bgt) ext.wb_off = appended_at = (int32_t)n_old;
+  }
   const int bh = c->batch * c->heads;
   // the scale read in place, if any, is the newest one
   const CallerIo io{caller_map(c, c->tokens[s], c->q_tok), caller_map(c, c->tokens[s], c->o_tok),
@@ -691,7 +704,7 @@ int32_t amskv_attend(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev
     newest.pending = false;
     newest.ext_k = newest.ext_v = nullptr;
   }
-  if (c->mode == AMSKV_MODE_TOKEN_BUDGET) return roll_budget(c, L, (hipStream_t)stream);
+  if (c->mode == AMSKV_MODE_TOKEN_BUDGET) return roll_budget(c, L, (hipStream_t)stream, appended_at);
   return AMSKV_OK;
 }
 
