@@ -342,7 +342,7 @@ def main():
                         "(kernels + result copy + wait)", "ms_per_call": d_ms, "tflops_qk": d_fl / (d_ms * 1e-3) / 1e12,
                 "last_layer_head0_density_per_kept_scale": [round(x, 4) for x in dl[0]]}
 
-    dom_name = "attend_bf16_kernel<%d,%s>" % (D, "1,8,64,4" if D == 64 else "1,4,32,2")
+    dom_name = "attend_bf16_kernel<%d,%s>" % (D, "1,8,64,4" if D == 64 else "1,4,32,3")
     if budgets is not None:   # the timed interval of an attend call holds the step's Algorithm 1 iteration too
         dom_name += " + Algorithm 1 iteration (similarity, compact, copy kernels)"
     ai = dom_flops / dom_bytes
