@@ -275,6 +275,27 @@ def test_large_values_do_not_overflow_softmax():
         r.close()
 
 
+@pytest.mark.parametrize("D", [64, 128])
+def test_late_dominant_keys_force_the_rescale_path(D):
+    """Scores that jump far above the running reference late in the key sequence: one key per scale is aligned with
+    every query and scaled up, more so at each later scale, so the lazily updated reference of the online softmax
+    has to move (and the accumulators be rescaled) in the last blocks of every kernel variant -- coarse, mid, wide."""
+    sides = (1, 2, 3, 4, 5, 6, 8, 10, 13, 16)
+    B, H = 1, 3
+    q, k, v = inp.iid_qkv(sides, B, H, D, "bf16", inp.layer_seed(6, 70 + D))
+    q = [x.abs() for x in q]                                  # every query in the positive orthant ...
+    for s, x in enumerate(k):
+        x[..., -1, :] = 0.25 * (s + 1)                        # ... so the last key of scale s scores ~ (s+1)*0.2*D above the rest
+    q, k, v = ([x.cuda() for x in t] for t in (q, k, v))
+    for pol in [(0, 0, True), (2, 2, False)]:
+        r = Runner(sides, sides, B, H, D, "bf16", [pol], layout=amskv.AMSKV_LAYOUT_PLANNED, borrow=True, fuse=True)
+        try:
+            outs, worst = r.run_layer(0, q, k, v)               # every step against the oracle, cache contents too
+            print("late dominant keys, D=%d, policy %s: worst max-abs %.3e" % (D, pol, worst))
+        finally:
+            r.close()
+
+
 # ------------------------------------------------------------------ Infinity-shaped (D=128, multi-tile queries)
 def test_config4_infinity_shape_small_batch():
     w = inp.config4(batch=1)
