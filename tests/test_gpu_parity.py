@@ -275,8 +275,9 @@ def test_large_values_do_not_overflow_softmax():
         r.close()
 
 
+@pytest.mark.parametrize("gain", [0.25, 3.0], ids=["jump23bits", "jump270bits"])
 @pytest.mark.parametrize("D", [64, 128])
-def test_late_dominant_keys_force_the_rescale_path(D):
+def test_late_dominant_keys_force_the_rescale_path(D, gain):
     """Scores that jump far above the running reference late in the key sequence: one key per scale is aligned with
     every query and scaled up, more so at each later scale, so the lazily updated reference of the online softmax
     has to move (and the accumulators be rescaled) in the last blocks of every kernel variant -- coarse, mid, wide."""
@@ -285,13 +286,14 @@ def test_late_dominant_keys_force_the_rescale_path(D):
     q, k, v = inp.iid_qkv(sides, B, H, D, "bf16", inp.layer_seed(6, 70 + D))
     q = [x.abs() for x in q]                                  # every query in the positive orthant ...
     for s, x in enumerate(k):
-        x[..., -1, :] = 0.25 * (s + 1)                        # ... so the last key of scale s scores ~ (s+1)*0.2*D above the rest
+        x[..., -1, :] = gain * (s + 1)                        # ... so the last key of scale s scores ~ gain*(s+1)*0.8*D above the rest:
+                                                              # with gain 3 a reference that failed to move would overflow fp32
     q, k, v = ([x.cuda() for x in t] for t in (q, k, v))
     for pol in [(0, 0, True), (2, 2, False)]:
         r = Runner(sides, sides, B, H, D, "bf16", [pol], layout=amskv.AMSKV_LAYOUT_PLANNED, borrow=True, fuse=True)
         try:
             outs, worst = r.run_layer(0, q, k, v)               # every step against the oracle, cache contents too
-            print("late dominant keys, D=%d, policy %s: worst max-abs %.3e" % (D, pol, worst))
+            print("late dominant keys, D=%d, gain %g, policy %s: worst max-abs %.3e" % (D, gain, pol, worst))
         finally:
             r.close()
 
