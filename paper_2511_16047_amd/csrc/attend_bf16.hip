@@ -72,6 +72,17 @@ __device__ __forceinline__ void lds_dma16(const char* g, char* lds_wave_base) {
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(m0v) : "memory", "m0");
 }
 
+// The same load with a wave-uniform 64-bit base in scalar registers and a 32-bit unsigned byte offset per
+// lane: the form the tile loop uses whenever all rows of a wave's part of a tile sit in one segment, so
+// that the address arithmetic of the common case runs on the scalar unit.
+__device__ __forceinline__ void lds_dma16_s(const char* base, unsigned lane_off, char* lds_wave_base) {
+  const unsigned m0v = (unsigned)(size_t)(AMSKV_LDS char*)lds_wave_base;
+  const unsigned long long b = (unsigned long long)base;
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)b), hi = __builtin_amdgcn_readfirstlane((unsigned)(b >> 32));
+  const unsigned long long bs = ((unsigned long long)hi << 32) | lo;
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_off), "s"(bs), "s"(m0v) : "memory", "m0");
+}
+
 // Compiler-visible use of a register value: the compiler places its own wait for the load that
 // produced it here (and not inside the tile loop, where it could not tell the first iteration
 // from the rest and would drain every outstanding load on each trip).
@@ -92,6 +103,17 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
 // it after the matrix instructions and before every later use.
 __device__ __forceinline__ void settle_mfma(f32x16& acc) { asm volatile("s_nop 11" : "+v"(acc)); }
 
+// Maximum of x over the two lane halves (lanes l and l^32), in every lane, without leaving the
+// vector ALU: v_permlane32_swap exchanges the upper half of its first operand with the lower half of
+// its second, so two copies of x become (lower, lower) and (upper, upper).  x comes out of inline
+// assembly, which the compiler's hazard tracking does not see as a vector write, so the wait states a
+// lane swap needs after one are spent here explicitly.
+__device__ __forceinline__ float half_max(float x) {
+  asm volatile("s_nop 1" : "+v"(x));
+  const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_int(x), __float_as_int(x), false, false);
+  return fmaxf(__int_as_float(sw[0]), __int_as_float(sw[1]));
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
@@ -103,47 +125,137 @@ struct TileLoader {
   static constexpr int CPR = D / 8;
   static constexpr int kRowsPerLoad = 64 / CPR;                            // rows covered by one wave-wide load
   static constexpr int kLoadsPerWave = kTileKeys / kRowsPerLoad / kWaves;  // per tensor
+  static constexpr int kRowsPerWave = kLoadsPerWave * kRowsPerLoad;        // consecutive rows of a tile one wave fetches
   static constexpr int kVmPerTile = 2 * kLoadsPerWave;                     // vector-memory ops per thread and tile
   static_assert(kLoadsPerWave >= 1 && kLoadsPerWave * kRowsPerLoad * kWaves == kTileKeys, "tile/wave split");
 
-  // Issue the loads of tile rows j0..j0+kTileKeys-1 of the virtual concatenation into one ring slot.
-  // x_tok: byte stride between the rows of the borrowed scale in the caller's tensors.
-  __device__ static __forceinline__ void issue(const char* kb, const char* vb, const char* xk, const char* xv, long long x_tok,
-                                               char* lds_k, char* lds_v, int j0, int t_kv, const SegTable& seg, int wave, int lane) {
+  // Where the rows this wave fetches sit.  Everything but `voff` is wave-uniform (scalar registers) and is
+  // carried from tile to tile: the wave's rows only move forward, by one tile per fetch, so while they stay
+  // inside one segment the next addresses are the last ones plus a constant, and the segment table is looked
+  // up again only when the first row passes the segment's end -- a handful of times per launch.
+  struct Stream {
+    int first;          // first virtual row of the wave's part of the next tile to fetch
+    int end;            // first virtual row past the segment that holds `first` (0: nothing looked up yet)
+    const char* k;      // address of row `first` (K, V) while first < end
+    const char* v;
+    long long step;     // bytes from a row to the row kTileKeys further on, in that segment
+    bool scalar_ok;     // the scalar-base form of the load can address the segment (32-bit lane offsets)
+    unsigned voff[kLoadsPerWave];  // per lane: byte offset of this lane's 16 bytes of load i from row `first`
+    // lane constants: row (inside the wave's part) and swizzled 16-byte chunk this lane fetches in load i
+    unsigned row[kLoadsPerWave], chunk[kLoadsPerWave];
+  };
+
+  __device__ static __forceinline__ void init(Stream& s, int wave, int lane) {
+    s.first = wave * kRowsPerWave;
+    s.end = 0;
+    s.k = s.v = nullptr;
+    s.step = 0;
+    s.scalar_ok = false;
+#pragma unroll
+    for (int i = 0; i < kLoadsPerWave; ++i) {
+      const int row = (wave * kLoadsPerWave + i) * kRowsPerLoad + lane / CPR;  // row inside the tile
+      s.chunk[i] = 16u * ((lane % CPR) ^ (row & 7));
+      s.row[i] = i * kRowsPerLoad + lane / CPR;
+      s.voff[i] = 0;
+    }
+  }
+
+  // Segment that holds virtual row s.first (< total), on the scalar unit.
+  __device__ static __forceinline__ void find(Stream& s, const SegTable& seg, const char* kb, const char* vb, const char* xk,
+                                              const char* xv, long long x_tok) {
+    int end = seg.virt_start[0] + seg.len[0], delta = seg.phys_off[0] - seg.virt_start[0];
+    for (int g = 1; g < seg.n; ++g)
+      if (s.first >= seg.virt_start[g]) {
+        end = seg.virt_start[g] + seg.len[g];
+        delta = seg.phys_off[g] - seg.virt_start[g];
+      }
+    const bool ext = s.first >= seg.ext_start;
+    if (ext) {
+      end = seg.total;
+      delta = -seg.ext_start;
+    }
+    const long long stride = ext ? x_tok : (long long)RB;
+    const long long at = (long long)(s.first + delta) * stride;
+    s.end = end;
+    s.k = (ext ? xk : kb) + at;
+    s.v = (ext ? xv : vb) + at;
+    s.step = stride * kTileKeys;
+    s.scalar_ok = stride < (1ll << 24);
+#pragma unroll
+    for (int i = 0; i < kLoadsPerWave; ++i) s.voff[i] = s.row[i] * (unsigned)stride + s.chunk[i];
+  }
+
+  // Fetch the wave's part of the next tile of the virtual concatenation into one ring slot (tiles are
+  // fetched in ascending order).  x_tok: byte stride between the rows of the borrowed scale in the caller's
+  // tensors.
+  __device__ static __forceinline__ void issue(Stream& s, const char* kb, const char* vb, const char* xk, const char* xv,
+                                               long long x_tok, char* lds_k, char* lds_v, int t_kv, const SegTable& seg,
+                                               int wave, int lane) {
+    const int first = s.first;
+    if (first >= s.end && first < t_kv) find(s, seg, kb, vb, xk, xv, x_tok);
+    s.first = first + kTileKeys;
+    if (first + kRowsPerWave <= s.end && s.scalar_ok) {
+      // every row of the wave's part lies in one segment: scalar base, lane-constant offsets
+#pragma unroll
+      for (int i = 0; i < kLoadsPerWave; ++i) {
+        const int blk = wave * kLoadsPerWave + i;
+        lds_dma16_s(s.k, s.voff[i], lds_k + blk * 1024);
+        lds_dma16_s(s.v, s.voff[i], lds_v + blk * 1024);
+      }
+      s.k += s.step;
+      s.v += s.step;
+      return;
+    }
+    // a segment boundary or the end of K~ inside the wave's rows: every lane locates its own row
+    const int j0 = first - wave * kRowsPerWave;
 #pragma unroll
     for (int i = 0; i < kLoadsPerWave; ++i) {
       const int blk = wave * kLoadsPerWave + i;  // which 1 KB block of the tile
       const int row = blk * kRowsPerLoad + lane / CPR;
-      const int cpos = lane % CPR;
       bool ext;
       const int row_at = locate_row(seg, min(j0 + row, t_kv - 1), ext);
-      const long long off = (long long)row_at * (ext ? x_tok : (long long)RB) + 16 * (cpos ^ (row & 7));
+      const long long off = (long long)row_at * (ext ? x_tok : (long long)RB) + s.chunk[i];
       lds_dma16((ext ? xk : kb) + off, lds_k + blk * 1024);
       lds_dma16((ext ? xv : vb) + off, lds_v + blk * 1024);
     }
   }
 
-  // Fused append: copy the rows of the landed tile that belong to the current (external) scale from
-  // LDS into the scale's slot of the cache.  Each wave stores exactly the 1 KB blocks it fetched, so
-  // lane i re-reads its own 16 bytes at block + 16*i and the swizzle of issue() is undone by using the
-  // same chunk mapping for the destination.  The stores are ordinary vector-memory operations issued
-  // before the next tile's loads; the tile waits of the caller stay valid because a vmcnt wait only
-  // counts operations (loads complete in order, and outstanding stores make the wait stricter, not laxer).
-  __device__ static __forceinline__ void write_back(char* kb, char* vb, const char* lds_k, const char* lds_v, int j0,
-                                                    int t_kv, const SegTable& seg, int wb_off, int wave, int lane) {
+  // Fused append: copy the rows of the landed tile (first row j0) that belong to the current (external)
+  // scale from LDS into the scale's slot of the cache.  Each wave stores exactly the 1 KB blocks it fetched,
+  // so lane i re-reads its own 16 bytes at block + 16*i and the swizzle of issue() is undone by using the same
+  // chunk mapping for the destination.  The stores are ordinary vector-memory operations issued before the
+  // next tile's loads; the tile waits of the caller stay valid because a vmcnt wait only counts operations
+  // (loads complete in order, and outstanding stores make the wait stricter, not laxer).
+  __device__ static __forceinline__ void write_back(const Stream& s, char* kb, char* vb, const char* lds_k, const char* lds_v,
+                                                    int j0, int t_kv, const SegTable& seg, int wb_off, int wave, int lane) {
+    const int first = j0 + wave * kRowsPerWave;  // wave-uniform
+    if (first >= seg.ext_start && first + kRowsPerWave <= t_kv) {  // all rows of the wave's part belong to the scale
+      const long long at = (long long)(wb_off + first - seg.ext_start) * RB;
+#pragma unroll
+      for (int i = 0; i < kLoadsPerWave; ++i) {
+        const int blk = wave * kLoadsPerWave + i;
+        const unsigned off = s.row[i] * RB + s.chunk[i];
+        *reinterpret_cast<uint4*>(kb + at + off) = *reinterpret_cast<const uint4*>(lds_k + blk * 1024 + 16 * lane);
+        *reinterpret_cast<uint4*>(vb + at + off) = *reinterpret_cast<const uint4*>(lds_v + blk * 1024 + 16 * lane);
+      }
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < kLoadsPerWave; ++i) {
       const int blk = wave * kLoadsPerWave + i;
-      const int row = blk * kRowsPerLoad + lane / CPR;
-      const int cpos = lane % CPR;
-      const int j = j0 + row;
+      const int j = j0 + blk * kRowsPerLoad + lane / CPR;
       if (j >= seg.ext_start && j < t_kv) {
-        const long long dst = (long long)(wb_off + j - seg.ext_start) * RB + 16 * (cpos ^ (row & 7));
+        const long long dst = (long long)(wb_off + j - seg.ext_start) * RB + s.chunk[i];
         *reinterpret_cast<uint4*>(kb + dst) = *reinterpret_cast<const uint4*>(lds_k + blk * 1024 + 16 * lane);
         *reinterpret_cast<uint4*>(vb + dst) = *reinterpret_cast<const uint4*>(lds_v + blk * 1024 + 16 * lane);
       }
     }
   }
+};
+
+template <bool B>
+struct Flag {
+  static constexpr bool value = B;
 };
 
 template <int D, int NQ, int kWaves, int kTileKeys, int kMinWavesPerSimd>
@@ -156,18 +268,22 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
   constexpr int DB = D / 32;  // 32-row blocks of O^T
   constexpr int BM = kWaves * 32 * NQ;
   constexpr int kTileBytes = kTileKeys * RB;
+  constexpr int kBlkBytes = 32 * RB;
   constexpr int kBlocksPerTile = kTileKeys / 32;
   // Ring of tiles in LDS: the tile in use, the one before it (the V rows of its last block are still being
-  // multiplied) and kAhead tiles in flight.  Head dim 64 keeps two in flight (its launches are bound by the
-  // memory pipeline and register count, not by LDS).  Head dim 128 is bound by latency at two waves per SIMD:
-  // one tile in flight makes the ring 48 KB, so three workgroups fit a CU -- three waves per SIMD, which
-  // measured 15 % faster on the 1024x1024 schedule than two waves with two tiles in flight.
+  // multiplied) and kAhead tiles in flight.  Head dim 128 is bound by latency at two waves per SIMD: one tile
+  // in flight makes the ring 48 KB, so three workgroups fit a CU -- three waves per SIMD, which measured 15 %
+  // faster on the 1024x1024 schedule than two waves with two tiles in flight.
   constexpr int kAhead = D == 128 ? 1 : 2;
   constexpr int kStages = kAhead + 2;
+  constexpr int kRing = kStages * kTileBytes;
   constexpr int VM = Loader::kVmPerTile;
+  // Fetch the K fragments of block g+1 into registers while the softmax of block g runs (16 registers at head
+  // dim 64; the head-dim-128 configuration has none to spare, and one-block tiles would need a fifth ring slot).
+  constexpr bool kPrefetchK = D == 64 && kBlocksPerTile == 2;
 
-  __shared__ __align__(1024) char lds_k[kStages * kTileBytes];
-  __shared__ __align__(1024) char lds_v[kStages * kTileBytes];
+  __shared__ __align__(1024) char lds_k[kRing];
+  __shared__ __align__(1024) char lds_v[kRing];
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -197,7 +313,7 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
   // fused append: the workgroup of the first query tile also fills the current scale's slot
   const bool write_back = ext_kv.wb_off >= 0 && (within >> 3) == 0;
 
-  // ---- prologue: the Q fragments (ordinary loads), then two tiles; everything is in flight
+  // ---- prologue: the Q fragments (ordinary loads), then kAhead tiles; everything is in flight
   // together, and the Q values are settled once, before the tile loop.
   // Q fragments: B operand of S^T = K Q^T; lane (r,h) holds Q[row r][16t + 8h .. +8).  Query rows
   // past T_q re-read the last row; their results are never stored.
@@ -208,10 +324,43 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
 #pragma unroll
     for (int t = 0; t < KS; ++t) qf[n][t] = *reinterpret_cast<const bf16x8*>(q_unit + row * io.q.tok + 32 * t + 16 * h);
   }
+  typename Loader::Stream stream;
+  Loader::init(stream, wave, lane);
+  // ring positions (byte offsets, the same in the K and the V ring), all wave-uniform
+  int fetch_off = 0;  // slot the next tile to fetch goes into
+  int sync_off = 0;   // slot of the next tile to become readable
+  auto ring_next = [](int off, int by) {
+    off += by;
+    return off == kRing ? 0 : off;
+  };
 #pragma unroll
   for (int st = 0; st < kAhead; ++st)
-    if (st < n_tiles)
-      Loader::issue(kb, vb, xk, xv, x_tok, lds_k + st * kTileBytes, lds_v + st * kTileBytes, st * kTileKeys, t_kv, seg, wave, lane);
+    if (st < n_tiles) {
+      Loader::issue(stream, kb, vb, xk, xv, x_tok, lds_k + fetch_off, lds_v + fetch_off, t_kv, seg, wave, lane);
+      fetch_off = ring_next(fetch_off, kTileBytes);
+    }
+
+  // Tile `it` becomes readable: this wave's loads of it have landed (the kAhead - 1 younger tiles may stay in
+  // flight), the barrier extends that to every wave's part, and it also retires the oldest ring slot, which
+  // the next tile to fetch goes into.  Called for it = 0, 1, ... by every wave of the workgroup.
+  auto tile_sync = [&](int it) {
+    if (kAhead > 1 && it + 1 < n_tiles) wait_vmcnt<VM*(kAhead - 1)>();
+    else wait_vmcnt<0>();
+    __syncthreads();
+    if (write_back && (it + 1) * kTileKeys > seg.ext_start)
+      Loader::write_back(stream, kb, vb, lds_k + sync_off, lds_v + sync_off, it * kTileKeys, t_kv, seg, ext_kv.wb_off, wave, lane);
+    sync_off = ring_next(sync_off, kTileBytes);
+    if (it + kAhead < n_tiles) {
+      Loader::issue(stream, kb, vb, xk, xv, x_tok, lds_k + fetch_off, lds_v + fetch_off, t_kv, seg, wave, lane);
+      fetch_off = ring_next(fetch_off, kTileBytes);
+    }
+  };
+  tile_sync(0);
+  if (!wave_active) {
+    // no query rows (T_q is not a multiple of the workgroup's rows): this wave only fetches its part of every tile
+    for (int it = 1; it < n_tiles; ++it) tile_sync(it);
+    return;
+  }
 
 #pragma unroll
   for (int n = 0; n < NQ; ++n)
@@ -225,11 +374,11 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
     for (int d = 0; d < DB; ++d)
 #pragma unroll
       for (int v = 0; v < 16; ++v) oacc[n][d][v] = 0.f;
-  float run_max[NQ], run_sum[NQ];
+  float run_mc[NQ], run_sum[NQ];  // softmax reference times c = softmax scale * log2(e); sum of 2^(s*c - reference)
   bf16x8 pf[NQ][2];  // probabilities of the previous block, two K-steps of 16 keys
 #pragma unroll
   for (int n = 0; n < NQ; ++n) {
-    run_max[n] = -INFINITY;
+    run_mc[n] = -INFINITY;
     run_sum[n] = 0.f;
 #pragma unroll
     for (int u = 0; u < 2; ++u)
@@ -251,38 +400,36 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
   int k_off[KS];  // K fragment byte offsets inside a 32-key block
 #pragma unroll
   for (int t = 0; t < KS; ++t) k_off[t] = r * RB + 16 * ((2 * t + h) ^ (r & 7));
-  const int xchg_addr = (lane ^ 32) << 2;  // ds_bpermute source of the other lane half
 
-  // V rows of the previous block (first iteration: the block itself, multiplied by pf = 0)
-  const char* v_prev = lds_v;
+  // ring positions of the blocks a step touches: g-1 (V rows of the second product; first step: block 0
+  // itself, multiplied by pf = 0), g, and g+1 (K prefetch)
+  int off_prev = 0, off_cur = 0, off_next = kBlkBytes == kRing ? 0 : kBlkBytes;
   float alpha[NQ];
   bool any_rescale = false;  // the rescale decided at block g is applied at the top of block g+1
 #pragma unroll
   for (int n = 0; n < NQ; ++n) alpha[n] = 1.f;
 
-  // One 32-key block: S^T of block g, its softmax, and O^T += V^T P^T of block g-1 (probabilities p_in,
-  // packed one step earlier); the new probabilities go to p_out.  The loop below alternates two register
-  // sets for p so that no copies are needed.
-  auto block_step = [&](int g, const bf16x8 (&p_in)[NQ][2], bf16x8 (&p_out)[NQ][2]) {
-    const int it = g / kBlocksPerTile;
-    const int sub = g % kBlocksPerTile;
-    if (sub == 0) {
-      // wait for tile `it`; the kAhead - 1 younger tiles may stay in flight
-      if (kAhead > 1 && it + 1 < n_tiles) wait_vmcnt<VM*(kAhead - 1)>();
-      else wait_vmcnt<0>();
-      __syncthreads();  // every wave's part of tile `it` has landed; every wave is done with tile it-2
-      if (write_back && (it + 1) * kTileKeys > seg.ext_start)
-        Loader::write_back(kb, vb, lds_k + (it % kStages) * kTileBytes, lds_v + (it % kStages) * kTileBytes,
-                           it * kTileKeys, t_kv, seg, ext_kv.wb_off, wave, lane);
-      if (it + kAhead < n_tiles) {  // into the slot of tile it-2, which the barrier above has just retired
-        const int slot = (it + kAhead) % kStages;
-        Loader::issue(kb, vb, xk, xv, x_tok, lds_k + slot * kTileBytes, lds_v + slot * kTileBytes, (it + kAhead) * kTileKeys, t_kv,
-                      seg, wave, lane);
-      }
-    }
-    if (!wave_active) return;
-    // ---- (rarely) move the accumulators to the running max chosen in the previous step;
-    // placed here so that the softmax and the matrix products below stay one basic block
+  // K fragments (A operand of S^T = K Q^T) of the block at ring position `off`, LDS -> registers
+  bf16x8 kf[KS];
+  auto load_k = [&](int off) {
+#pragma unroll
+    for (int t = 0; t < KS; ++t) kf[t] = *reinterpret_cast<const bf16x8*>(lds_k + off + k_off[t]);
+  };
+  if (kPrefetchK) load_k(0);
+  int next_tile = 1;  // next tile to synchronise on
+
+  // One 32-key block g: S^T, its softmax, and O^T += V^T P^T of block g-1, whose probabilities pf were
+  // packed one step earlier and are replaced by those of g as the step goes.
+  //   sync_next: (K prefetch only) g is the last block of its tile and another tile follows: the barrier for
+  //     that tile sits behind the score products, so that the fragments of the new tile's first block are
+  //     fetched while the softmax of g runs.  Every wave has then finished step g-1 (V rows of block g-2 = last
+  //     block of the tile two back, which the barrier retires), and what the rest of step g still reads (V rows
+  //     of block g-1) lies in the tile one back.  Without K prefetch the caller synchronises in front of the
+  //     first block of a tile instead.
+  //   has_next: a block g+1 exists (K prefetch)
+  //   ragged: g is the last block and t_kv is not a multiple of 32: keys past the end get zero weight
+  auto block_step = [&](auto sync_next, auto has_next, bool ragged) {
+    // ---- (rarely) move the accumulators to the reference chosen in the previous step
     if (any_rescale) {
 #pragma unroll
       for (int n = 0; n < NQ; ++n)
@@ -291,23 +438,22 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
 #pragma unroll
           for (int v = 0; v < 16; ++v) oacc[n][d][v] *= alpha[n];
     }
-    const int blk_off = (it % kStages) * kTileBytes + sub * 32 * RB;
-    const char* tk = lds_k + blk_off;
-    const char* tv = lds_v + blk_off;
-
     // ---- S^T = K Q^T for this 32-key block
+    if (!kPrefetchK) load_k(off_cur);
     f32x16 sacc[NQ];
 #pragma unroll
     for (int n = 0; n < NQ; ++n)
 #pragma unroll
       for (int v = 0; v < 16; ++v) sacc[n][v] = 0.f;
 #pragma unroll
-    for (int t = 0; t < KS; ++t) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(tk + k_off[t]);
+    for (int t = 0; t < KS; ++t)
 #pragma unroll
-      for (int n = 0; n < NQ; ++n) sacc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[n][t], sacc[n], 0, 0, 0);
+      for (int n = 0; n < NQ; ++n) sacc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[n][t], sacc[n], 0, 0, 0);
+    if (kPrefetchK) {
+      if (decltype(sync_next)::value) tile_sync(next_tile++);
+      if (decltype(has_next)::value) load_k(off_next);
     }
-    if (g == n_blocks - 1 && (t_kv & 31) != 0) {  // ragged tail: keys past the end get zero weight
+    if (ragged) {
       const int valid = t_kv & 31;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
@@ -319,77 +465,94 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
       }
     }
 
-    // ---- softmax statistics of this block (vector ALU)
-    any_rescale = false;
+    // ---- softmax reference of this block (vector ALU).  Lazy: the reference (kept multiplied by c) stays
+    // while no score of the block exceeds it by 2^kMaxLag or more.  Each lane tests the 16 keys it holds; only
+    // when some lane of the wave trips are the two lane halves combined and the reference moved.
+    float mine[NQ];
+    bool trip = false;
 #pragma unroll
     for (int n = 0; n < NQ; ++n) {
       settle_mfma(sacc[n]);
-      float mx = max3(sacc[n][0], sacc[n][1], sacc[n][2]);
+      const float a0 = max3(sacc[n][0], sacc[n][1], sacc[n][2]), a1 = max3(sacc[n][3], sacc[n][4], sacc[n][5]);
+      const float a2 = max3(sacc[n][6], sacc[n][7], sacc[n][8]), a3 = max3(sacc[n][9], sacc[n][10], sacc[n][11]);
+      const float a4 = max3(sacc[n][12], sacc[n][13], sacc[n][14]);
+      const float b0 = max3(a0, a1, a2), b1 = max3(a3, a4, sacc[n][15]);
+      mine[n] = max3(b0, b1, b1);
+      // NaN (-inf against -inf: a lane whose keys are all past the end, first block) compares false
+      trip |= __builtin_amdgcn_ballot_w64(fmaf(mine[n], scale_log2e, -run_mc[n]) > kMaxLag) != 0;
+    }
+    any_rescale = trip;
+    if (trip) {
 #pragma unroll
-      for (int v = 3; v < 15; v += 2) mx = max3(mx, sacc[n][v], sacc[n][v + 1]);
-      const float mine = max3(mx, sacc[n][15], sacc[n][15]);
-      const float other = __int_as_float(__builtin_amdgcn_ds_bpermute(xchg_addr, __float_as_int(mine)));
-      mx = max3(mine, other, other);
-      // lazy rescale: keep the old reference while the block's max exceeds it by < 2^kMaxLag
-      const bool lag = (mx - run_max[n]) * scale_log2e > kMaxLag;
-      const float new_max = lag ? mx : run_max[n];
-      alpha[n] = __builtin_amdgcn_exp2f((run_max[n] - new_max) * scale_log2e);  // 1 when unchanged, 0 on the first block
-      run_max[n] = new_max;
-      any_rescale |= (__builtin_amdgcn_ballot_w64(lag) != 0);
+      for (int n = 0; n < NQ; ++n) {
+        const float full = half_max(mine[n]) * scale_log2e;  // finite: key 0 of the block is valid for every query
+        const float new_mc = full - run_mc[n] > kMaxLag ? full : run_mc[n];
+        alpha[n] = __builtin_amdgcn_exp2f(run_mc[n] - new_mc);  // 1 when unchanged, 0 on the first block
+        run_sum[n] *= alpha[n];
+        run_mc[n] = new_mc;
+      }
     }
 
-    // ---- one basic block: probabilities of this block (vector ALU) next to O^T += V^T P^T of the
-    // previous block (matrix cores); the two share no data
+    // ---- probabilities of this block (vector ALU) next to O^T += V^T P^T of the previous block (matrix
+    // cores), one K-step of 16 keys at a time: the matrix instructions of K-step u read the old pf[.][u] when
+    // they issue, after which the new probabilities of keys 16u..16u+15 overwrite it.
+    // p = 2^(s*c - m*c) in fp32; the row sum is taken over these, the second product uses them rounded to bf16.
+    float sum[NQ][2];
 #pragma unroll
     for (int n = 0; n < NQ; ++n) {
-      // p = 2^(s*c - m*c), rounded to bf16 in pairs; the row sum is taken over the ROUNDED values
-      // (the same weights the second product uses) with one v_dot2c_f32_bf16 per pair
-      const float mc = run_max[n] * scale_log2e;
-      const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-      float sum = run_sum[n] * alpha[n];
-#pragma unroll
-      for (int v = 0; v < 16; v += 2) {
-        bf16x2 pk;
-        pk[0] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[n][v], scale_log2e, -mc));
-        pk[1] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sacc[n][v + 1], scale_log2e, -mc));
-        sum = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, sum, false);
-        p_out[n][v >> 3][v & 7] = pk[0];
-        p_out[n][v >> 3][(v & 7) + 1] = pk[1];
-      }
-      run_sum[n] = sum;
+      sum[n][0] = run_sum[n];
+      sum[n][1] = 0.f;
     }
 #pragma unroll
-    for (int d = 0; d < DB; ++d) {
-      const char* vp = v_prev + v_base[d];
+    for (int u = 0; u < 2; ++u) {
 #pragma unroll
-      for (int u = 0; u < 2; ++u) {
+      for (int d = 0; d < DB; ++d) {
+        const char* vp = lds_v + off_prev + v_base[d];
         const bf16x4 lo = lds_read_tr16(vp + (16 * u) * RB);
         const bf16x4 hi = lds_read_tr16(vp + (16 * u + 8) * RB);
         bf16x8 a;
         a[0] = lo[0]; a[1] = lo[1]; a[2] = lo[2]; a[3] = lo[3];
         a[4] = hi[0]; a[5] = hi[1]; a[6] = hi[2]; a[7] = hi[3];
 #pragma unroll
-        for (int n = 0; n < NQ; ++n) oacc[n][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p_in[n][u], oacc[n][d], 0, 0, 0);
+        for (int n = 0; n < NQ; ++n) oacc[n][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[n][u], oacc[n][d], 0, 0, 0);
       }
+#pragma unroll
+      for (int n = 0; n < NQ; ++n)
+#pragma unroll
+        for (int v = 8 * u; v < 8 * u + 8; v += 2) {
+          const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[n][v], scale_log2e, -run_mc[n]));
+          const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[n][v + 1], scale_log2e, -run_mc[n]));
+          sum[n][0] += p0;
+          sum[n][1] += p1;
+          pf[n][u][v & 7] = (__bf16)p0;
+          pf[n][u][(v & 7) + 1] = (__bf16)p1;
+        }
     }
-    v_prev = tv;
+#pragma unroll
+    for (int n = 0; n < NQ; ++n) run_sum[n] = sum[n][0] + sum[n][1];
+    off_prev = off_cur;
+    off_cur = off_next;
+    off_next = ring_next(off_next, kBlkBytes);
   };
 
-  bf16x8 pf2[NQ][2];  // second register set for the probabilities
-  int g = 0;
-  for (; g + 1 < n_blocks; g += 2) {
-    block_step(g, pf, pf2);
-    block_step(g + 1, pf2, pf);
-  }
-  if (g < n_blocks) {  // odd block count: finish through the second set, then bring it back
-    block_step(g, pf, pf2);
-#pragma unroll
-    for (int n = 0; n < NQ; ++n)
-#pragma unroll
-      for (int u = 0; u < 2; ++u) pf[n][u] = pf2[n][u];
+  const bool ragged = (t_kv & 31) != 0;
+  constexpr Flag<true> yes;
+  constexpr Flag<false> no;
+  if (kPrefetchK) {
+    // two blocks per tile: the loop takes the tiles that have a successor, the tail the last tile (1 or 2 blocks)
+    for (int it = 0; it + 1 < n_tiles; ++it) {
+      block_step(no, yes, false);
+      block_step(yes, yes, false);
+    }
+    if (!(n_blocks & 1)) block_step(no, yes, false);
+    block_step(no, no, ragged);
+  } else {
+    for (int g = 0; g < n_blocks; ++g) {
+      if (g > 0 && g % kBlocksPerTile == 0) tile_sync(next_tile++);
+      block_step(no, no, ragged && g == n_blocks - 1);
+    }
   }
 
-  if (!wave_active) return;
   if (any_rescale) {
 #pragma unroll
     for (int n = 0; n < NQ; ++n)
@@ -401,7 +564,7 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
   // ---- drain: the last block's O^T += V^T P^T
 #pragma unroll
   for (int d = 0; d < DB; ++d) {
-    const char* vp = v_prev + v_base[d];
+    const char* vp = lds_v + off_prev + v_base[d];
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       const bf16x4 lo = lds_read_tr16(vp + (16 * u) * RB);
