@@ -60,8 +60,9 @@ struct MoveList {
 #if defined(__HIPCC__)
 // Byte offset of row 0 of unit bh = b*heads + h inside a caller tensor.
 __device__ __forceinline__ long long unit_offset(const RowMap& m, long long bh, int heads) {
-  const long long b = bh / heads;
-  return b * m.batch + (bh - b * heads) * m.head;
+  if (m.batch == m.head * heads) return bh * m.head;  // units back to back (head-major tensors): no division
+  const unsigned b = (unsigned)bh / (unsigned)heads;   // bh < 2^24 (checked at create)
+  return (long long)b * m.batch + (long long)((unsigned)bh - b * (unsigned)heads) * m.head;
 }
 
 // Virtual row j of K~/V~ -> row index inside the layer's cache region of this (b,h), or, for a

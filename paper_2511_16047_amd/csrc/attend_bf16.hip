@@ -192,9 +192,9 @@ struct TileLoader {
                                                long long x_tok, char* lds_k, char* lds_v, int t_kv, const SegTable& seg,
                                                int wave, int lane) {
     const int first = s.first;
-    if (first >= s.end && first < t_kv) find(s, seg, kb, vb, xk, xv, x_tok);
+    if (__builtin_expect(first >= s.end && first < t_kv, 0)) find(s, seg, kb, vb, xk, xv, x_tok);
     s.first = first + kTileKeys;
-    if (first + kRowsPerWave <= s.end && s.scalar_ok) {
+    if (__builtin_expect(first + kRowsPerWave <= s.end && s.scalar_ok, 1)) {
       // every row of the wave's part lies in one segment: scalar base, lane-constant offsets
 #pragma unroll
       for (int i = 0; i < kLoadsPerWave; ++i) {
@@ -229,7 +229,7 @@ struct TileLoader {
   __device__ static __forceinline__ void write_back(const Stream& s, char* kb, char* vb, const char* lds_k, const char* lds_v,
                                                     int j0, int t_kv, const SegTable& seg, int wb_off, int wave, int lane) {
     const int first = j0 + wave * kRowsPerWave;  // wave-uniform
-    if (first >= seg.ext_start && first + kRowsPerWave <= t_kv) {  // all rows of the wave's part belong to the scale
+    if (__builtin_expect(first >= seg.ext_start && first + kRowsPerWave <= t_kv, 1)) {  // all rows of the wave's part belong to the scale
       const long long at = (long long)(wb_off + first - seg.ext_start) * RB;
 #pragma unroll
       for (int i = 0; i < kLoadsPerWave; ++i) {
@@ -293,11 +293,18 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
   // XCD-aware unit mapping: consecutive workgroup ids go round-robin to the 8 XCDs, each with its own L2,
   // so the query tiles of one (b,h) are given ids 8 apart: they land on the same XCD back to back and the
   // second one finds K~/V~ in that L2 instead of fetching them from HBM again.
-  const int per_group = 8 * n_qtiles;
-  const int within = blockIdx.x % per_group;
-  const long long bh = (long long)(blockIdx.x / per_group) * 8 + (within & 7);
+  int bh_i, q_tile;
+  if (n_qtiles == 1) {  // the common case, spelled out: it needs no division
+    bh_i = blockIdx.x;
+    q_tile = 0;
+  } else {
+    const unsigned per_group = 8u * n_qtiles, group = blockIdx.x / per_group, within = blockIdx.x - group * per_group;
+    bh_i = group * 8 + (within & 7);
+    q_tile = within >> 3;
+  }
+  const long long bh = bh_i;
   if (bh >= n_bh) return;  // whole workgroup leaves together (n_bh not a multiple of 8)
-  const int q_base = (within >> 3) * BM + wave * (32 * NQ);
+  const int q_base = q_tile * BM + wave * (32 * NQ);
   const bool wave_active = q_base < t_q;
   const int t_kv = seg.total;
   const int n_tiles = (t_kv + kTileKeys - 1) / kTileKeys;
@@ -309,21 +316,12 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
   const char* xk = (const char*)ext_kv.k + x_unit;
   const char* xv = (const char*)ext_kv.v + x_unit;
   const long long x_tok = io.kv.tok;
-  const char* q_unit = (const char*)q + unit_offset(io.q, bh, io.heads);
   // fused append: the workgroup of the first query tile also fills the current scale's slot
-  const bool write_back = ext_kv.wb_off >= 0 && (within >> 3) == 0;
+  const bool write_back = ext_kv.wb_off >= 0 && q_tile == 0;
 
-  // ---- prologue: the Q fragments (ordinary loads), then kAhead tiles; everything is in flight
-  // together, and the Q values are settled once, before the tile loop.
-  // Q fragments: B operand of S^T = K Q^T; lane (r,h) holds Q[row r][16t + 8h .. +8).  Query rows
-  // past T_q re-read the last row; their results are never stored.
-  bf16x8 qf[NQ][KS];
-#pragma unroll
-  for (int n = 0; n < NQ; ++n) {
-    const int row = min(q_base + 32 * n + r, t_q - 1);
-#pragma unroll
-    for (int t = 0; t < KS; ++t) qf[n][t] = *reinterpret_cast<const bf16x8*>(q_unit + row * io.q.tok + 32 * t + 16 * h);
-  }
+  // ---- prologue: fill the whole ring (the steady state keeps kAhead tiles in flight; at the start nothing is
+  // in use yet, and the first tiles are what the workgroup waits for), then the Q fragments with ordinary
+  // loads; everything is in flight together, and the Q values are settled once, before the tile loop.
   typename Loader::Stream stream;
   Loader::init(stream, wave, lane);
   // ring positions (byte offsets, the same in the K and the V ring), all wave-uniform
@@ -334,31 +332,55 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
     return off == kRing ? 0 : off;
   };
 #pragma unroll
-  for (int st = 0; st < kAhead; ++st)
+  for (int st = 0; st < kStages; ++st)
     if (st < n_tiles) {
       Loader::issue(stream, kb, vb, xk, xv, x_tok, lds_k + fetch_off, lds_v + fetch_off, t_kv, seg, wave, lane);
       fetch_off = ring_next(fetch_off, kTileBytes);
     }
+  // Q fragments: B operand of S^T = K Q^T; lane (r,h) holds Q[row r][16t + 8h .. +8).  Query rows
+  // past T_q re-read the last row; their results are never stored.
+  const char* q_unit = (const char*)q + unit_offset(io.q, bh, io.heads);
+  bf16x8 qf[NQ][KS];
+#pragma unroll
+  for (int n = 0; n < NQ; ++n) {
+    const int row = min(q_base + 32 * n + r, t_q - 1);
+#pragma unroll
+    for (int t = 0; t < KS; ++t) qf[n][t] = *reinterpret_cast<const bf16x8*>(q_unit + row * io.q.tok + 32 * t + 16 * h);
+  }
 
-  // Tile `it` becomes readable: this wave's loads of it have landed (the kAhead - 1 younger tiles may stay in
-  // flight), the barrier extends that to every wave's part, and it also retires the oldest ring slot, which
-  // the next tile to fetch goes into.  Called for it = 0, 1, ... by every wave of the workgroup.
-  auto tile_sync = [&](int it) {
-    if (kAhead > 1 && it + 1 < n_tiles) wait_vmcnt<VM*(kAhead - 1)>();
-    else wait_vmcnt<0>();
+  // Tile `it` becomes readable: this wave's loads of it have landed (younger tiles may stay in flight), the
+  // barrier extends that to every wave's part, and it also retires the oldest ring slot, which the next tile
+  // to fetch goes into.  Called for it = 0, 1, ... by every wave of the workgroup.
+  // Fetch schedule: tiles 0..kStages-1 are requested in the prologue; from it = 2 on (the first barrier that
+  // retires a slot) tile it+kAhead is requested here, so it+1 .. it+kAhead are in flight behind the barrier.
+  // steady: the caller knows that it >= 2 and that tile it+kAhead exists (nothing to test on the common path).
+  auto tile_sync = [&](int it, auto steady) {
+    constexpr bool kSteady = decltype(steady)::value;
+    if (kSteady) {
+      wait_vmcnt<VM*(kAhead - 1)>();
+    } else {
+      // tiles requested so far, minus those up to `it`, may stay in flight
+      const int ahead = min(n_tiles, max(kStages, it + kAhead)) - (it + 1);
+      if (ahead >= 3 && kStages >= 4) wait_vmcnt<VM * 3>();
+      else if (ahead == 2) wait_vmcnt<VM * 2>();
+      else if (ahead == 1) wait_vmcnt<VM>();
+      else wait_vmcnt<0>();
+    }
     __syncthreads();
     if (write_back && (it + 1) * kTileKeys > seg.ext_start)
       Loader::write_back(stream, kb, vb, lds_k + sync_off, lds_v + sync_off, it * kTileKeys, t_kv, seg, ext_kv.wb_off, wave, lane);
     sync_off = ring_next(sync_off, kTileBytes);
-    if (it + kAhead < n_tiles) {
+    if (kSteady || (it >= 2 && it + kAhead < n_tiles)) {
       Loader::issue(stream, kb, vb, xk, xv, x_tok, lds_k + fetch_off, lds_v + fetch_off, t_kv, seg, wave, lane);
       fetch_off = ring_next(fetch_off, kTileBytes);
     }
   };
-  tile_sync(0);
+  constexpr Flag<true> yes;
+  constexpr Flag<false> no;
+  tile_sync(0, no);
   if (!wave_active) {
     // no query rows (T_q is not a multiple of the workgroup's rows): this wave only fetches its part of every tile
-    for (int it = 1; it < n_tiles; ++it) tile_sync(it);
+    for (int it = 1; it < n_tiles; ++it) tile_sync(it, no);
     return;
   }
 
@@ -428,9 +450,9 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
   //     first block of a tile instead.
   //   has_next: a block g+1 exists (K prefetch)
   //   ragged: g is the last block and t_kv is not a multiple of 32: keys past the end get zero weight
-  auto block_step = [&](auto sync_next, auto has_next, bool ragged) {
+  auto block_step = [&](auto sync_next, auto steady, auto has_next, bool ragged) {
     // ---- (rarely) move the accumulators to the reference chosen in the previous step
-    if (any_rescale) {
+    if (__builtin_expect(any_rescale, 0)) {
 #pragma unroll
       for (int n = 0; n < NQ; ++n)
 #pragma unroll
@@ -450,7 +472,7 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
 #pragma unroll
       for (int n = 0; n < NQ; ++n) sacc[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[t], qf[n][t], sacc[n], 0, 0, 0);
     if (kPrefetchK) {
-      if (decltype(sync_next)::value) tile_sync(next_tile++);
+      if (decltype(sync_next)::value) tile_sync(next_tile++, steady);
       if (decltype(has_next)::value) load_k(off_next);
     }
     if (ragged) {
@@ -482,7 +504,7 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
       trip |= __builtin_amdgcn_ballot_w64(fmaf(mine[n], scale_log2e, -run_mc[n]) > kMaxLag) != 0;
     }
     any_rescale = trip;
-    if (trip) {
+    if (__builtin_expect(trip, 0)) {
 #pragma unroll
       for (int n = 0; n < NQ; ++n) {
         const float full = half_max(mine[n]) * scale_log2e;  // finite: key 0 of the block is valid for every query
@@ -536,20 +558,29 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
   };
 
   const bool ragged = (t_kv & 31) != 0;
-  constexpr Flag<true> yes;
-  constexpr Flag<false> no;
   if (kPrefetchK) {
-    // two blocks per tile: the loop takes the tiles that have a successor, the tail the last tile (1 or 2 blocks)
-    for (int it = 0; it + 1 < n_tiles; ++it) {
-      block_step(no, yes, false);
-      block_step(yes, yes, false);
+    // two blocks per tile.  First the tiles whose barrier has nothing to test (the tile it fetches exists),
+    // then the ones near the end of the stream, then the last tile (1 or 2 blocks).
+    int it = 0;
+    if (n_tiles > 1) {  // the barrier of tile 1 belongs to the start-up schedule
+      block_step(no, no, yes, false);
+      block_step(yes, no, yes, false);
+      it = 1;
     }
-    if (!(n_blocks & 1)) block_step(no, yes, false);
-    block_step(no, no, ragged);
+    for (; it + 1 + kAhead < n_tiles; ++it) {
+      block_step(no, no, yes, false);
+      block_step(yes, yes, yes, false);
+    }
+    for (; it + 1 < n_tiles; ++it) {
+      block_step(no, no, yes, false);
+      block_step(yes, no, yes, false);
+    }
+    if (!(n_blocks & 1)) block_step(no, no, yes, false);
+    block_step(no, no, no, ragged);
   } else {
     for (int g = 0; g < n_blocks; ++g) {
-      if (g > 0 && g % kBlocksPerTile == 0) tile_sync(next_tile++);
-      block_step(no, no, ragged && g == n_blocks - 1);
+      if (g > 0 && g % kBlocksPerTile == 0) tile_sync(next_tile++, no);
+      block_step(no, no, no, ragged && g == n_blocks - 1);
     }
   }
 
