@@ -18,14 +18,26 @@ def _f64(t):
     return t.detach().to("cpu", torch.float64).numpy()
 
 
-def _check(h, layer, s, tokens, q_dev, k_all, H, softmax_scale=None):
-    """Compare the library's density of step s with the oracle's over the library's own group list."""
+def _runs_by_scale(ids, tokens):
+    """Token ids -> maximal runs of consecutive ids that stay inside one scale, as (first id, length)."""
+    st = orc.scale_starts(tokens)
+    scale_of = orc.scale_of_token(tokens)
+    out = []
+    for g in ids:
+        if out and out[-1][0] + out[-1][1] == g and scale_of[g] == scale_of[out[-1][0]]:
+            out[-1][1] += 1
+        else:
+            out.append([g, 1])
+    return [(a, n) for a, n in out]
+
+
+def _check(h, layer, s, tokens, q_dev, k_all, H, pieces, rows, softmax_scale=None):
+    """Compare the library's density of step s with the oracle's.  `pieces` (groups of keys) and `rows` (what the
+    queries of s may see) come from the oracle's own kept set / token list; the library's group list must be
+    the same list."""
     st = orc.scale_starts(tokens)
     segs = amskv.amskv_cache_segments(h, layer)
-    pieces = [(st[sc] + first, ln) for sc, first, _, ln in segs]
-    rows = np.zeros((tokens[s], sum(tokens)), dtype=bool)
-    for a, n in pieces:
-        rows[:, a: a + n] = True
+    assert [(st[sc] + first, ln) for sc, first, _, ln in segs] == list(pieces)
     want_d, want_m = orc.attention_density(_f64(q_dev), k_all, rows, pieces, softmax_scale)
     got_d, got_m = amskv.amskv_attention_density(h, layer, s, q_dev, H)
     got_d, got_m = np.asarray(got_d), np.asarray(got_m)
@@ -34,6 +46,13 @@ def _check(h, layer, s, tokens, q_dev, k_all, H, softmax_scale=None):
     assert np.allclose(got_d, want_d, rtol=2e-4, atol=1e-5)
     assert np.allclose(got_m.sum(axis=-1), tokens[s], rtol=1e-4)
     return got_d
+
+
+def _window_view(tokens, pol, s):
+    st = orc.scale_starts(tokens)
+    pieces = [(st[k], tokens[k]) for k in orc.kept_scales(pol, s)]
+    rows = orc.allow_mask(tokens, pol)[st[s]: st[s] + tokens[s]]
+    return pieces, rows
 
 
 @pytest.mark.parametrize("flags", [dict(), dict(layout=amskv.AMSKV_LAYOUT_PLANNED, borrow_unretained=True, fuse_append=True)],
@@ -57,11 +76,12 @@ def test_density_scale_window(D, flags):
             for l, pol in enumerate(pols):
                 amskv.amskv_append_scale(h, l, s, kd[s], vd[s])
                 assert [x[0] for x in amskv.amskv_cache_segments(h, l)] == orc.kept_scales(pol, s)
-                _check(h, l, s, tokens, qd[s], k_all, H)           # before the attention of the step ...
+                pieces, rows = _window_view(tokens, pol, s)
+                _check(h, l, s, tokens, qd[s], k_all, H, pieces, rows)   # before the attention of the step ...
                 o = torch.empty_like(qd[s])
                 amskv.amskv_attend(h, l, s, qd[s], o)
                 if s in (4, 9):
-                    _check(h, l, s, tokens, qd[s], k_all, H)       # ... and after it (fused append has filled the slot)
+                    _check(h, l, s, tokens, qd[s], k_all, H, pieces, rows)   # ... and after it (fused append has filled the slot)
     finally:
         amskv.amskv_cache_destroy(h)
 
@@ -77,6 +97,11 @@ def test_density_token_budget_partial_groups():
     need = amskv.amskv_cache_required_bytes(2, H, D, sides, sides, B, BF16, None, 0.3, budgets=budgets)
     arena = torch.empty(need, dtype=torch.uint8, device="cuda")
     h = amskv.amskv_cache_create(2, H, D, sides, sides, B, BF16, None, 0.3, arena=arena, budgets=budgets)
+    # the oracle's own token lists: Algorithm 1 with the outcome of the Eq. 3 test fixed by the thresholds
+    # (-2: never below, the budget stays; 2: always below, the budget grows at the first overflow)
+    traces = [orc.alg1_cache_trace(tokens, b[0], b[1], b[2], [b[3] > 1.0] * len(sides)) for b in budgets]
+    masks = [orc.alg1_allow_mask(tokens, t) for t in traces]
+    st = orc.scale_starts(tokens)
     try:
         split = False
         for s in range(len(sides)):
@@ -84,7 +109,11 @@ def test_density_token_budget_partial_groups():
                 amskv.amskv_append_scale(h, l, s, kd[s], vd[s])
                 segs = amskv.amskv_cache_segments(h, l)
                 split |= len({x[0] for x in segs}) < len(segs)     # one scale present as head and tail
-                _check(h, l, s, tokens, qd[s], k_all, H, 0.3)
+                # what step s attends to: the list iteration s-1 left, then its own scale
+                ids = (traces[l][s - 1][0] if s else []) + list(range(st[s], st[s] + tokens[s]))
+                rows = masks[l][st[s]: st[s] + tokens[s]]
+                assert sorted(np.flatnonzero(rows[0]).tolist()) == sorted(ids)
+                _check(h, l, s, tokens, qd[s], k_all, H, _runs_by_scale(ids, tokens), rows, 0.3)
                 o = torch.empty_like(qd[s])
                 amskv.amskv_attend(h, l, s, qd[s], o)
                 with pytest.raises(amskv.AmskvError) as e:          # the step's trim has run: no longer the step's view

@@ -110,16 +110,59 @@ def test_token_major_matches_oracle_and_head_major(case):
     for (ka, va), (kb, vb) in zip(ex_tm, ex_hm):
         assert np.array_equal(ka, kb) and np.array_equal(va, vb)
     assert sim_tm == sim_hm and dens_tm == dens_hm
-    # and the token-major outputs against the oracle (scale-window cases; the budget mode's oracle leg is
-    # covered on head-major tensors, which the equality above carries over)
+    # and the token-major outputs against the oracle, in both policy modes
+    tokens = [s * s for s in VAR]
+    st = orc.scale_starts(tokens)
+    f64s = lambda xs: [_f64(x) for x in xs]
     if "policies" in case:
-        tokens = [s * s for s in VAR]
         n_layers = len(case["policies"])
-        for l, pol in enumerate(case["policies"]):
-            want = orc.attend_all_steps([_f64(x) for x in q], [_f64(x) for x in k], [_f64(x) for x in v], tokens, pol)
-            for s in range(len(VAR)):
-                err = float(np.abs(_f64(o_tm[s * n_layers + l]) - want[s]).max())
-                assert err <= TOL[dtype], (l, s, err)
+        wants = [orc.attend_all_steps(f64s(q), f64s(k), f64s(v), tokens, pol) for pol in case["policies"]]
+    else:
+        n_layers = len(case["budgets"])
+        cat = lambda xs: np.concatenate(f64s(xs), axis=-2)
+        wants = []
+        for c_min, c_max, c_cds, theta in case["budgets"]:
+            trace = orc.alg1_cache_trace(tokens, c_min, c_max, c_cds, [theta > 1.0] * len(VAR))
+            o = orc.masked_attention(cat(q), cat(k), cat(v), orc.alg1_allow_mask(tokens, trace))
+            wants.append([o[..., st[s]: st[s] + tokens[s], :] for s in range(len(VAR))])
+    for l in range(n_layers):
+        for s in range(len(VAR)):
+            err = float(np.abs(_f64(o_tm[s * n_layers + l]) - wants[l][s]).max())
+            assert err <= TOL[dtype], (l, s, err)
+    # Eq. 3 on token-major tensors against the oracle (layer 0, every step whose neighbour is still cached)
+    if "policies" in case:
+        for s in range(1, len(VAR)):
+            got = sim_tm[s - 1]
+            if got is None:
+                continue
+            wk, wsum = orc.interscale_similarity(_f64(k[s]), _f64(k[s - 1]), (VAR[s],) * 2, (VAR[s - 1],) * 2)
+            wv, _ = orc.interscale_similarity(_f64(v[s]), _f64(v[s - 1]), (VAR[s],) * 2, (VAR[s - 1],) * 2)
+            np.testing.assert_allclose(np.array(got[0]), wk, rtol=0, atol=1e-5)
+            np.testing.assert_allclose(np.array(got[1]), wv, rtol=0, atol=1e-5)
+            np.testing.assert_allclose(np.array(got[2]), wsum, rtol=2e-5, atol=1e-3)
+    # attention density (mass per group of keys) on token-major queries against the oracle, layer 0
+    if dens_tm:
+        k_all = np.concatenate(f64s(k), axis=-2)
+        for got_m, s in zip(dens_tm, (3, len(VAR) - 1)):
+            if "policies" in case:
+                pol = case["policies"][0]
+                pieces = [(st[j], tokens[j]) for j in orc.kept_scales(pol, s)]
+                rows = orc.allow_mask(tokens, pol)[st[s]: st[s] + tokens[s]]
+            else:
+                c_min, c_max, c_cds, theta = case["budgets"][0]
+                trace = orc.alg1_cache_trace(tokens, c_min, c_max, c_cds, [theta > 1.0] * len(VAR))
+                rows = orc.alg1_allow_mask(tokens, trace)[st[s]: st[s] + tokens[s]]
+                ids = np.flatnonzero(rows[0]).tolist()
+                scale_of = orc.scale_of_token(tokens)
+                pieces = []
+                for g in ids:
+                    if pieces and pieces[-1][0] + pieces[-1][1] == g and scale_of[g] == scale_of[pieces[-1][0]]:
+                        pieces[-1][1] += 1
+                    else:
+                        pieces.append([g, 1])
+                pieces = [tuple(x) for x in pieces]
+            _, want_m = orc.attention_density(_f64(q[s]), k_all, rows, pieces)
+            assert np.allclose(np.asarray(got_m)[:, : len(pieces)], want_m, rtol=2e-4, atol=1e-5)
 
 
 def test_io_layout_argument_checks():
