@@ -45,7 +45,8 @@ typedef enum {
   AMSKV_ERR_EVICTED = -3,         /* the call needs a scale that is not resident             */
   AMSKV_ERR_ARENA_TOO_SMALL = -4, /* arena_bytes < amskv_cache_required_bytes                 */
   AMSKV_ERR_HIP = -5,             /* a HIP runtime call failed (launch, copy, sync)          */
-  AMSKV_ERR_NO_DEVICE_MEMORY = -6 /* device work asked of a plan-only cache (arena == NULL)  */
+  AMSKV_ERR_NO_DEVICE_MEMORY = -6,/* device work asked of a plan-only cache (arena == NULL)  */
+  AMSKV_ERR_STATIC_LIMIT = -7     /* batch * heads beyond what the static workspace holds    */
 } amskv_status;
 
 enum { AMSKV_DTYPE_F32 = 0, AMSKV_DTYPE_BF16 = 1 };
@@ -53,6 +54,7 @@ enum { AMSKV_LAYOUT_COMPACT = 0, AMSKV_LAYOUT_PLANNED = 1 };
 enum { AMSKV_MODE_SCALE_WINDOW = 0, AMSKV_MODE_TOKEN_BUDGET = 1 };
 enum { AMSKV_IO_HEAD_MAJOR = 0, AMSKV_IO_TOKEN_MAJOR = 1 };
 enum { AMSKV_MAX_SCALES = 16 };
+enum { AMSKV_STATIC_MAX_UNITS = 16384 }; /* batch * heads limit of amskv_interscale_similarity_enqueue_static */
 
 typedef struct amskv_cache amskv_cache; /* opaque, host memory, owned by the library */
 
@@ -219,6 +221,23 @@ int32_t amskv_interscale_similarity_enqueue(amskv_cache* cache, int32_t layer, i
                                             int32_t want_v, void* stream);
 int32_t amskv_interscale_similarity_collect(amskv_cache* cache, float* cosK_host, float* cosV_host,
                                             float* sums_host, void* stream);
+
+/* For callers that cannot allocate or let the library touch memory it was not handed for this call: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The kernels of
+ * amskv_interscale_similarity_enqueue with their partial sums in a static device array of the library
+ * (2 * AMSKV_STATIC_MAX_UNITS * 4 floats = 512 KB per device, held until the process ends) instead of the
+ * arena's workspace, and the result written to the caller's buffer instead of the arena's per-layer slot:
+ *   sums_out_dev  device, (want_v ? 2 : 1) * heads * 4 floats, 16-byte aligned: for head h the four sums
+ *                 [h*4 + {0,1,2,3}] = sum over (batch, token) of the per-token cosine, sum k.k^, sum |k|^2,
+ *                 sum |k^|^2 of the keys, followed (want_v) by the same block for the values.
+ *                 cosK[h] = sums[h*4] / (batch * T_s).
+ * Calls no allocating routine (the static array's address is looked up once per device, at the first call
+ * on it).  batch * heads > AMSKV_STATIC_MAX_UNITS returns AMSKV_ERR_STATIC_LIMIT.  Nothing in the array has
+ * to start at zero; every call on a device uses the same array, so calls that overlap in time on one device
+ * (different streams, or processes sharing the library image do not count) race and must be ordered by the
+ * caller.  Same residency rules and status codes as amskv_interscale_similarity_enqueue otherwise. */
+int32_t amskv_interscale_similarity_enqueue_static(amskv_cache* cache, int32_t layer, int32_t s, int32_t want_v,
+                                                   float* sums_out_dev, void* stream);
 
 /* Attention density (Section 4.1): of the softmax mass that the queries Q of scale s spread over
  * the keys they attend to, how much lands on each group of keys of layer `layer` -- the groups

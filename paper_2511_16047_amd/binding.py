@@ -21,6 +21,8 @@ AMSKV_ERR_EVICTED = -3
 AMSKV_ERR_ARENA_TOO_SMALL = -4
 AMSKV_ERR_HIP = -5
 AMSKV_ERR_NO_DEVICE_MEMORY = -6
+AMSKV_ERR_STATIC_LIMIT = -7
+AMSKV_STATIC_MAX_UNITS = 16384
 AMSKV_DTYPE_F32, AMSKV_DTYPE_BF16 = 0, 1
 AMSKV_LAYOUT_COMPACT, AMSKV_LAYOUT_PLANNED = 0, 1
 AMSKV_MODE_SCALE_WINDOW, AMSKV_MODE_TOKEN_BUDGET = 0, 1
@@ -35,6 +37,7 @@ EXPORTED = [
     "amskv_cache_reset", "amskv_cache_destroy", "amskv_status_string",
     "amskv_cache_segments", "amskv_cache_budget_tokens", "amskv_cache_settle", "amskv_attention_density",
     "amskv_cache_set_io_layout", "amskv_interscale_similarity_enqueue", "amskv_interscale_similarity_collect",
+    "amskv_interscale_similarity_enqueue_static",
 ]
 
 
@@ -121,6 +124,8 @@ def load_library() -> C.CDLL:
     lib.amskv_interscale_similarity_enqueue.restype = i32
     lib.amskv_interscale_similarity_collect.argtypes = [vp, pf, pf, pf, vp]
     lib.amskv_interscale_similarity_collect.restype = i32
+    lib.amskv_interscale_similarity_enqueue_static.argtypes = [vp, i32, i32, i32, vp, vp]
+    lib.amskv_interscale_similarity_enqueue_static.restype = i32
     _lib = lib
     return lib
 
@@ -231,6 +236,13 @@ def amskv_attention_density(cache, layer, s, Q, heads, stream=None):
 def amskv_interscale_similarity_enqueue(cache, layer, s, want_v=True, stream=None):
     _check(load_library().amskv_interscale_similarity_enqueue(cache, layer, s, int(bool(want_v)), _stream(stream)),
            "amskv_interscale_similarity_enqueue")
+
+
+def amskv_interscale_similarity_enqueue_static(cache, layer, s, want_v, sums_out, stream=None):
+    """sums_out: device tensor or address of (2 if want_v else 1) * heads * 4 floats."""
+    _check(load_library().amskv_interscale_similarity_enqueue_static(cache, layer, s, int(bool(want_v)), _ptr(sums_out),
+                                                                      _stream(stream)),
+           "amskv_interscale_similarity_enqueue_static")
 
 
 def amskv_interscale_similarity_collect(cache, layers, heads, want_v=True, want_sums=True, stream=None):

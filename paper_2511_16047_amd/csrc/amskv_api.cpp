@@ -296,23 +296,26 @@ inline float* similarity_slot(const amskv_cache* c, int layer) {
 // Eq. 3 between scale s (segment cur) and the upsampled scale s-1 (segment prev), both held
 // whole: enqueue the kernels that leave, in the layer's result slot, per head four sums (cosine
 // total, k.k^, |k|^2, |k^|^2) of K at [0 .. 4H) and, when want_v, of V at [4H .. 8H).
+// Where a whole scale sits: in the caller's tensors while it is read in place, else in the layer's regions.
+ScaleRef scale_ref(const amskv_cache* c, const LayerState& L, const Segment& g, bool want_v) {
+  ScaleRef r;
+  if (g.off < 0 || g.pending) {
+    r.k = g.ext_k;
+    r.v = want_v ? g.ext_v : nullptr;
+    r.map = caller_map(c, g.len, c->kv_tok);
+    r.off_tokens = 0;
+  } else {
+    r.k = c->arena + L.k_off;
+    r.v = want_v ? c->arena + L.v_off : nullptr;
+    r.map = arena_map(c, L);
+    r.off_tokens = g.off;
+  }
+  return r;
+}
+
 int similarity_launch(amskv_cache* c, LayerState& L, int layer, const Segment& cur, const Segment& prev, int s,
                       bool want_v, hipStream_t st) {
-  auto ref = [&](const Segment& g) {
-    ScaleRef r;
-    if (g.off < 0 || g.pending) {
-      r.k = g.ext_k;
-      r.v = want_v ? g.ext_v : nullptr;
-      r.map = caller_map(c, g.len, c->kv_tok);
-      r.off_tokens = 0;
-    } else {
-      r.k = c->arena + L.k_off;
-      r.v = want_v ? c->arena + L.v_off : nullptr;
-      r.map = arena_map(c, L);
-      r.off_tokens = g.off;
-    }
-    return r;
-  };
+  auto ref = [&](const Segment& g) { return scale_ref(c, L, g, want_v); };
   hipError_t e = amskv::launch_similarity(ref(cur), ref(prev), c->batch, c->heads, c->head_dim, c->dtype,
                                           c->side_h[s], c->side_w[s], c->side_h[s - 1], c->side_w[s - 1],
                                           (float*)(c->arena + c->ws_off), similarity_slot(c, layer), st);
@@ -505,6 +508,7 @@ const char* amskv_status_string(int32_t st) {
     case AMSKV_ERR_ARENA_TOO_SMALL: return "arena too small";
     case AMSKV_ERR_HIP: return "HIP runtime error";
     case AMSKV_ERR_NO_DEVICE_MEMORY: return "plan-only cache has no device memory";
+    case AMSKV_ERR_STATIC_LIMIT: return "batch * heads exceeds AMSKV_STATIC_MAX_UNITS, the size of the static workspace";
     default: return "unknown status";
   }
 }
@@ -757,6 +761,20 @@ int32_t amskv_interscale_similarity_enqueue(amskv_cache* c, int32_t layer, int32
   int rc = similarity_operands(c, layer, s, &cur, &prev);
   if (rc) return rc;
   return similarity_launch(c, c->layer[layer], layer, *cur, *prev, s, want_v != 0, (hipStream_t)stream);
+}
+
+int32_t amskv_interscale_similarity_enqueue_static(amskv_cache* c, int32_t layer, int32_t s, int32_t want_v,
+                                                   float* sums_out_dev, void* stream) {
+  if (!sums_out_dev || misaligned(sums_out_dev)) return AMSKV_ERR_INVALID_ARG;
+  const Segment *cur, *prev;
+  int rc = similarity_operands(c, layer, s, &cur, &prev);
+  if (rc) return rc;
+  if ((int64_t)c->batch * c->heads > AMSKV_STATIC_MAX_UNITS) return AMSKV_ERR_STATIC_LIMIT;
+  const LayerState& L = c->layer[layer];
+  hipError_t e = amskv::launch_similarity_static(scale_ref(c, L, *cur, want_v != 0), scale_ref(c, L, *prev, want_v != 0),
+                                                 c->batch, c->heads, c->head_dim, c->dtype, c->side_h[s], c->side_w[s],
+                                                 c->side_h[s - 1], c->side_w[s - 1], sums_out_dev, (hipStream_t)stream);
+  return e == hipSuccess ? AMSKV_OK : AMSKV_ERR_HIP;
 }
 
 int32_t amskv_interscale_similarity_collect(amskv_cache* c, float* cosK_host, float* cosV_host, float* sums_host,

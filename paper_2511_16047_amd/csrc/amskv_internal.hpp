@@ -112,6 +112,12 @@ hipError_t launch_similarity(const ScaleRef& cur, const ScaleRef& prev, int batc
                              int head_dim, int dtype, int h_cur, int w_cur, int h_prev, int w_prev,
                              float* partial_ws, float* out_dev, hipStream_t st);
 
+// the same with the partial sums in the library's static device array instead of partial_ws; batch * heads
+// must not exceed AMSKV_STATIC_MAX_UNITS.  Calls no allocating routine.
+hipError_t launch_similarity_static(const ScaleRef& cur, const ScaleRef& prev, int batch, int heads,
+                                    int head_dim, int dtype, int h_cur, int w_cur, int h_prev, int w_prev,
+                                    float* out_dev, hipStream_t st);
+
 // attention density: pieces = one table entry per group of keys (nothing merged); partial_ws holds
 // batch*heads*ceil(t_q/32)*AMSKV_MAX_SCALES floats, out_dev heads*AMSKV_MAX_SCALES floats; bf16 only
 hipError_t launch_density(const void* q, const void* kc, int batch, int heads, int t_q, int head_dim,

@@ -9,6 +9,8 @@ namespace amskv {
 namespace {
 
 constexpr int kThreads = 256;
+constexpr int kStaticMaxUnits = AMSKV_STATIC_MAX_UNITS;
+constexpr int kMaxDevices = 64;
 
 template <bool BF16>
 struct Chunk;  // one 16-byte piece of a token row, widened to fp32
@@ -140,7 +142,42 @@ __global__ __launch_bounds__(64) void similarity_total_kernel(const float* __res
     *reinterpret_cast<float4*>(totals + ((long long)tn * heads + h) * 4) = make_float4(acc[0], acc[1], acc[2], acc[3]);
 }
 
+// Partial-sum workspace of the entry point that allocates nothing: per (tensor, b, h) four floats, for up to
+// kStaticMaxUnits = batch * heads units and both tensors (512 KB).  Every device the library runs on holds its
+// own copy for the life of the process.
+__device__ __align__(256) float scratch[2 * kStaticMaxUnits * 4];
+
+// Device address of `scratch` on the current device, looked up once per device (the array's name is only a
+// host-side handle).
+hipError_t scratch_address(float** out) {
+  static float* address[kMaxDevices];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  float* p = __atomic_load_n(&address[dev], __ATOMIC_ACQUIRE);
+  if (!p) {
+    e = hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    __atomic_store_n(&address[dev], p, __ATOMIC_RELEASE);  // every caller looks up the same value
+  }
+  *out = p;
+  return hipSuccess;
+}
+
 }  // namespace
+
+hipError_t launch_similarity_static(const ScaleRef& cur, const ScaleRef& prev, int batch, int heads, int head_dim,
+                                    int dtype, int h_cur, int w_cur, int h_prev, int w_prev, float* out_dev,
+                                    hipStream_t st) {
+  if ((long long)batch * heads > kStaticMaxUnits) return hipErrorInvalidValue;  // the caller checks first
+  float* ws = nullptr;
+  hipError_t e = scratch_address(&ws);
+  if (e != hipSuccess) return e;
+  // every partial sum the totals kernel reads is written by the partial kernel of the same call: nothing to clear
+  return launch_similarity(cur, prev, batch, heads, head_dim, dtype, h_cur, w_cur, h_prev, w_prev, ws, out_dev, st);
+}
 
 hipError_t launch_similarity(const ScaleRef& cur, const ScaleRef& prev, int batch, int heads, int head_dim,
                              int dtype, int h_cur, int w_cur, int h_prev, int w_prev, float* partial_ws,
