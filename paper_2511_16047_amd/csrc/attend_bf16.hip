@@ -38,8 +38,6 @@
 // tail of the virtual concatenation and its rows are fetched from the caller's K/V instead.
 // The ring holds tile t-1 (its last block's V is still being multiplied), t (in use) and the tiles in
 // flight: t+1 and t+2 at head dim 64, t+1 alone at head dim 128 (see kAhead).
-#include <cstdlib>
-
 #include "amskv_internal.hpp"
 
 namespace amskv {
@@ -647,13 +645,8 @@ hipError_t launch(const void* q, void* o, void* kc, void* vc, int bh, int t_q, i
 hipError_t launch_attend_bf16(const void* q, void* o, void* kc, void* vc, int bh, int t_q,
                               int head_dim, int64_t cap_tokens, const SegTable& seg, const ExtKV& ext, const CallerIo& io,
                               float softmax_scale, hipStream_t st) {
-#if defined(AMSKV_TUNE_ENV)
-  static const int small_tq = getenv("AMSKV_SMALL_TQ") ? atoi(getenv("AMSKV_SMALL_TQ")) : kSmallTq;
-#else
-  constexpr int small_tq = kSmallTq;
-#endif
   // coarse scales: latency-bound, one independent wave per 32 query rows
-  if (t_q <= small_tq) return launch_attend_bf16_small(q, o, kc, vc, bh, t_q, head_dim, cap_tokens, seg, ext, io, softmax_scale, st);
+  if (t_q <= kSmallTq) return launch_attend_bf16_small(q, o, kc, vc, bh, t_q, head_dim, cap_tokens, seg, ext, io, softmax_scale, st);
   const float c = softmax_scale * 1.4426950408889634f;
   const bool wide = t_q > 128;  // 256 query rows per workgroup keeps K/V single-pass up to T_q = 256
   if (head_dim == 64)
