@@ -80,11 +80,14 @@ typedef struct {
 } amskv_layer_policy;
 
 /* Per-layer budgets in tokens for AMSKV_MODE_TOKEN_BUDGET: Algorithm 1 and Algorithm 2 taken
- * literally (Section 4.3).  The layer starts with the budget c_min; the first time the cache
- * would exceed it, the layer is tested for being cache-demanding (Eq. 3 score below theta) and,
- * if so, the budget becomes c_max for good.  A scale larger than c_max, or larger than the
- * budget in force, is never cached.  Otherwise the cache keeps its first c_cds tokens and the
- * most recent (budget - c_cds) tokens, so a scale may stay in part.
+ * literally (Section 4.3).  The layer starts with the budget c_min.  At every iteration of
+ * Algorithm 1 at which the cached tokens plus the new scale exceed the budget while the budget
+ * still is c_min, the layer is tested for being cache-demanding (Eq. 3 score below theta); the
+ * first time the test holds the budget becomes c_max for good, and a layer whose test keeps
+ * failing is tested again at each later overflowing step (three times on a ten-scale schedule
+ * with c_min below the sixth scale's running total).  A scale larger than c_max, or larger than
+ * the budget in force, is never cached.  Otherwise the cache keeps its first c_cds tokens and
+ * the most recent (budget - c_cds) tokens, so a scale may stay in part.
  * The score compared with theta is the mean over heads of the mean per-token cosine between
  * the keys of the new scale and the bilinearly upsampled keys of the scale before it (the
  * cosine form of Eq. 3 that amskv_interscale_similarity returns as cosK).  It can be computed
@@ -133,12 +136,25 @@ typedef struct {
  * back to back from offset 0 of the layer's regions (layout must be AMSKV_LAYOUT_COMPACT,
  * borrow_unretained and fuse_append must be 0; the capacity of a layer is c_max tokens).
  * Step s runs in this order: amskv_append_scale(s) only records K_dev/V_dev; amskv_attend(s)
- * attends to the cache as the previous step left it plus scale s read in place, and then, in
- * stream order behind the attention kernel, performs Algorithm 1's iteration for scale s
- * (budget test, skip, Algorithm 2's trim, copy of what stays of scale s).  If amskv_attend(s)
- * is not called, the next amskv_append_scale or amskv_cache_settle on the layer performs that
- * iteration.  K_dev/V_dev of scale s must stay valid and unchanged until that work has run.
- * The one iteration per layer that evaluates Eq. 3 waits for the stream. */
+ * attends to the cache as the previous step left it plus scale s read in place.  Algorithm 1's
+ * iteration for scale s (budget test, skip, Algorithm 2's trim, copy of what stays of scale s)
+ * comes after that attention.  When the scale fits the budget untrimmed, the attention launch
+ * itself writes it behind the cached tokens and the iteration is complete when amskv_attend
+ * returns.  Otherwise amskv_attend leaves the iteration to the next call that reads or changes
+ * the layer's state -- amskv_append_scale, amskv_cache_settle, any query, export -- which
+ * enqueues its device work on the stream amskv_attend was given; amskv_cache_reset drops an
+ * iteration nobody asked for (after the last step of an image its result is never read).
+ * If amskv_attend(s) is not called at all, the next amskv_append_scale or amskv_cache_settle
+ * performs the iteration.
+ * An iteration that needs the Eq. 3 score does not make amskv_attend wait: the call enqueues the
+ * similarity kernels, a transfer of their sums into pinned host memory (allocated by
+ * amskv_cache_create) and an event, and returns.  The call that later performs the iteration
+ * waits for that event alone, not for the stream; Algorithm 1 needs the decision only before the
+ * next scale is appended, and by then the device has long passed the test when other layers'
+ * steps were enqueued in between.
+ * K_dev/V_dev of scale s must stay valid and unchanged until the iteration has run: until the
+ * work enqueued by the next amskv_append_scale / amskv_cache_settle / query on the layer has
+ * finished, or until amskv_cache_reset. */
 
 /* Bytes the arena must have for this configuration: for every layer the K and V regions
  * sized for the largest kept set the policy ever reaches (Section 4.3: capacity is fixed

@@ -46,6 +46,12 @@ struct LayerState {
   amskv_layer_budget bud = {0, 0, 0, 0.f};
   int32_t c_bgt = 0;
   bool roll_pending = false;
+  // amskv_attend leaves the iteration to the next call that needs the layer's state (`deferred`); if the
+  // iteration needs the Eq. 3 score, the test has been enqueued and its sums are on their way to the host
+  bool deferred = false;
+  bool test_pending = false;
+  hipEvent_t test_done = nullptr;
+  hipStream_t test_stream = nullptr;
 };
 
 }  // namespace
@@ -61,6 +67,7 @@ struct amskv_cache {
   uint64_t dens_off = 0;  // attention-density workspace
   int32_t io_layout = AMSKV_IO_HEAD_MAJOR;
   int64_t q_tok = 0, kv_tok = 0, o_tok = 0;  // token strides in elements (token-major tensors only)
+  float* theta_host = nullptr;  // token-budget mode: pinned, [layers][heads * 4], the sums of each layer's Eq. 3 test
   std::vector<LayerState> layer;
 };
 
@@ -340,11 +347,14 @@ int similarity_sums(amskv_cache* c, LayerState& L, int layer, const Segment& cur
 }
 
 // Algorithm 1's test for a cache-demanding layer: Eq. 3 (cosine form, mean over heads) of the
-// newest scale against the scale before it, compared with theta.
-int below_theta(amskv_cache* c, LayerState& L, const Segment& cur, hipStream_t st, bool* below) {
-  *below = false;
+// newest scale against the scale before it, compared with theta.  Either the outcome is known
+// without device work (kTestFails, kTestHolds), or the kernels, the transfer of their sums into
+// the layer's pinned slot and an event behind them are enqueued (kTestEnqueued).
+enum { kTestFails = 0, kTestHolds = 1, kTestEnqueued = 2 };
+int start_theta_test(amskv_cache* c, LayerState& L, const Segment& cur, hipStream_t st, int* state) {
+  *state = kTestFails;
   if (L.bud.theta > 1.f) {
-    *below = true;
+    *state = kTestHolds;
     return AMSKV_OK;
   }
   if (L.bud.theta < -1.f || cur.scale < 1) return AMSKV_OK;
@@ -352,12 +362,28 @@ int below_theta(amskv_cache* c, LayerState& L, const Segment& cur, hipStream_t s
   for (const Segment& g : L.segs)
     if (&g != &L.segs.back() && whole_scale(c, g, cur.scale - 1)) prev = &g;
   if (!prev) return AMSKV_OK;  // the earlier scale is not cached whole: no score, no expansion
-  if (!c->arena || !cur.ext_k) return AMSKV_ERR_NO_DEVICE_MEMORY;
-  std::vector<float> host;
-  int rc = similarity_sums(c, L, (int)(&L - c->layer.data()), cur, *prev, cur.scale, false, &host, st);
+  if (!c->arena || !cur.ext_k || !c->theta_host || !L.test_done) return AMSKV_ERR_NO_DEVICE_MEMORY;
+  const int layer = (int)(&L - c->layer.data());
+  int rc = similarity_launch(c, L, layer, cur, *prev, cur.scale, false, st);
   if (rc) return rc;
+  const size_t n = (size_t)c->heads * 4;
+  if (hipMemcpyAsync(c->theta_host + layer * n, similarity_slot(c, layer), n * sizeof(float), hipMemcpyDeviceToHost,
+                     st) != hipSuccess)
+    return AMSKV_ERR_HIP;
+  if (hipEventRecord(L.test_done, st) != hipSuccess) return AMSKV_ERR_HIP;
+  L.test_stream = st;
+  *state = kTestEnqueued;
+  return AMSKV_OK;
+}
+
+// Waits for the enqueued test of the layer (only for it, not for the stream) and compares.
+int read_theta_test(amskv_cache* c, LayerState& L, bool* below) {
+  if (hipEventSynchronize(L.test_done) != hipSuccess) return AMSKV_ERR_HIP;
+  const int layer = (int)(&L - c->layer.data());
+  const float* host = c->theta_host + (size_t)layer * c->heads * 4;
+  const int32_t s = L.segs.back().scale;
   double mean = 0.0;
-  const double n_tok = (double)c->batch * c->tokens[cur.scale];
+  const double n_tok = (double)c->batch * c->tokens[s];
   for (int h = 0; h < c->heads; ++h) mean += (double)(float)(host[h * 4] / n_tok);
   mean /= c->heads;
   *below = mean < (double)L.bud.theta;
@@ -366,13 +392,16 @@ int below_theta(amskv_cache* c, LayerState& L, const Segment& cur, hipStream_t s
 
 // Token-budget mode: Algorithm 1's iteration for the newest scale, which until now has been read
 // in place as the last segment.  Decides whether the scale is cached at all, expands the budget
-// once if the layer tests as cache-demanding, and applies Algorithm 2 to the token list
-// (cached tokens followed by the new scale): the first c_cds tokens and the last
-// (budget - c_cds) tokens stay.  Survivors slide toward offset 0; what stays of the new scale
-// is copied behind them.
+// if the layer tests as cache-demanding (the test is made at every iteration that overflows the
+// budget while it still is c_min), and applies Algorithm 2 to the token list (cached tokens
+// followed by the new scale): the first c_cds tokens and the last (budget - c_cds) tokens stay.
+// Survivors slide toward offset 0 and what stays of the new scale is copied behind them, in one launch.
 // appended_at >= 0: the attention kernel of this step has already written the whole scale into the cache at that
 // token offset (possible whenever the scale fits the budget without trimming), so nothing is left to copy.
-int roll_budget(amskv_cache* c, LayerState& L, hipStream_t st, int32_t appended_at = -1) {
+// may_defer (amskv_attend): leave the iteration to the next call on the layer; if it needs the Eq. 3 score from
+// the device, enqueue the test now, so that the later call finds the result waiting.  An iteration that is never
+// asked for (a reset comes first, as after the last step of an image) costs no device work.
+int roll_budget(amskv_cache* c, LayerState& L, hipStream_t st, int32_t appended_at = -1, bool may_defer = false) {
   if (!L.roll_pending) return AMSKV_OK;
   const Segment cur = L.segs.back();
   const int32_t t_new = cur.len;
@@ -380,12 +409,38 @@ int roll_budget(amskv_cache* c, LayerState& L, hipStream_t st, int32_t appended_
   for (size_t i = 0; i + 1 < L.segs.size(); ++i) n_old += L.segs[i].len;
   int32_t bgt = L.c_bgt;
   bool cache_it = t_new <= L.bud.c_max;
-  if (cache_it && n_old + t_new > bgt) {
-    if (bgt == L.bud.c_min && L.bud.c_max > L.bud.c_min) {
-      bool below = false;
-      int rc = below_theta(c, L, cur, st, &below);
+  const bool overflow = cache_it && n_old + t_new > bgt;
+  const bool wants_test = overflow && bgt == L.bud.c_min && L.bud.c_max > L.bud.c_min;
+  if (L.deferred) {
+    // the part amskv_attend left: same state as then; what is enqueued goes behind that step's own work
+    st = L.test_stream;
+    L.deferred = false;
+  } else if (may_defer && appended_at < 0) {
+    if (wants_test) {
+      int state = kTestFails;
+      int rc = start_theta_test(c, L, cur, st, &state);
       if (rc) return rc;
-      if (below) bgt = L.bud.c_max;
+      L.test_pending = state == kTestEnqueued;
+    }
+    L.deferred = true;
+    L.test_stream = st;
+    return AMSKV_OK;
+  }
+  if (overflow) {
+    if (wants_test) {
+      int state = kTestFails;
+      if (!L.test_pending) {
+        int rc = start_theta_test(c, L, cur, st, &state);
+        if (rc) return rc;
+      }
+      if (L.test_pending || state == kTestEnqueued) {
+        bool below = false;
+        int rc = read_theta_test(c, L, &below);
+        if (rc) return rc;
+        L.test_pending = false;
+        state = below ? kTestHolds : kTestFails;
+      }
+      if (state == kTestHolds) bgt = L.bud.c_max;
     }
     if (t_new > bgt) cache_it = false;
   }
@@ -451,29 +506,35 @@ int roll_budget(amskv_cache* c, LayerState& L, hipStream_t st, int32_t appended_
   const bool copied_already = appended_at >= 0 && mv.n == 0 && copies.size() == 1 && copies[0].src_first == 0 &&
                               copies[0].len == t_new && copies[0].dst == appended_at;
   if (appended_at >= 0 && !copied_already) return AMSKV_ERR_INVALID_ARG;  // cannot happen: the caller used the same rule
-  if (c->arena && cur.ext_k && !copied_already) {
+  if (c->arena && cur.ext_k && !copied_already && (mv.n > 0 || !copies.empty())) {
     const int bh = c->batch * c->heads;
     const int row_bytes = c->head_dim * c->elem_bytes;
-    char* kc = c->arena + L.k_off;
-    char* vc = c->arena + L.v_off;
-    if (mv.n > 0) {
-      hipError_t e = amskv::launch_append(kc, vc, nullptr, nullptr, bh, row_bytes, L.cap, mv, 0, 0, 0, RowMap{0, 0, 0},
-                                          c->heads, st);
-      if (e != hipSuccess) return AMSKV_ERR_HIP;
+    amskv::NewRanges nr;
+    std::memset(&nr, 0, sizeof(nr));
+    for (const CopyRange& r : copies) {  // at most the head and the tail of the new scale
+      nr.src_first[nr.n] = r.src_first;
+      nr.len[nr.n] = r.len;
+      nr.dst[nr.n] = r.dst;
+      ++nr.n;
     }
-    MoveList none;
-    std::memset(&none, 0, sizeof(none));
-    for (const CopyRange& r : copies) {
-      hipError_t e = amskv::launch_append(kc, vc, cur.ext_k, cur.ext_v, bh, row_bytes, L.cap, none, r.len, r.dst,
-                                          r.src_first, caller_map(c, t_new, c->kv_tok), c->heads, st);
-      if (e != hipSuccess) return AMSKV_ERR_HIP;
-    }
+    hipError_t e = amskv::launch_roll(c->arena + L.k_off, c->arena + L.v_off, cur.ext_k, cur.ext_v, bh, row_bytes, L.cap,
+                                      mv, nr, caller_map(c, t_new, c->kv_tok), c->heads, st);
+    if (e != hipSuccess) return AMSKV_ERR_HIP;
   }
   L.segs.swap(next);
   L.last_evicted.swap(evicted);
   L.c_bgt = bgt;
   L.roll_pending = false;
   return AMSKV_OK;
+}
+
+// An iteration of Algorithm 1 whose Eq. 3 test is still on its way is finished before anything reads or changes
+// the layer's state (the cache object is never const where it was created; the queries only promise not to
+// change what they report).
+int finish_iteration(const amskv_cache* cc, int32_t layer) {
+  amskv_cache* c = const_cast<amskv_cache*>(cc);
+  LayerState& L = c->layer[layer];
+  return L.deferred ? roll_budget(c, L, L.test_stream) : AMSKV_OK;
 }
 
 // fuse_append: a scale whose attend never came still lives only in the caller's buffers; copy it
@@ -576,6 +637,16 @@ int32_t amskv_cache_create(int32_t layers, int32_t heads, int32_t head_dim,
     L.v_off = pl.v_off[l];
     for (int i = 0; i < AMSKV_MAX_SCALES; ++i) L.planned_off[i] = pl.slot[l][i];
   }
+  if (c->mode == AMSKV_MODE_TOKEN_BUDGET && c->arena) {
+    // where the Eq. 3 sums of each layer's test arrive, and the event that says they have
+    bool ok = hipHostMalloc((void**)&c->theta_host, (size_t)layers * heads * 4 * sizeof(float), hipHostMallocDefault) == hipSuccess;
+    for (int l = 0; ok && l < layers; ++l)
+      ok = hipEventCreateWithFlags(&c->layer[l].test_done, hipEventDisableTiming) == hipSuccess;
+    if (!ok) {
+      amskv_cache_destroy(c);
+      return AMSKV_ERR_HIP;
+    }
+  }
   *out = c;
   return AMSKV_OK;
 }
@@ -672,6 +743,7 @@ int32_t amskv_attend(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev
                      void* stream) {
   if (bad_layer(c, layer) || s < 0 || s >= c->n_scales || !Q_dev || !O_dev || misaligned(Q_dev) || misaligned(O_dev))
     return AMSKV_ERR_INVALID_ARG;
+  if (int rc = finish_iteration(c, layer)) return rc;
   LayerState& L = c->layer[layer];
   if (s != L.last_scale) return AMSKV_ERR_ORDER;
   // token-budget mode: once the scale's iteration of Algorithm 1 has run it is no longer whole
@@ -708,13 +780,15 @@ int32_t amskv_attend(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev
     newest.pending = false;
     newest.ext_k = newest.ext_v = nullptr;
   }
-  if (c->mode == AMSKV_MODE_TOKEN_BUDGET) return roll_budget(c, L, (hipStream_t)stream, appended_at);
+  // what is left of the iteration (anything, unless this launch wrote the whole scale to its place) waits for the next call on the layer
+  if (c->mode == AMSKV_MODE_TOKEN_BUDGET) return roll_budget(c, L, (hipStream_t)stream, appended_at, true);
   return AMSKV_OK;
 }
 
 // Checks shared by the two ways of asking for Eq. 3; on success cur/prev point at the two whole scales.
 static int similarity_operands(amskv_cache* c, int32_t layer, int32_t s, const Segment** cur, const Segment** prev) {
   if (bad_layer(c, layer) || s < 1 || s >= c->n_scales) return AMSKV_ERR_INVALID_ARG;
+  if (int rc = finish_iteration(c, layer)) return rc;
   LayerState& L = c->layer[layer];
   if (s > L.last_scale) return AMSKV_ERR_ORDER;
   *cur = *prev = nullptr;
@@ -811,6 +885,7 @@ int32_t amskv_attention_density(amskv_cache* c, int32_t layer, int32_t s, const 
   if (bad_layer(c, layer) || s < 0 || s >= c->n_scales || !Q_dev || misaligned(Q_dev) || (!density_host && !mass_host))
     return AMSKV_ERR_INVALID_ARG;
   if (c->dtype != AMSKV_DTYPE_BF16) return AMSKV_ERR_INVALID_ARG;
+  if (int rc = finish_iteration(c, layer)) return rc;
   LayerState& L = c->layer[layer];
   if (s != L.last_scale) return AMSKV_ERR_ORDER;
   if (c->mode == AMSKV_MODE_TOKEN_BUDGET && !L.roll_pending) return AMSKV_ERR_ORDER;
@@ -847,6 +922,7 @@ int32_t amskv_attention_density(amskv_cache* c, int32_t layer, int32_t s, const 
 int32_t amskv_cache_layout(const amskv_cache* c, int32_t layer, int32_t* n_seg, int32_t* scale_id,
                            int64_t* tok_offset, int32_t* tok_len) {
   if (bad_layer(c, layer) || !n_seg) return AMSKV_ERR_INVALID_ARG;
+  if (int rc = finish_iteration(c, layer)) return rc;
   const LayerState& L = c->layer[layer];
   *n_seg = (int32_t)L.segs.size();
   for (size_t i = 0; i < L.segs.size(); ++i) {
@@ -860,6 +936,7 @@ int32_t amskv_cache_layout(const amskv_cache* c, int32_t layer, int32_t* n_seg, 
 int32_t amskv_cache_segments(const amskv_cache* c, int32_t layer, int32_t* n_seg, int32_t* scale_id,
                              int32_t* first_token, int64_t* tok_offset, int32_t* tok_len) {
   if (bad_layer(c, layer) || !n_seg) return AMSKV_ERR_INVALID_ARG;
+  if (int rc = finish_iteration(c, layer)) return rc;
   const LayerState& L = c->layer[layer];
   *n_seg = (int32_t)L.segs.size();
   for (size_t i = 0; i < L.segs.size(); ++i) {
@@ -873,6 +950,7 @@ int32_t amskv_cache_segments(const amskv_cache* c, int32_t layer, int32_t* n_seg
 
 int64_t amskv_cache_budget_tokens(const amskv_cache* c, int32_t layer) {
   if (bad_layer(c, layer)) return AMSKV_ERR_INVALID_ARG;
+  if (int rc = finish_iteration(c, layer)) return rc;
   const LayerState& L = c->layer[layer];
   return c->mode == AMSKV_MODE_TOKEN_BUDGET ? (int64_t)L.c_bgt : L.cap;
 }
@@ -887,6 +965,7 @@ int32_t amskv_cache_settle(amskv_cache* c, int32_t layer, void* stream) {
 int32_t amskv_cache_last_evicted(const amskv_cache* c, int32_t layer, int32_t* n_evicted,
                                  int32_t* scale_id) {
   if (bad_layer(c, layer) || !n_evicted) return AMSKV_ERR_INVALID_ARG;
+  if (int rc = finish_iteration(c, layer)) return rc;
   const LayerState& L = c->layer[layer];
   *n_evicted = (int32_t)L.last_evicted.size();
   if (scale_id)
@@ -896,6 +975,7 @@ int32_t amskv_cache_last_evicted(const amskv_cache* c, int32_t layer, int32_t* n
 
 int64_t amskv_cache_bytes_held(const amskv_cache* c, int32_t layer, int32_t include_current) {
   if (bad_layer(c, layer)) return AMSKV_ERR_INVALID_ARG;
+  if (int rc = finish_iteration(c, layer)) return rc;
   const LayerState& L = c->layer[layer];
   int64_t tok = 0;
   for (const Segment& g : L.segs)
@@ -912,6 +992,7 @@ int32_t amskv_cache_export(const amskv_cache* c, int32_t layer, void* K_out_dev,
                            void* stream) {
   if (bad_layer(c, layer) || (!K_out_dev && !V_out_dev)) return AMSKV_ERR_INVALID_ARG;
   if (!c->arena) return AMSKV_ERR_NO_DEVICE_MEMORY;
+  if (int rc = finish_iteration(c, layer)) return rc;
   const LayerState& L = c->layer[layer];
   if (L.segs.empty()) return AMSKV_OK;
   ExtKV ext;
@@ -950,11 +1031,21 @@ int32_t amskv_cache_reset(amskv_cache* c) {
     L.last_scale = -1;
     L.c_bgt = L.bud.c_min;
     L.roll_pending = false;
+    L.deferred = L.test_pending = false;  // an enqueued test still runs; its result is not read
     L.sim_scale = -1;
   }
   return AMSKV_OK;
 }
 
-void amskv_cache_destroy(amskv_cache* c) { delete c; }
+void amskv_cache_destroy(amskv_cache* c) {
+  if (!c) return;
+  for (LayerState& L : c->layer)
+    if (L.test_done) {
+      (void)hipEventSynchronize(L.test_done);  // a transfer into theta_host may still be in flight
+      (void)hipEventDestroy(L.test_done);
+    }
+  if (c->theta_host) (void)hipHostFree(c->theta_host);
+  delete c;
+}
 
 }  // extern "C"

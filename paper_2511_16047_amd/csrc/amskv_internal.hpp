@@ -57,6 +57,15 @@ struct MoveList {
   int32_t len[AMSKV_MAX_SCALES];
 };
 
+// Token ranges of the newest scale that Algorithm 2's trim keeps (its head while the cache is still
+// shorter than the condensed part, and its tail): tokens [src_first, src_first + len) go to offset dst.
+struct NewRanges {
+  int32_t n;
+  int32_t src_first[2];
+  int32_t dst[2];
+  int32_t len[2];
+};
+
 #if defined(__HIPCC__)
 // Byte offset of row 0 of unit bh = b*heads + h inside a caller tensor.
 __device__ __forceinline__ long long unit_offset(const RowMap& m, long long bh, int heads) {
@@ -95,6 +104,11 @@ hipError_t launch_attend_f32(const void* q, void* o, void* kc, void* vc, int bh,
 hipError_t launch_append(void* kc, void* vc, const void* k_new, const void* v_new, int bh,
                          int row_bytes, int64_t cap_tokens, const MoveList& mv, int t_new,
                          int dst_new, int src_first, const RowMap& src_map, int heads, hipStream_t st);
+// One iteration of Algorithm 1 at token granularity in one launch: the surviving ranges slide down (mv), then
+// the kept ranges of the new scale (rows located by src_map) are copied behind them
+hipError_t launch_roll(void* kc, void* vc, const void* k_new, const void* v_new, int bh, int row_bytes,
+                       int64_t cap_tokens, const MoveList& mv, const NewRanges& nr, const RowMap& src_map, int heads,
+                       hipStream_t st);
 // k_out/v_out are head-major [BH][T_kept][row]; ext_map locates the rows of a borrowed scale
 hipError_t launch_export(const void* kc, const void* vc, void* k_out, void* v_out, int bh,
                          int row_bytes, int64_t cap_tokens, const SegTable& seg, const ExtKV& ext,

@@ -60,6 +60,67 @@ __global__ __launch_bounds__(kThreads) void compact_kernel(char* __restrict__ kc
   }
 }
 
+// Token-granular iteration of Algorithm 1 in one launch: the moves of compact_kernel, then -- the workgroup owns the
+// row, and behind the last pass's barrier every moved chunk has been read -- the kept ranges of the new scale
+// are copied from the caller's tensor to their place behind the survivors (which may overlap where a survivor
+// used to be).
+__global__ __launch_bounds__(kThreads) void roll_kernel(char* __restrict__ kc, char* __restrict__ vc,
+                                                        const char* __restrict__ k_new, const char* __restrict__ v_new,
+                                                        int row_bytes, long long cap_tokens, MoveList mv, NewRanges nr,
+                                                        RowMap src_map, int heads) {
+  const int tid = threadIdx.x;
+  const long long bh = blockIdx.x;
+  char* base = (blockIdx.y ? vc : kc) + bh * cap_tokens * row_bytes;
+  const int cpr = row_bytes >> 4;
+
+  int total = 0;
+  for (int i = 0; i < mv.n; ++i) total += mv.len[i] * cpr;
+  for (int c0 = 0; c0 < total; c0 += kThreads * kUnroll) {
+    uint4 buf[kUnroll];
+    long long dst_byte[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int c = c0 + u * kThreads + tid;
+      dst_byte[u] = -1;
+      if (c < total) {
+        int rem = c, src_tok = 0, dst_tok = 0;
+        for (int i = 0; i < mv.n; ++i) {
+          const int n = mv.len[i] * cpr;
+          if (rem < n) {
+            src_tok = mv.src[i];
+            dst_tok = mv.dst[i];
+            break;
+          }
+          rem -= n;
+        }
+        const long long so = (long long)src_tok * row_bytes + ((long long)rem << 4);
+        dst_byte[u] = (long long)dst_tok * row_bytes + ((long long)rem << 4);
+        buf[u] = *reinterpret_cast<const uint4*>(base + so);
+      }
+    }
+    wait_all_vector_loads();
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u)
+      if (dst_byte[u] >= 0) *reinterpret_cast<uint4*>(base + dst_byte[u]) = buf[u];
+  }
+  if (total > 0) __syncthreads();  // the copies below may overwrite sources of the last pass
+
+  const char* src = (blockIdx.y ? v_new : k_new) + unit_offset(src_map, bh, heads);
+#pragma unroll
+  for (int r = 0; r < 2; ++r) {
+    const int n = r < nr.n ? nr.len[r] * cpr : 0;
+    const char* from = src + (long long)nr.src_first[r] * src_map.tok;
+    char* to = base + (long long)nr.dst[r] * row_bytes;
+#pragma unroll 4
+    for (int c = tid; c < n; c += kThreads) {
+      const int tok = c / cpr;
+      *reinterpret_cast<uint4*>(to + ((long long)c << 4)) =
+          *reinterpret_cast<const uint4*>(from + (long long)tok * src_map.tok + ((c - tok * cpr) << 4));
+    }
+  }
+}
+
 // Append: copy t_new tokens of the new scale K_s, V_s (the caller's tensors, rows located by
 // src_map, starting at token src_first of every (b,h)) into their slot of every (b,h) row of the
 // cache.  Flat over all 16-byte chunks of both tensors, so a one-token scale and a 256-token scale
@@ -138,6 +199,14 @@ hipError_t launch_append(void* kc, void* vc, const void* k_new, const void* v_ne
   hipLaunchKernelGGL(append_kernel, dim3(grid), dim3(kThreads), 0, st, (char*)kc, (char*)vc, (const char*)k_new,
                      (const char*)v_new, row_bytes, (long long)cap_tokens, t_new, dst_new, src_first, src_map, heads,
                      chunks);
+  return hipGetLastError();
+}
+
+hipError_t launch_roll(void* kc, void* vc, const void* k_new, const void* v_new, int bh, int row_bytes,
+                       int64_t cap_tokens, const MoveList& mv, const NewRanges& nr, const RowMap& src_map, int heads,
+                       hipStream_t st) {
+  hipLaunchKernelGGL(roll_kernel, dim3(bh, 2), dim3(kThreads), 0, st, (char*)kc, (char*)vc, (const char*)k_new,
+                     (const char*)v_new, row_bytes, (long long)cap_tokens, mv, nr, src_map, heads);
   return hipGetLastError();
 }
 

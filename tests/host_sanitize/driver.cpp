@@ -20,6 +20,8 @@ hipError_t launch_attend_f32(const void*, void*, void*, void*, int, int, int, in
                              const CallerIo&, float, hipStream_t) { std::abort(); }
 hipError_t launch_append(void*, void*, const void*, const void*, int, int, int64_t, const MoveList&, int, int, int,
                          const RowMap&, int, hipStream_t) { std::abort(); }
+hipError_t launch_roll(void*, void*, const void*, const void*, int, int, int64_t, const MoveList&, const NewRanges&,
+                       const RowMap&, int, hipStream_t) { std::abort(); }
 hipError_t launch_export(const void*, const void*, void*, void*, int, int, int64_t, const SegTable&, const ExtKV&,
                          const RowMap&, int, hipStream_t) { std::abort(); }
 hipError_t launch_similarity(const ScaleRef&, const ScaleRef&, int, int, int, int, int, int, int, int, float*, float*,
@@ -31,6 +33,12 @@ hipError_t launch_density(const void*, const void*, int, int, int, int, int64_t,
 }  // namespace amskv
 extern "C" hipError_t hipMemcpyAsync(void*, const void*, size_t, hipMemcpyKind, hipStream_t) { std::abort(); }
 extern "C" hipError_t hipStreamSynchronize(hipStream_t) { std::abort(); }
+extern "C" hipError_t hipHostMalloc(void**, size_t, unsigned int) { std::abort(); }
+extern "C" hipError_t hipHostFree(void*) { std::abort(); }
+extern "C" hipError_t hipEventCreateWithFlags(hipEvent_t*, unsigned) { std::abort(); }
+extern "C" hipError_t hipEventDestroy(hipEvent_t) { std::abort(); }
+extern "C" hipError_t hipEventRecord(hipEvent_t, hipStream_t) { std::abort(); }
+extern "C" hipError_t hipEventSynchronize(hipEvent_t) { std::abort(); }
 
 static int failures = 0;
 #define CHECK(cond)                                                          \

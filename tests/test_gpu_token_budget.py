@@ -243,3 +243,68 @@ def test_full_batch_sampled_units():
             amskv.amskv_cache_destroy(h)
             del q, k, v, arena
             torch.cuda.empty_cache()
+
+
+def test_iterations_left_to_the_next_call_interleaved_layers():
+    """The calling pattern of a model: for every step, every layer appends and attends, nothing is queried in
+    between.  amskv_attend leaves each trimming iteration (and the reading of its Eq. 3 score) to the layer's next
+    append; a reset drops the last one.  Three layers with different outcomes of the test, two images in a row
+    through the same cache: outputs of both passes, and the final token list and contents, against the oracle."""
+    sides, B, H, D = VAR, 3, 4, 64
+    tokens = [s * s for s in sides]
+    st = orc.scale_starts(tokens)
+    c_min, c_max, c_cds = 174, 274, 5
+    data, budgets, traces, wants = [], [], [], []
+    for layer, kind in enumerate(("demanding", "efficient", "always")):
+        q, k, v = inp.correlated_qkv(sides, B, H, D, "bf16", inp.layer_seed(7, 40 + layer), 0.8)
+        scores = _scores(sides, k)
+        asked = []
+        orc.alg1_cache_trace(tokens, c_min, c_max, c_cds, lambda i, c: asked.append(i) or False)
+        theta = {"demanding": _theta_above(scores, asked), "efficient": _theta_below_all(scores, asked), "always": 1.5}[kind]
+
+        def below(i, cached, scores=scores, theta=theta):
+            prev = set(range(st[i - 1], st[i])) if i > 0 else None
+            if theta > 1.0:
+                return True
+            if not prev or not prev <= set(cached):
+                return False
+            assert abs(scores[i] - theta) >= 0.05
+            return scores[i] < theta
+
+        trace = orc.alg1_cache_trace(tokens, c_min, c_max, c_cds, below)
+        cat = lambda xs: np.concatenate([_f64(x) for x in xs], axis=-2)
+        wants.append(orc.masked_attention(cat(q), cat(k), cat(v), orc.alg1_allow_mask(tokens, trace)))
+        traces.append(trace)
+        budgets.append((c_min, c_max, c_cds, theta))
+        data.append(tuple([x.cuda() for x in t] for t in (q, k, v)))
+    L = len(data)
+    need = amskv.amskv_cache_required_bytes(L, H, D, sides, sides, B, DT["bf16"], None, budgets=budgets)
+    arena = torch.empty(need, dtype=torch.uint8, device="cuda")
+    h = amskv.amskv_cache_create(L, H, D, sides, sides, B, DT["bf16"], None, arena=arena, budgets=budgets)
+    try:
+        for image in range(2):
+            amskv.amskv_cache_reset(h)
+            outs = [[torch.full_like(x, float("nan")) for x in data[l][0]] for l in range(L)]
+            for s in range(len(sides)):
+                for l in range(L):
+                    amskv.amskv_append_scale(h, l, s, data[l][1][s], data[l][2][s])
+                    amskv.amskv_attend(h, l, s, data[l][0][s], outs[l][s])
+            torch.cuda.synchronize()
+            for l in range(L):
+                got = np.concatenate([_f64(o) for o in outs[l]], axis=-2)
+                assert np.isfinite(got).all()
+                assert float(np.abs(got - wants[l]).max()) <= TOL["bf16"], "image %d layer %d" % (image, l)
+        for l in range(L):                      # the queries finish the last iteration
+            ids = traces[l][-1][0]
+            assert amskv.amskv_cache_budget_tokens(h, l) == traces[l][-1][1]
+            assert _segment_ids(tokens, amskv.amskv_cache_segments(h, l)) == ids
+            ko = torch.empty(B, H, len(ids), D, dtype=torch.bfloat16, device="cuda")
+            vo = torch.empty_like(ko)
+            amskv.amskv_cache_export(h, l, ko, vo)
+            torch.cuda.synchronize()
+            kb = np.concatenate([_bits(x) for x in data[l][1]], axis=-2)
+            vb = np.concatenate([_bits(x) for x in data[l][2]], axis=-2)
+            assert np.array_equal(_bits(ko), kb[..., ids, :]) and np.array_equal(_bits(vo), vb[..., ids, :])
+        assert [traces[l][-1][1] for l in range(L)] == [c_max, c_min, c_max]
+    finally:
+        amskv.amskv_cache_destroy(h)
