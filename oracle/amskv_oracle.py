@@ -15,7 +15,8 @@ Readings taken where the paper is silent or ambiguous (each is repeated at the
 function it affects):
   * eviction is scale-granular: a scale is either wholly kept or wholly dropped
     (the prose of Section 4.3 speaks of evicting whole scales; the token slicing of
-    Algorithm 2 is modelled separately in `clru` / `alg1_cache_trace`);
+    Algorithm 2 is modelled separately in `clru` / `alg1_cache_trace`, and the
+    token windows of the comparison policies in `token_window_cache`);
   * at step s the queries of scale s see the condensed scales {0..c-1}, the w scales
     that precede s, and s itself, all clipped to [0, s];
   * softmax scale defaults to 1/sqrt(D), no bias;
@@ -28,7 +29,9 @@ tiny schedules, equality with plain block-causal attention when the window cover
 every scale, library attention on the gathered kept keys, rows of P summing to one,
 O = V at scale 0, NaN-poisoned evicted scales, pure-Python triple loops on a 3-scale
 schedule, library bilinear resize, affine-ramp reproduction, cos = +-1 cases, and the
-integer-list simulation of Algorithms 1 and 2 (hand-derived traces, closed-form masks), and
+token-id sets of Algorithms 1 and 2 (hand-derived traces, closed-form masks), the token
+windows (hand trace, token-by-token queue, the cases that reduce to Algorithm 1 and to the
+block-causal mask), and
 for the attention density: mass summing to T_s, an element-by-element brute force, the
 uniform and the one-dominant-key cases.  No function here is "parity unpinned";
 the paper's printed GB and percent figures are unpinned (its Tables 3 and 5 disagree
@@ -292,46 +295,52 @@ def neg_l2_from_sums(sums: np.ndarray) -> np.ndarray:
     return -np.sqrt(np.maximum(s[..., 1] + s[..., 2] - 2.0 * s[..., 0], 0.0))
 
 
-# --------------------------------------------------------------------------- Algorithms 1 and 2, literal
-def clru(entries: List[int], c_bgt: int, c_cds: int) -> List[int]:
-    """Algorithm 2 on a list of cached token ids: unchanged within budget, otherwise the
-    first c_cds entries plus the last (c_bgt - c_cds) entries."""
-    if len(entries) <= c_bgt:
-        return list(entries)
-    k = c_bgt - c_cds
-    tail = entries[len(entries) - k:] if k > 0 else []
-    return list(entries[:c_cds]) + list(tail)
+# --------------------------------------------------------------------------- Algorithms 1 and 2 at token granularity
+# Stated here as what the two algorithms define rather than as their listings: the cache of a layer
+# is a SET of global token ids (ids grow with arrival time, so "oldest" = smallest id), Algorithm 2
+# is a selection rule on such a set, and one iteration of Algorithm 1 is three predicates on the
+# sizes involved followed by that selection.
+def clru(entries: Sequence[int], c_bgt: int, c_cds: int) -> List[int]:
+    """What Algorithm 2 leaves of a set of cached token ids under the budget c_bgt: everything if
+    it fits, otherwise the c_cds oldest ids (the condensed part) and the c_bgt - c_cds newest."""
+    ids = np.sort(np.asarray(list(entries), dtype=np.int64))
+    if ids.size <= c_bgt:
+        return ids.tolist()
+    rank = np.arange(ids.size)
+    keep = (rank < c_cds) | (rank >= ids.size - (c_bgt - c_cds))
+    return ids[keep].tolist()
 
 
 def alg1_cache_trace(tokens: Sequence[int], c_min: int, c_max: int, c_cds: int,
-                     below_theta: Sequence[bool]) -> List[Tuple[List[int], int]]:
-    """Algorithm 1 on token ids (token-granular, exactly as printed).
+                     below_theta) -> List[Tuple[List[int], int]]:
+    """The cache Algorithm 1 (Section 4.3) holds after every scale, token-granular.
 
-    below_theta[i] says whether S(k_i, k^_{i-1}) < theta would hold at scale i; a callable
-    (i, cached_ids_before) -> bool is asked only when the algorithm evaluates the test.
-    Returns, for every scale i, (global token ids cached after the iteration, budget in force).
+    Definition used.  With cache C and budget b before scale i (T_i tokens, ids I_i):
+      * the scale is a candidate only if T_i <= C_max;
+      * it overflows if |C| + T_i > b;
+      * an overflowing candidate met while b = C_min asks the similarity test of Eq. 3, and a
+        positive answer raises b to C_max for every later scale too;
+      * the scale is admitted if it is a candidate and, when it overflows, T_i <= b (after the raise);
+      * C becomes Algorithm 2's selection from C u I_i if admitted, and stays as it is otherwise.
+    below_theta: a sequence of bools per scale, or a callable (i, cached ids before) -> bool that
+    is called exactly when the test is asked.
+    Returns, per scale, (sorted cached ids after it, budget in force after it).
     """
     starts = scale_starts(tokens)
-    cache: List[int] = []
-    bgt = c_min
-    trace = []
-    for i, t in enumerate(tokens):
-        ids = list(range(starts[i], starts[i] + int(t)))
-        if len(ids) > c_max:
-            trace.append((list(cache), bgt))
-            continue
-        cand = cache + ids
-        if len(cand) > bgt:
-            if bgt == c_min and (below_theta(i, list(cache)) if callable(below_theta)
-                                 else below_theta[i]):
-                bgt = c_max
-            if len(ids) > bgt:
-                trace.append((list(cache), bgt))
-                continue
-            cand = clru(cand, bgt, c_cds)
-        cache = cand
-        trace.append((list(cache), bgt))
-    return trace
+    held = np.zeros(0, dtype=np.int64)
+    budget = c_min
+    out: List[Tuple[List[int], int]] = []
+    for i, t in enumerate(int(x) for x in tokens):
+        candidate = t <= c_max
+        overflows = candidate and held.size + t > budget
+        if overflows and budget == c_min:
+            answer = below_theta(i, held.tolist()) if callable(below_theta) else below_theta[i]
+            if answer:
+                budget = c_max
+        if candidate and (not overflows or t <= budget):
+            held = np.asarray(clru(np.concatenate([held, starts[i] + np.arange(t)]), budget, c_cds), dtype=np.int64)
+        out.append((held.tolist(), budget))
+    return out
 
 
 def alg1_allow_mask(tokens: Sequence[int], trace: Sequence[Tuple[List[int], int]]) -> np.ndarray:
@@ -348,6 +357,43 @@ def alg1_allow_mask(tokens: Sequence[int], trace: Sequence[Tuple[List[int], int]
         if i > 0:
             allow[rows, np.asarray(trace[i - 1][0], dtype=np.int64)] = True
     return allow
+
+
+# --------------------------------------------------------------------------- token windows (SWA / STA kept sets)
+def token_window_cache(tokens: Sequence[int], window: int, n_sink: int = 0) -> List[List[int]]:
+    """Cached token ids after every step under a fixed budget of `window` tokens over the flattened
+    token sequence: the sliding-window (n_sink = 0) and sink-plus-window kept sets that the
+    comparison with other cache strategies (Section 5, table of SWA / H2O / STA at a fixed
+    compression ratio) sets against AMS-KV.  Reading taken, the paper giving no definition for
+    next-scale prediction: after step i the cache holds, of all tokens of scales 0..i in order of
+    arrival, the first n_sink and the most recent window - n_sink (all of them while they fit);
+    a scale larger than the window is cut, never skipped."""
+    assert 0 <= n_sink <= window
+    starts = scale_starts(tokens)
+    out = []
+    for i, t in enumerate(tokens):
+        seen = starts[i] + int(t)
+        if seen <= window:
+            out.append(list(range(seen)))
+        else:
+            out.append(list(range(n_sink)) + list(range(seen - (window - n_sink), seen)))
+    return out
+
+
+def token_window_allow_mask(tokens: Sequence[int], window: int, n_sink: int = 0) -> np.ndarray:
+    """T x T mask of that policy: a query of scale i sees its own scale and what the cache held
+    after step i-1, written as a predicate on (query id, key id) alone."""
+    assert 0 <= n_sink <= window
+    sc = scale_of_token(tokens)
+    st = np.asarray(scale_starts(tokens), dtype=np.int64)
+    n = sc.size
+    key = np.arange(n)[None, :]
+    own_start = st[sc][:, None]                      # first token of the query's scale = tokens seen before it
+    same = sc[:, None] == sc[None, :]
+    past = key < own_start
+    fits = own_start <= window
+    recent = key >= own_start - (window - n_sink)
+    return same | (past & (fits | recent | (key < n_sink)))
 
 
 # --------------------------------------------------------------------------- attention density

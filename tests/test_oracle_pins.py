@@ -445,6 +445,75 @@ def test_alg1_theta_test_is_asked_once_and_only_on_overflow():
     assert calls == [7, 8, 9]
 
 
+# ------------------------------------------------------------------ token windows: the SWA / STA kept sets
+def test_token_window_hand_trace():
+    # 1 + 4 + 9 tokens, budget 6 with one sink token.  After step 0: {0}.  After step 1: five tokens, all fit.
+    # After step 2 fourteen tokens were seen: the sink 0 and the five newest, 9..13 -- the 3x3 scale is cut.
+    assert orc.token_window_cache([1, 4, 9], 6, 1) == [[0], [0, 1, 2, 3, 4], [0, 9, 10, 11, 12, 13]]
+    # no sink: the six newest
+    assert orc.token_window_cache([1, 4, 9], 6, 0)[2] == [8, 9, 10, 11, 12, 13]
+    m = orc.token_window_allow_mask([1, 4, 9, 4], 6, 1)
+    # queries of the 3x3 scale (ids 5..13) see their own scale and the five cached tokens
+    assert m[5].tolist() == [True] * 14 + [False] * 4
+    # queries of the last scale (ids 14..17) see the sink, ids 9..13 and themselves
+    assert np.flatnonzero(m[14]).tolist() == [0, 9, 10, 11, 12, 13, 14, 15, 16, 17]
+    assert np.array_equal(m[14], m[17])
+
+
+def test_token_window_against_a_token_by_token_queue():
+    # the same policy simulated one token at a time: a queue that, once full, drops its oldest
+    # entry behind the sink for every token that arrives
+    rng = np.random.default_rng(11)
+    for _ in range(40):
+        tokens = [int(x) for x in rng.integers(1, 12, size=int(rng.integers(1, 7)))]
+        window = int(rng.integers(1, 30))
+        n_sink = int(rng.integers(0, window + 1))
+        queue, after = [], []
+        g = 0
+        for t in tokens:
+            for _ in range(t):
+                queue.append(g)
+                g += 1
+                if len(queue) > window:
+                    del queue[n_sink]
+            after.append(list(queue))
+        if n_sink == window:      # nothing but sinks: the queue keeps the first `window` tokens
+            after = [list(range(min(window, sum(tokens[: i + 1])))) for i in range(len(tokens))]
+        assert orc.token_window_cache(tokens, window, n_sink) == after
+        # mask rows: own scale plus the cache of the step before
+        m = orc.token_window_allow_mask(tokens, window, n_sink)
+        st = orc.scale_starts(tokens)
+        for i, t in enumerate(tokens):
+            want = np.zeros(sum(tokens), dtype=bool)
+            want[st[i]: st[i] + t] = True
+            if i:
+                want[after[i - 1]] = True
+            assert np.array_equal(m[st[i]], want) and np.array_equal(m[st[i] + t - 1], want)
+
+
+def test_token_window_special_cases():
+    tokens = [s * s for s in (1, 2, 3, 4, 5, 6)]
+    n = sum(tokens)
+    st = orc.scale_starts(tokens)
+    # a window that holds everything is the block-causal mask; every row count is T_s + min(seen before, window)
+    assert np.array_equal(orc.token_window_allow_mask(tokens, n, 0), orc.allow_mask(tokens, (0, 0, True)))
+    assert np.array_equal(orc.token_window_allow_mask(tokens, n, 7), orc.allow_mask(tokens, (0, 0, True)))
+    for window, n_sink in ((10, 0), (10, 3), (40, 5), (1, 1), (0, 0)):
+        m = orc.token_window_allow_mask(tokens, window, n_sink)
+        for i, t in enumerate(tokens):
+            assert m[st[i]].sum() == t + min(st[i], window)
+    # while no scale exceeds the budget Algorithm 1 never skips, and with C_min = C_max it never tests:
+    # its cache is then this window with the condensed tokens as sinks
+    for window, n_sink in ((36, 0), (40, 5), (57, 14)):
+        tr = orc.alg1_cache_trace(tokens, window, window, n_sink, [False] * len(tokens))
+        assert [ids for ids, _ in tr] == orc.token_window_cache(tokens, window, n_sink)
+        assert np.array_equal(orc.alg1_allow_mask(tokens, tr), orc.token_window_allow_mask(tokens, window, n_sink))
+    # a scale larger than the window: Algorithm 1 skips it, the window keeps its newest tokens
+    tr = orc.alg1_cache_trace(tokens, 30, 30, 5, [False] * len(tokens))
+    tw = orc.token_window_cache(tokens, 30, 5)
+    assert tr[5][0] == tr[4][0] and tw[5] == [0, 1, 2, 3, 4] + list(range(n - 25, n))
+
+
 # ------------------------------------------------------------------ attention density (Section 4.1)
 def test_attention_density_invariants_and_closed_forms():
     rng = np.random.default_rng(5)
