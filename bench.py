@@ -117,13 +117,14 @@ def probe_policies(amskv, torch, x, dev):
     return pols
 
 
-def plan_trace(amskv, w, pols, budgets, layout, borrow, fuse):
+def plan_trace(amskv, w, pols, budgets, layout, borrow, fuse, windows=None):
     """What every step attends to, moves and copies, from the library's own host logic on a plan-only cache
     (no device memory): per (layer, scale) the tokens attended, the tokens that changed their place in the arena
     and the tokens of the new scale written into it."""
     B, H, D, L, S = w.batch, w.heads, w.head_dim, w.layers, len(w.tokens)
     plan = amskv.amskv_cache_create(L, H, D, w.sides, w.sides, B, 1, pols, 0.0, layout, borrow_unretained=borrow,
-                                    fuse_append=fuse, budgets=budgets)
+                                    fuse_append=fuse, budgets=budgets, windows=windows)
+    token_mode = budgets is not None or windows is not None
     kv_len = [[0] * S for _ in range(L)]
     moved = [[0] * S for _ in range(L)]
     copied = [[0] * S for _ in range(L)]
@@ -134,7 +135,7 @@ def plan_trace(amskv, w, pols, budgets, layout, borrow, fuse):
                 amskv.amskv_append_scale(plan, l, s)
                 segs = amskv.amskv_cache_segments(plan, l)
                 kv_len[l][s] = sum(x[3] for x in segs)            # the step's attention sees these (current scale included)
-                if budgets is not None:
+                if token_mode:
                     amskv.amskv_cache_settle(plan, l)             # the step's iteration of Algorithm 1
                     segs = amskv.amskv_cache_segments(plan, l)
                 now = {(sc, first + i): off + i for sc, first, off, ln in segs if off >= 0 for i in range(ln)}
@@ -156,16 +157,19 @@ def dominant_kernel_name(w, tokens):
     return "attend_bf16_kernel<64,1,8,64,4>" if max(tokens) > 128 else "attend_bf16_kernel<64,1,4,32,4>"
 
 
-def measure(amskv, torch, x, dev, mode, pols, budgets, layout_name, borrow, fuse, steps, warmup, per_scale=False, n_inst=3):
+def measure(amskv, torch, x, dev, mode, pols, budgets, layout_name, borrow, fuse, steps, warmup, per_scale=False, n_inst=3,
+            windows=None):
     """Timed steps, then instrumented passes with HIP events around every launch on the launch stream."""
     w = x.w
     B, H, D, L = w.batch, w.heads, w.head_dim, w.layers
     tokens, S = w.tokens, len(w.tokens)
     layout = amskv.AMSKV_LAYOUT_PLANNED if layout_name == "planned" else amskv.AMSKV_LAYOUT_COMPACT
-    need = amskv.amskv_cache_required_bytes(L, H, D, w.sides, w.sides, B, 1, pols, 0.0, layout, borrow, fuse, budgets=budgets)
+    need = amskv.amskv_cache_required_bytes(L, H, D, w.sides, w.sides, B, 1, pols, 0.0, layout, borrow, fuse, budgets=budgets,
+                                            windows=windows)
     arena = torch.empty(need, dtype=torch.uint8, device=dev)
     cache = amskv.amskv_cache_create(L, H, D, w.sides, w.sides, B, 1, pols, 0.0, layout, arena=arena,
-                                     borrow_unretained=borrow, fuse_append=fuse, budgets=budgets)
+                                     borrow_unretained=borrow, fuse_append=fuse, budgets=budgets, windows=windows)
+    token_mode = budgets is not None or windows is not None
     probe = PROBE_SCALE if S > PROBE_SCALE else S - 1
     Kp, Vp, Qp, Op, stream = x.Kp, x.Vp, x.Qp, x.Op, x.stream
 
@@ -184,10 +188,10 @@ def measure(amskv, torch, x, dev, mode, pols, budgets, layout_name, borrow, fuse
                     amskv.amskv_attend(cache, l, s, Qp[l][s], Op[s], stream)
                     e[2].record()
                     timers.append((l, s, e))
-            if s == probe and probe >= 1 and budgets is None:
+            if s == probe and probe >= 1 and not token_mode:
                 for l in range(L):
                     amskv.amskv_interscale_similarity_enqueue(cache, l, s, want_v=False, stream=stream)
-        if probe >= 1 and budgets is None:   # the scores of all layers: one transfer, one wait per step
+        if probe >= 1 and not token_mode:   # the scores of all layers: one transfer, one wait per step
             amskv.amskv_interscale_similarity_collect(cache, L, H, want_v=False, want_sums=False, stream=stream)
 
     for _ in range(warmup):
@@ -206,7 +210,7 @@ def measure(amskv, torch, x, dev, mode, pols, budgets, layout_name, borrow, fuse
         expanded = [amskv.amskv_cache_budget_tokens(cache, l) == budgets[l][1] for l in range(L)]
         forced = [(a, b, c, 2.0 if expanded[l] else -2.0) for l, (a, b, c, _) in enumerate(budgets)]
         log("layers whose budget the Eq. 3 test expanded:", [l for l in range(L) if expanded[l]])
-    kv_len, moved, copied = plan_trace(amskv, w, pols, forced, layout, borrow, fuse)
+    kv_len, moved, copied = plan_trace(amskv, w, pols, forced, layout, borrow, fuse, windows)
     flops = sum(4.0 * B * H * tokens[s] * kv_len[l][s] * D for l in range(L) for s in range(S))
     held = sum(amskv.amskv_cache_bytes_held(cache, l, True) for l in range(L))
     held_paper = sum(amskv.amskv_cache_bytes_held(cache, l, False) for l in range(L))
@@ -225,7 +229,7 @@ def measure(amskv, torch, x, dev, mode, pols, budgets, layout_name, borrow, fuse
         ta, tt = e[0].elapsed_time(e[1]) * 1e-3, e[1].elapsed_time(e[2]) * 1e-3
         by = (2 * tokens[s] + 2 * kv_len[l][s]) * unit                    # Q read, O written, K~ and V~ read once
         roll = 2 * (2 * moved[l][s] + 2 * copied[l][s]) * unit             # K and V: read + write what moves or is copied in
-        if budgets is not None:
+        if token_mode:
             if moved[l][s] == 0 and copied[l][s] == tokens[s]:
                 by += 2 * copied[l][s] * unit      # the scale fits untrimmed: the attend launch writes it as it streams it
                 aby = 0.0
@@ -351,11 +355,13 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="var_d30", choices=["var_d30", "var_d16", "var_d24", "infinity_2b"])
     ap.add_argument("--batch", type=int, default=0, help="0 = the configuration's batch")
-    ap.add_argument("--mode", default="amskv", choices=["amskv", "vanilla", "efficient", "token_budget"],
+    ap.add_argument("--mode", default="amskv", choices=["amskv", "vanilla", "efficient", "token_budget", "swa", "sta"],
                     help="amskv: per-layer scale windows picked from the similarity probe (the default, the contract's "
                          "workload); vanilla: every layer keeps everything; efficient: every layer gets the configuration's "
                          "cache-efficient policy; token_budget: Algorithms 1 and 2 literally, budgets in tokens, the Eq. 3 "
-                         "test and the budget expansion run inside the step")
+                         "test and the budget expansion run inside the step; swa / sta: the sliding-window and sink + window "
+                         "kept sets of the paper's comparison at 75 %% compression (a quarter of the schedule's tokens, "
+                         "sta with the first two scales as sinks), token-granular, structure only")
     ap.add_argument("--layout", default="planned", choices=["compact", "planned"],
                     help="planned (default): every scale has a fixed slot, eviction moves nothing; compact: kept "
                          "scales stay back to back, eviction slides the survivors down")
@@ -400,7 +406,7 @@ def main():
     x = Inputs(args.workload, args.batch, dev)
     w = x.w
     tokens, S, L, H, D, B = w.tokens, len(w.tokens), w.layers, w.heads, w.head_dim, w.batch
-    budgets = None
+    budgets = windows = None
     mix = probe_policies(amskv, torch, x, dev) if args.workload == "var_d30" and args.mode in ("amskv",) else None
     if args.mode == "token_budget":
         # Section 5 set-up read as token counts: condensed = the first two scales, C_min = condensed + the
@@ -408,6 +414,10 @@ def main():
         # contiguous run (COMPACT), the current scale is always read in place
         c_cds = tokens[0] + tokens[1]
         budgets = [(c_cds + tokens[-2], c_cds + tokens[-3] + tokens[-2], c_cds, COS_THRESHOLD)] * L
+        layout_name, borrow, fuse = "compact", False, False
+        pols = None
+    elif args.mode in ("swa", "sta"):
+        windows = [(sum(tokens) // 4, tokens[0] + tokens[1] if args.mode == "sta" else 0)] * L
         layout_name, borrow, fuse = "compact", False, False
         pols = None
     elif args.mode == "vanilla":
@@ -418,9 +428,9 @@ def main():
         pols = mix
 
     res = measure(amskv, torch, x, dev, args.mode, pols, budgets, layout_name, borrow, fuse, args.steps, args.warmup,
-                  per_scale=args.per_scale)
+                  per_scale=args.per_scale, windows=windows)
     sa = standalone_append(amskv, torch, x, dev, pols if pols is not None else list(w.policies))
-    dens = density_probe(amskv, torch, x, res) if budgets is None else None
+    dens = density_probe(amskv, torch, x, res) if pols is not None else None
     roof = res["roofline"]
 
     out = {
@@ -430,9 +440,10 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "mode": args.mode, "layout": layout_name, "borrow_unretained": int(borrow),
                    "fuse_append": int(fuse), "layers": L, "heads": H, "head_dim": D, "batch": B, "tokens": sum(tokens), "scales": S,
-                   "cache_demanding_layers": sum(res["expanded"]) if budgets is not None else sum(1 for p in pols if p[2]),
+                   "cache_demanding_layers": sum(res["expanded"]) if budgets is not None else sum(1 for p in (pols or []) if p[2]),
                    "probe_scale": res["probe"],
-                   **({"budgets_c_min_c_max_c_cds_theta": list(budgets[0])} if budgets is not None else {})},
+                   **({"budgets_c_min_c_max_c_cds_theta": list(budgets[0])} if budgets is not None else {}),
+                   **({"window_tokens_and_sinks": list(windows[0])} if windows is not None else {})},
         "ms_per_image": res["ms_per_step"] / B,
         "kv_bytes_held": res["held"], "kv_bytes_held_excluding_current_scale": res["held_paper"],
         "kv_bytes_vanilla": res["vanilla_held"], "kv_reduction": 1.0 - res["held"] / res["vanilla_held"],
@@ -475,7 +486,8 @@ def main():
 
     # ---------------- the oracle, timed on the host cores, on a bounded sample of the same workload
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, pols, x.K, x.V, x.Q, tokens, H, D, kv_len0, out["attention_flops_per_step"], budget0)
+        out["cpu_baseline"] = cpu_baseline(w, pols, x.K, x.V, x.Q, tokens, H, D, kv_len0, out["attention_flops_per_step"], budget0,
+                                           None if windows is None else windows[0])
 
     if full:
         # ---------------- the other shapes the contract names, each with its own roofline object
@@ -494,7 +506,7 @@ def main():
     print(json.dumps(out), flush=True)
 
 
-def cpu_baseline(w, pols, K, V, Q, tokens, H, D, kv_len0, step_flops, budget0=None):
+def cpu_baseline(w, pols, K, V, Q, tokens, H, D, kv_len0, step_flops, budget0=None, window0=None):
     """The oracle as it stands, on (layer 0, the first few batch rows, all heads, all scales)."""
     import numpy as np
     from oracle import amskv_oracle as orc
@@ -514,7 +526,10 @@ def cpu_baseline(w, pols, K, V, Q, tokens, H, D, kv_len0, step_flops, budget0=No
         k = [t[b:b + nb_now].double().cpu().numpy() for t in K[l]]
         v = [t[b:b + nb_now].double().cpu().numpy() for t in V[l]]
         t0 = time.perf_counter()
-        if budget0 is not None:
+        if window0 is not None:
+            cat = lambda xs: np.concatenate(xs, axis=-2)
+            orc.masked_attention(cat(q), cat(k), cat(v), orc.token_window_allow_mask(tokens, window0[0], window0[1]))
+        elif budget0 is not None:
             (c_min, c_max, c_cds, _), grew = budget0
             trace = orc.alg1_cache_trace(tokens, c_min, c_max, c_cds, [grew] * S)
             cat = lambda xs: np.concatenate(xs, axis=-2)

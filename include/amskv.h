@@ -51,7 +51,7 @@ typedef enum {
 
 enum { AMSKV_DTYPE_F32 = 0, AMSKV_DTYPE_BF16 = 1 };
 enum { AMSKV_LAYOUT_COMPACT = 0, AMSKV_LAYOUT_PLANNED = 1 };
-enum { AMSKV_MODE_SCALE_WINDOW = 0, AMSKV_MODE_TOKEN_BUDGET = 1 };
+enum { AMSKV_MODE_SCALE_WINDOW = 0, AMSKV_MODE_TOKEN_BUDGET = 1, AMSKV_MODE_TOKEN_WINDOW = 2 };
 enum { AMSKV_IO_HEAD_MAJOR = 0, AMSKV_IO_TOKEN_MAJOR = 1 };
 enum { AMSKV_MAX_SCALES = 16 };
 enum { AMSKV_STATIC_MAX_UNITS = 16384 }; /* batch * heads limit of amskv_interscale_similarity_enqueue_static */
@@ -108,8 +108,8 @@ typedef struct {
   int32_t layout;                   /* AMSKV_LAYOUT_COMPACT or AMSKV_LAYOUT_PLANNED       */
   int32_t borrow_unretained;        /* 0 / 1, see below                                   */
   int32_t fuse_append;              /* 0 / 1, see below                                   */
-  int32_t mode;                     /* AMSKV_MODE_SCALE_WINDOW (0) or AMSKV_MODE_TOKEN_BUDGET */
-  const amskv_layer_budget* budget; /* host, [n_layers]; token-budget mode only           */
+  int32_t mode;                     /* AMSKV_MODE_SCALE_WINDOW (0), _TOKEN_BUDGET or _TOKEN_WINDOW */
+  const amskv_layer_budget* budget; /* host, [n_layers]; token-budget and token-window modes */
 } amskv_policy;
 
 /* borrow_unretained.  Algorithm 1 stores a scale only if a later step will read it (a scale
@@ -155,6 +155,17 @@ typedef struct {
  * K_dev/V_dev of scale s must stay valid and unchanged until the iteration has run: until the
  * work enqueued by the next amskv_append_scale / amskv_cache_settle / query on the layer has
  * finished, or until amskv_cache_reset. */
+
+/* mode = AMSKV_MODE_TOKEN_WINDOW.  The sliding-window and sink-plus-window kept sets that the
+ * comparison with other cache strategies (Section 5, the table of SWA / H2O / STA) sets against
+ * AMS-KV, at token granularity over the flattened token sequence: budget[l] with c_min == c_max
+ * = the window W in tokens and c_cds = the number of sink tokens (0 for a plain sliding window);
+ * theta is not used.  After step s the layer holds the first c_cds tokens ever appended and the
+ * newest W - c_cds (everything while it fits).  It is the token-budget machinery with one
+ * budget and one difference: a scale larger than the window is cut to its newest tokens, not
+ * skipped.  Layout, calling order, deferred iteration and buffer lifetimes as in token-budget
+ * mode.  (H2O keeps tokens by attention score and is not expressible as a kept set fixed before
+ * the step.) */
 
 /* Bytes the arena must have for this configuration: for every layer the K and V regions
  * sized for the largest kept set the policy ever reaches (Section 4.3: capacity is fixed

@@ -25,7 +25,7 @@ AMSKV_ERR_STATIC_LIMIT = -7
 AMSKV_STATIC_MAX_UNITS = 16384
 AMSKV_DTYPE_F32, AMSKV_DTYPE_BF16 = 0, 1
 AMSKV_LAYOUT_COMPACT, AMSKV_LAYOUT_PLANNED = 0, 1
-AMSKV_MODE_SCALE_WINDOW, AMSKV_MODE_TOKEN_BUDGET = 0, 1
+AMSKV_MODE_SCALE_WINDOW, AMSKV_MODE_TOKEN_BUDGET, AMSKV_MODE_TOKEN_WINDOW = 0, 1, 2
 AMSKV_IO_HEAD_MAJOR, AMSKV_IO_TOKEN_MAJOR = 0, 1
 AMSKV_MAX_SCALES = 16
 _MAX_SEGMENTS = AMSKV_MAX_SCALES + 2
@@ -140,9 +140,16 @@ def _check(status: int, where: str):
 
 
 def _structs(sides_h, sides_w, batch, dtype, policies, softmax_scale, layout, borrow_unretained=False, fuse_append=False,
-             budgets=None):
+             budgets=None, windows=None):
     """policies: [(n_condensed, window, keep_all)] per layer (scale-window mode), or None with
-    budgets: [(c_min, c_max, c_cds, theta)] per layer (token-budget mode)."""
+    budgets: [(c_min, c_max, c_cds, theta)] per layer (token-budget mode), or None with
+    windows: [(window_tokens, n_sink)] per layer (token-window mode)."""
+    mode = AMSKV_MODE_SCALE_WINDOW
+    if budgets is not None:
+        mode = AMSKV_MODE_TOKEN_BUDGET
+    if windows is not None:
+        mode = AMSKV_MODE_TOKEN_WINDOW
+        budgets = [(int(w), int(w), int(k), 0.0) for w, k in windows]
     n = len(sides_h)
     ah = (C.c_int32 * n)(*[int(x) for x in sides_h])
     aw = (C.c_int32 * n)(*[int(x) for x in sides_w])
@@ -154,7 +161,7 @@ def _structs(sides_h, sides_w, batch, dtype, policies, softmax_scale, layout, bo
         bp = (_LayerBudget * len(budgets))(*[_LayerBudget(int(a), int(b), int(c), float(t)) for a, b, c, t in budgets])
     n_layers = len(budgets) if budgets is not None else len(policies)
     po = _Policy(n_layers, lp, float(softmax_scale), int(layout), int(bool(borrow_unretained)), int(bool(fuse_append)),
-                 AMSKV_MODE_TOKEN_BUDGET if budgets is not None else AMSKV_MODE_SCALE_WINDOW, bp)
+                 mode, bp)
     return sc, po, (ah, aw, lp, bp)
 
 
@@ -179,9 +186,9 @@ def _stream(stream) -> Optional[int]:
 # ------------------------------------------------------------------ the calls of amskv.h
 def amskv_cache_required_bytes(layers, heads, head_dim, sides_h, sides_w, batch, dtype, policies,
                                softmax_scale=0.0, layout=AMSKV_LAYOUT_COMPACT, borrow_unretained=False, fuse_append=False,
-                               budgets=None) -> int:
+                               budgets=None, windows=None) -> int:
     sc, po, _keep = _structs(sides_h, sides_w, batch, dtype, policies, softmax_scale, layout, borrow_unretained, fuse_append,
-                             budgets)
+                             budgets, windows)
     out = C.c_uint64(0)
     _check(load_library().amskv_cache_required_bytes(layers, heads, head_dim, C.byref(sc), C.byref(po),
                                                      C.byref(out)), "amskv_cache_required_bytes")
@@ -190,11 +197,12 @@ def amskv_cache_required_bytes(layers, heads, head_dim, sides_h, sides_w, batch,
 
 def amskv_cache_create(layers, heads, head_dim, sides_h, sides_w, batch, dtype, policies,
                        softmax_scale=0.0, layout=AMSKV_LAYOUT_COMPACT, arena=None, arena_bytes=None,
-                       borrow_unretained=False, fuse_append=False, budgets=None):
+                       borrow_unretained=False, fuse_append=False, budgets=None, windows=None):
     """arena: torch uint8 device tensor (kept alive by the caller) or None for a plan-only cache.
-    budgets (with policies=None) selects the token-budget mode.  Returns the opaque handle (an int)."""
+    budgets (with policies=None) selects the token-budget mode, windows (with policies=None) the token-window mode.
+    Returns the opaque handle (an int)."""
     sc, po, _keep = _structs(sides_h, sides_w, batch, dtype, policies, softmax_scale, layout, borrow_unretained, fuse_append,
-                             budgets)
+                             budgets, windows)
     h = C.c_void_p(None)
     nbytes = 0 if arena is None else (int(arena.numel() * arena.element_size()) if arena_bytes is None else int(arena_bytes))
     _check(load_library().amskv_cache_create(layers, heads, head_dim, C.byref(sc), C.byref(po), _ptr(arena),

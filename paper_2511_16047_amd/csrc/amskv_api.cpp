@@ -58,6 +58,7 @@ struct LayerState {
 
 struct amskv_cache {
   int32_t layers, heads, head_dim, batch, dtype, n_scales, layout, borrow, fuse, mode;
+  bool cut_oversize = false;  // token-window mode: a scale larger than the budget keeps its newest tokens instead of being skipped
   int32_t side_h[AMSKV_MAX_SCALES], side_w[AMSKV_MAX_SCALES], tokens[AMSKV_MAX_SCALES];
   float softmax_scale;
   int32_t elem_bytes;
@@ -125,7 +126,7 @@ int validate(int32_t layers, int32_t heads, int32_t head_dim, const amskv_schedu
   if (po->borrow_unretained != 0 && po->borrow_unretained != 1) return AMSKV_ERR_INVALID_ARG;
   if (po->fuse_append != 0 && po->fuse_append != 1) return AMSKV_ERR_INVALID_ARG;
   if (!(po->softmax_scale >= 0.f) || !std::isfinite(po->softmax_scale)) return AMSKV_ERR_INVALID_ARG;
-  if (po->mode == AMSKV_MODE_TOKEN_BUDGET) {
+  if (po->mode == AMSKV_MODE_TOKEN_BUDGET || po->mode == AMSKV_MODE_TOKEN_WINDOW) {
     if (!po->budget || po->layout != AMSKV_LAYOUT_COMPACT || po->borrow_unretained || po->fuse_append)
       return AMSKV_ERR_INVALID_ARG;
     for (int l = 0; l < layers; ++l) {
@@ -133,6 +134,7 @@ int validate(int32_t layers, int32_t heads, int32_t head_dim, const amskv_schedu
       if (b.c_cds < 0 || b.c_min < b.c_cds || b.c_max < b.c_min || b.c_max < 1 || b.c_max > (1 << 22) ||
           std::isnan(b.theta))
         return AMSKV_ERR_INVALID_ARG;
+      if (po->mode == AMSKV_MODE_TOKEN_WINDOW && b.c_min != b.c_max) return AMSKV_ERR_INVALID_ARG;  // one fixed window
     }
     return AMSKV_OK;
   }
@@ -211,7 +213,7 @@ void build_plan(int32_t layers, int32_t heads, int32_t head_dim, const amskv_sch
   pl->slot.assign(layers, std::vector<int32_t>(AMSKV_MAX_SCALES, 0));
   for (int l = 0; l < layers; ++l) {
     int64_t cap;
-    if (po->mode == AMSKV_MODE_TOKEN_BUDGET)
+    if (po->mode != AMSKV_MODE_SCALE_WINDOW)
       cap = po->budget[l].c_max;  // Section 4.3: C_max is the most a layer ever holds
     else if (po->layout == AMSKV_LAYOUT_PLANNED)
       cap = plan_slots(po->layer[l], tokens, sc->n_scales, borrow, pl->slot[l].data());
@@ -408,7 +410,7 @@ int roll_budget(amskv_cache* c, LayerState& L, hipStream_t st, int32_t appended_
   int64_t n_old = 0;
   for (size_t i = 0; i + 1 < L.segs.size(); ++i) n_old += L.segs[i].len;
   int32_t bgt = L.c_bgt;
-  bool cache_it = t_new <= L.bud.c_max;
+  bool cache_it = c->cut_oversize || t_new <= L.bud.c_max;
   const bool overflow = cache_it && n_old + t_new > bgt;
   const bool wants_test = overflow && bgt == L.bud.c_min && L.bud.c_max > L.bud.c_min;
   if (L.deferred) {
@@ -442,7 +444,7 @@ int roll_budget(amskv_cache* c, LayerState& L, hipStream_t st, int32_t appended_
       }
       if (state == kTestHolds) bgt = L.bud.c_max;
     }
-    if (t_new > bgt) cache_it = false;
+    if (t_new > bgt && !c->cut_oversize) cache_it = false;
   }
 
   struct CopyRange {
@@ -610,7 +612,9 @@ int32_t amskv_cache_create(int32_t layers, int32_t heads, int32_t head_dim,
   c->layout = po->layout;
   c->borrow = po->borrow_unretained;
   c->fuse = po->fuse_append;
-  c->mode = po->mode;
+  // the token window is the token-budget machinery with one fixed budget and oversize scales cut
+  c->mode = po->mode == AMSKV_MODE_TOKEN_WINDOW ? AMSKV_MODE_TOKEN_BUDGET : po->mode;
+  c->cut_oversize = po->mode == AMSKV_MODE_TOKEN_WINDOW;
   c->elem_bytes = sc->dtype == AMSKV_DTYPE_BF16 ? 2 : 4;
   c->softmax_scale = po->softmax_scale > 0.f ? po->softmax_scale : 1.0f / std::sqrt((float)head_dim);
   for (int i = 0; i < sc->n_scales; ++i) {

@@ -1,0 +1,163 @@
+"""GPU parity of the token-window mode: sliding window (SWA) and sink + window (STA) kept sets at token
+granularity, the comparison policies of Section 5, through the C ABI against the oracle's mask on the same
+seeded inputs.
+
+Bar: bit-exact for the cached token list, its offsets and the cache contents; max-abs 1e-4 (fp32) / 2e-2
+(bf16) on the attention outputs.
+"""
+import numpy as np
+import pytest
+import torch
+
+import amskv_inputs as inp
+import paper_2511_16047_amd as amskv
+from oracle import amskv_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+DT = {"f32": amskv.AMSKV_DTYPE_F32, "bf16": amskv.AMSKV_DTYPE_BF16}
+VAR = (1, 2, 3, 4, 5, 6, 8, 10, 13, 16)
+
+
+def _bits(t):
+    it = torch.int16 if t.dtype == torch.bfloat16 else torch.int32
+    return t.contiguous().view(it).cpu().numpy()
+
+
+def _f64(t):
+    return t.detach().to("cpu", torch.float64).numpy()
+
+
+def _segment_ids(tokens, segs):
+    st = orc.scale_starts(tokens)
+    ids, at = [], 0
+    for scale, first, off, ln in segs:
+        if off >= 0:
+            assert off == at
+            at += ln
+        ids += list(range(st[scale] + first, st[scale] + first + ln))
+    return ids
+
+
+def _run(sides, B, H, D, dtype, window, n_sink, seed, query_between=True):
+    tokens = [s * s for s in sides]
+    st = orc.scale_starts(tokens)
+    q, k, v = inp.correlated_qkv(sides, B, H, D, dtype, seed, 0.7)
+    cat = lambda xs: np.concatenate([_f64(x) for x in xs], axis=-2)
+    want = orc.masked_attention(cat(q), cat(k), cat(v), orc.token_window_allow_mask(tokens, window, n_sink))
+    cached = orc.token_window_cache(tokens, window, n_sink)
+    kb_all = np.concatenate([_bits(x) for x in k], axis=-2)
+    vb_all = np.concatenate([_bits(x) for x in v], axis=-2)
+    qd, kd, vd = ([x.cuda() for x in t] for t in (q, k, v))
+    windows = [(window, n_sink)]
+    need = amskv.amskv_cache_required_bytes(1, H, D, sides, sides, B, DT[dtype], None, windows=windows)
+    arena = torch.empty(need, dtype=torch.uint8, device="cuda")
+    arena.fill_(0xFF)
+    h = amskv.amskv_cache_create(1, H, D, sides, sides, B, DT[dtype], None, arena=arena, windows=windows)
+
+    def check_contents(ids):
+        assert _segment_ids(tokens, amskv.amskv_cache_segments(h, 0)) == ids
+        if not ids:
+            return
+        ko = torch.empty(B, H, len(ids), D, dtype=kd[0].dtype, device="cuda")
+        vo = torch.empty_like(ko)
+        amskv.amskv_cache_export(h, 0, ko, vo)
+        torch.cuda.synchronize()
+        assert np.array_equal(_bits(ko), kb_all[..., ids, :]) and np.array_equal(_bits(vo), vb_all[..., ids, :])
+
+    worst = 0.0
+    try:
+        outs = []
+        for s in range(len(sides)):
+            amskv.amskv_append_scale(h, 0, s, kd[s], vd[s])
+            o = torch.full_like(qd[s], float("nan"))
+            amskv.amskv_attend(h, 0, s, qd[s], o)
+            outs.append(o)
+            if query_between:
+                check_contents(cached[s])
+        torch.cuda.synchronize()
+        for s in range(len(sides)):
+            got = _f64(outs[s])
+            assert np.isfinite(got).all()
+            err = float(np.abs(got - want[..., st[s]: st[s] + tokens[s], :]).max())
+            worst = max(worst, err)
+            assert err <= TOL[dtype], "step %d max-abs %.3e" % (s, err)
+        check_contents(cached[-1])
+        assert amskv.amskv_cache_bytes_held(h, 0) == 2 * (2 if dtype == "bf16" else 4) * B * H * D * len(cached[-1])
+    finally:
+        amskv.amskv_cache_destroy(h)
+    return worst
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("window,n_sink", [(170, 0), (170, 5), (100, 0), (64, 14), (680, 0), (1, 1), (1, 0)],
+                         ids=["swa170", "sta170", "swa_cuts_scales", "sta_cuts_scales", "everything", "one_sink", "one_token"])
+def test_var_schedule(dtype, window, n_sink):
+    # 170 tokens = a quarter of the 680 of the schedule: the 75 % compression of the paper's comparison;
+    # windows of 100 and 64 are smaller than the last scales, which are then cut, not skipped
+    _run(VAR, 2, 3, 64, dtype, window, n_sink, inp.layer_seed(8, window + n_sink))
+
+
+@pytest.mark.parametrize("case", [
+    ((2, 3, 5, 7, 11), 1, 5, 64, 40, 4),     # ragged: 121-token final scale, cut
+    ((3, 1, 4, 1, 5), 2, 2, 128, 17, 9),     # head dim 128, the sinks end inside a scale
+    ((1, 2, 3, 4, 6, 9, 13, 18, 24), 1, 2, 128, 300, 5),   # several query tiles per unit at head dim 128
+], ids=["ragged", "d128_sink_inside_scale", "d128_multi_tile"])
+def test_other_schedules(case):
+    sides, B, H, D, window, n_sink = case
+    _run(sides, B, H, D, "bf16", window, n_sink, inp.layer_seed(8, 100 + window))
+
+
+def test_no_queries_between_steps():
+    # the model's calling pattern: nothing reads the cache state between the steps
+    _run(VAR, 3, 2, 64, "bf16", 170, 5, inp.layer_seed(8, 7), query_between=False)
+
+
+def test_full_batch_sampled_units():
+    """The benchmark's window configurations (VAR-d30 shape, batch 256, 170 tokens without and with 5 sinks):
+    16 sampled (b,h) each against the oracle."""
+    w = inp.config3(batch=256)
+    sides, B, H, D = w.sides, w.batch, w.heads, w.head_dim
+    tokens = [s * s for s in sides]
+    st = orc.scale_starts(tokens)
+    for layer, (window, n_sink) in enumerate(((170, 0), (170, 5))):
+        q, k, v = inp.correlated_qkv(sides, B, H, D, "bf16", inp.layer_seed(3, layer), 0.6, device="cuda")
+        windows = [(window, n_sink)]
+        need = amskv.amskv_cache_required_bytes(1, H, D, sides, sides, B, DT["bf16"], None, windows=windows)
+        arena = torch.empty(need, dtype=torch.uint8, device="cuda")
+        arena.fill_(0xFF)
+        h = amskv.amskv_cache_create(1, H, D, sides, sides, B, DT["bf16"], None, arena=arena, windows=windows)
+        try:
+            outs = []
+            for s in range(len(sides)):
+                amskv.amskv_append_scale(h, 0, s, k[s], v[s])
+                o = torch.full_like(q[s], float("nan"))
+                amskv.amskv_attend(h, 0, s, q[s], o)
+                outs.append(o)
+            torch.cuda.synchronize()
+            ids = orc.token_window_cache(tokens, window, n_sink)[-1]
+            assert _segment_ids(tokens, amskv.amskv_cache_segments(h, 0)) == ids
+            ko = torch.empty(B, H, len(ids), D, dtype=torch.bfloat16, device="cuda")
+            vo = torch.empty_like(ko)
+            amskv.amskv_cache_export(h, 0, ko, vo)
+            torch.cuda.synchronize()
+            allow = orc.token_window_allow_mask(tokens, window, n_sink)
+            units = sorted({(b, hh) for (_, b, hh) in inp.sample_units(1, B, H, 16, 17 + layer)})
+            worst = 0.0
+            for b, hh in units:
+                pick = lambda xs: np.concatenate([_f64(x[b:b + 1, hh:hh + 1]) for x in xs], axis=-2)
+                want = orc.masked_attention(pick(q), pick(k), pick(v), allow)
+                for s in range(len(sides)):
+                    got = _f64(outs[s][b:b + 1, hh:hh + 1])
+                    assert np.isfinite(got).all()
+                    worst = max(worst, float(np.abs(got - want[..., st[s]: st[s] + tokens[s], :]).max()))
+                kb = np.concatenate([_bits(x[b:b + 1, hh:hh + 1]) for x in k], axis=-2)[..., ids, :]
+                vb = np.concatenate([_bits(x[b:b + 1, hh:hh + 1]) for x in v], axis=-2)[..., ids, :]
+                assert np.array_equal(_bits(ko[b:b + 1, hh:hh + 1]), kb) and np.array_equal(_bits(vo[b:b + 1, hh:hh + 1]), vb)
+            assert worst <= TOL["bf16"], worst
+            print("token window %d with %d sinks, full batch: worst max-abs %.3e over %d units" % (window, n_sink, worst, len(units)))
+        finally:
+            amskv.amskv_cache_destroy(h)
+            del q, k, v, arena
+            torch.cuda.empty_cache()

@@ -330,3 +330,46 @@ def test_oversized_launches_are_rejected_at_create():
     with pytest.raises(amskv.AmskvError) as e:
         amskv.amskv_cache_required_bytes(1, 4096, 64, (1024,), (1024,), 4096, amskv.AMSKV_DTYPE_BF16, [(0, 0, True)])
     assert e.value.status == amskv.AMSKV_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("sides", [VAR, INF, (1, 2, 3), (2, 2, 5, 3), (3, 1, 4, 1, 5, 9, 2, 6)])
+def test_token_window_mode_matches_the_oracle(sides):
+    """Sliding window / sink + window at token granularity (the SWA / STA kept sets): the segment list after every
+    step is the oracle's window over the flattened token sequence, also where a scale is larger than the window."""
+    import random
+    tokens = [s * s for s in sides]
+    total = sum(tokens)
+    rng = random.Random(4321 + len(sides))
+    windows = [(170, 0), (170, 5), (total, 0), (total + 5, 3), (1, 0), (1, 1), (7, 7), (max(tokens) - 1, 2)]
+    for _ in range(40):
+        w = rng.randint(1, total + 3)
+        windows.append((w, rng.randint(0, w)))
+    B, H, D = 2, 3, 64
+    h = amskv.amskv_cache_create(len(windows), H, D, sides, sides, B, amskv.AMSKV_DTYPE_BF16, None, windows=windows)
+    try:
+        want = [orc.token_window_cache(tokens, w, k) for w, k in windows]
+        for s in range(len(sides)):
+            for l, (w, k) in enumerate(windows):
+                amskv.amskv_append_scale(h, l, s)
+                segs = amskv.amskv_cache_segments(h, l)
+                assert segs[-1] == (s, 0, -1, tokens[s])
+                assert _segment_ids(tokens, segs) == (want[l][s - 1] if s else [])
+                amskv.amskv_cache_settle(h, l)
+                assert _segment_ids(tokens, amskv.amskv_cache_segments(h, l), cached_only=False) == want[l][s]
+                assert amskv.amskv_cache_bytes_held(h, l, True) == 2 * 2 * B * H * D * len(want[l][s])
+                assert amskv.amskv_cache_budget_tokens(h, l) == w == amskv.amskv_cache_capacity_tokens(h, l)
+    finally:
+        amskv.amskv_cache_destroy(h)
+    # a window is one budget: two different ones are refused
+    with pytest.raises(amskv.AmskvError):
+        _two_budget_window(sides, B, H, D)
+
+
+def _two_budget_window(sides, B, H, D):
+    import ctypes as C
+    from paper_2511_16047_amd import binding as b
+    sc, po, keep = b._structs(sides, sides, B, amskv.AMSKV_DTYPE_BF16, None, 0.0, amskv.AMSKV_LAYOUT_COMPACT,
+                              budgets=[(3, 9, 0, 0.0)])
+    po.mode = amskv.AMSKV_MODE_TOKEN_WINDOW
+    out = C.c_uint64(0)
+    b._check(b.load_library().amskv_cache_required_bytes(1, H, D, C.byref(sc), C.byref(po), C.byref(out)), "required_bytes")
