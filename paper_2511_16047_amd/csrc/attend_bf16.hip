@@ -23,17 +23,19 @@
 //
 // Pipeline.  Block g's softmax runs on the vector ALUs, block g-1's O^T += V^T P^T on the matrix
 // cores; they share no data (the probabilities of g-1 were packed one iteration earlier), so
-// they sit in one basic block and the scheduler interleaves them.  The accumulator rescale that
-// a larger running max requires is applied after that, and only when some query of the wave
-// needs it: the running max may lag the true max by up to 2^kMaxLag.
+// they sit in one basic block and the scheduler interleaves them.  The softmax reference is lazy:
+// the probabilities of a block are formed against the reference the earlier blocks left, and only
+// when the sum of a lane's new probabilities shows that some score lay far above it (more than
+// 2^kMaxLag times) is the block's maximum taken, the reference moved and the block redone; the
+// accumulator rescale this requires is applied one step later.  The common block takes no maximum.
 //
 // Memory.  The kernel is HBM-bound at VAR shapes (arithmetic intensity T_q*T_kv/(T_q+T_kv)
 // flop/byte, below the chip's ridge), so the tile loop keeps tiles in flight (two at head dim 64):
 // global_load_lds_dwordx4 writes 64 lanes x 16 bytes straight into LDS with no register staging,
 // and the wave only waits (s_waitcnt vmcnt) for the tile it is about to use.  A direct-to-LDS load
-// puts lane i's 16 bytes at base + 16*i, so the XOR swizzle that keeps the 16-byte fragment reads
-// conflict-free (chunk ^= row & 7) is applied on the global side: the lane that fills LDS chunk
-// position c' of row r fetches global chunk c' ^ (r & 7).  Rows past the end of K~ re-read the
+// puts lane i's 16 bytes at base + 16*i, so the XOR swizzle that spreads the fragment reads over the
+// banks (chunk ^= swizzle(row)) is applied on the global side: the lane that fills LDS chunk
+// position c' of row r fetches global chunk c' ^ swizzle(r).  Rows past the end of K~ re-read the
 // last valid row (finite data) and their scores are set to -inf.  A borrowed current scale is the
 // tail of the virtual concatenation and its rows are fetched from the caller's K/V instead.
 // The ring holds tile t-1 (its last block's V is still being multiplied), t (in use) and the tiles in
@@ -53,6 +55,8 @@ constexpr int kSmallTq = 32;
 // the online softmax lets the running max lag by up to this many powers of two before the
 // accumulators are rescaled; probabilities then stay below 2^kMaxLag, far inside fp32/bf16 range
 constexpr float kMaxLag = 6.0f;
+// sum of a lane's 16 new probabilities above which the reference is looked at again: 16 * 2^kMaxLag
+constexpr float kTripSum = 1024.0f;
 
 #define AMSKV_LDS __attribute__((address_space(3)))
 
@@ -112,6 +116,18 @@ __device__ __forceinline__ float half_max(float x) {
   return fmaxf(__int_as_float(sw[0]), __int_as_float(sw[1]));
 }
 
+// XOR swizzle of a row's 16-byte chunks in LDS: chunk c of row `row` sits at chunk position c ^ swizzle(row).
+// Head dim 64 (8 chunks, two rows per 64 banks): the three low row bits.  Head dim 128 (16 chunks, a row
+// spans all banks): a permutation of the four low row bits -- row bits 1..0 move to chunk bits 2..1 and row
+// bit 2 to chunk bit 0, so that the four keys one 16-lane group of a transposing V read touches (keys k..k+3,
+// two chunks each) land in eight different chunks, and row bit 3 stays in place, which makes the 16 rows of a
+// quarter-wave K read hit 16 different chunks.  Measured on the fragment-read patterns of this kernel: the
+// (row & 7) form costs 1.15x (K) and 1.37x (V) the time of this one at head dim 128 and nothing at 64.
+template <int D>
+__device__ __forceinline__ constexpr int swizzle(int row) {
+  return D == 64 ? (row & 7) : (((row & 3) << 1) | ((row >> 2) & 1) | (row & 8));
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
@@ -152,7 +168,7 @@ struct TileLoader {
 #pragma unroll
     for (int i = 0; i < kLoadsPerWave; ++i) {
       const int row = (wave * kLoadsPerWave + i) * kRowsPerLoad + lane / CPR;  // row inside the tile
-      s.chunk[i] = 16u * ((lane % CPR) ^ (row & 7));
+      s.chunk[i] = 16u * ((lane % CPR) ^ swizzle<D>(row));
       s.row[i] = i * kRowsPerLoad + lane / CPR;
       s.voff[i] = 0;
     }
@@ -409,17 +425,20 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
   // lane-constant pieces of the fragment addresses
   const int tr_key = 4 * h + ((lane & 15) >> 2);               // + K-step base (+8 for the second read)
   const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);  // + 32*db
-  // V^T fragment of K-step u, read x: key = 16u + 8x + tr_key.  (key & 7) == (tr_key & 7), so the swizzle
-  // term does not depend on u or x and those two enter the address as compile-time offsets.
+  // V^T fragment of K-step u, read x: key = 16u + 8x + tr_key.  The swizzle of that key is the swizzle of tr_key
+  // (< 8), plus, at head dim 128, chunk bit 3 flipped when x = 1; u and x therefore enter the address as
+  // compile-time offsets: hi_off(d) is what x = 1 adds -- eight rows, and the flip of address bit 7, whose
+  // value before the flip is bit 6 of the column, i.e. known from d.
   int v_base[DB];
 #pragma unroll
   for (int d = 0; d < DB; ++d) {
     const int col = 32 * d + tr_col;
-    v_base[d] = tr_key * RB + 16 * ((col >> 3) ^ (tr_key & 7)) + 2 * (col & 7);
+    v_base[d] = tr_key * RB + 16 * ((col >> 3) ^ swizzle<D>(tr_key)) + 2 * (col & 7);
   }
+  auto hi_off = [](int d) { return 8 * RB + (D == 64 ? 0 : (d < 2 ? 128 : -128)); };
   int k_off[KS];  // K fragment byte offsets inside a 32-key block
 #pragma unroll
-  for (int t = 0; t < KS; ++t) k_off[t] = r * RB + 16 * ((2 * t + h) ^ (r & 7));
+  for (int t = 0; t < KS; ++t) k_off[t] = r * RB + 16 * ((2 * t + h) ^ swizzle<D>(r));
 
   // ring positions of the blocks a step touches: g-1 (V rows of the second product; first step: block 0
   // itself, multiplied by pf = 0), g, and g+1 (K prefetch)
@@ -485,51 +504,24 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
       }
     }
 
-    // ---- softmax reference of this block (vector ALU).  Lazy: the reference (kept multiplied by c) stays
-    // while no score of the block exceeds it by 2^kMaxLag or more.  Each lane tests the 16 keys it holds; only
-    // when some lane of the wave trips are the two lane halves combined and the reference moved.
-    float mine[NQ];
-    bool trip = false;
-#pragma unroll
-    for (int n = 0; n < NQ; ++n) {
-      settle_mfma(sacc[n]);
-      const float a0 = max3(sacc[n][0], sacc[n][1], sacc[n][2]), a1 = max3(sacc[n][3], sacc[n][4], sacc[n][5]);
-      const float a2 = max3(sacc[n][6], sacc[n][7], sacc[n][8]), a3 = max3(sacc[n][9], sacc[n][10], sacc[n][11]);
-      const float a4 = max3(sacc[n][12], sacc[n][13], sacc[n][14]);
-      const float b0 = max3(a0, a1, a2), b1 = max3(a3, a4, sacc[n][15]);
-      mine[n] = max3(b0, b1, b1);
-      // NaN (-inf against -inf: a lane whose keys are all past the end, first block) compares false
-      trip |= __builtin_amdgcn_ballot_w64(fmaf(mine[n], scale_log2e, -run_mc[n]) > kMaxLag) != 0;
-    }
-    any_rescale = trip;
-    if (__builtin_expect(trip, 0)) {
-#pragma unroll
-      for (int n = 0; n < NQ; ++n) {
-        const float full = half_max(mine[n]) * scale_log2e;  // finite: key 0 of the block is valid for every query
-        const float new_mc = full - run_mc[n] > kMaxLag ? full : run_mc[n];
-        alpha[n] = __builtin_amdgcn_exp2f(run_mc[n] - new_mc);  // 1 when unchanged, 0 on the first block
-        run_sum[n] *= alpha[n];
-        run_mc[n] = new_mc;
-      }
-    }
-
     // ---- probabilities of this block (vector ALU) next to O^T += V^T P^T of the previous block (matrix
     // cores), one K-step of 16 keys at a time: the matrix instructions of K-step u read the old pf[.][u] when
     // they issue, after which the new probabilities of keys 16u..16u+15 overwrite it.
     // p = 2^(s*c - m*c) in fp32; the row sum is taken over these, the second product uses them rounded to bf16.
+    // Lazy reference: m*c (run_mc) is NOT looked for first.  The probabilities are formed against the reference
+    // of the blocks before, and the sum of the lane's 16 new ones tells whether that was good enough: while it
+    // stays below kTripSum no score exceeded the reference by more than log2(kTripSum) powers of two, which is
+    // far inside the range of fp32 and bf16, and the block costs no maximum at all.
     float sum[NQ][2];
 #pragma unroll
-    for (int n = 0; n < NQ; ++n) {
-      sum[n][0] = run_sum[n];
-      sum[n][1] = 0.f;
-    }
+    for (int n = 0; n < NQ; ++n) sum[n][0] = sum[n][1] = 0.f;
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
 #pragma unroll
       for (int d = 0; d < DB; ++d) {
         const char* vp = lds_v + off_prev + v_base[d];
         const bf16x4 lo = lds_read_tr16(vp + (16 * u) * RB);
-        const bf16x4 hi = lds_read_tr16(vp + (16 * u + 8) * RB);
+        const bf16x4 hi = lds_read_tr16(vp + (16 * u) * RB + hi_off(d));
         bf16x8 a;
         a[0] = lo[0]; a[1] = lo[1]; a[2] = lo[2]; a[3] = lo[3];
         a[4] = hi[0]; a[5] = hi[1]; a[6] = hi[2]; a[7] = hi[3];
@@ -548,8 +540,47 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
           pf[n][u][(v & 7) + 1] = (__bf16)p1;
         }
     }
+    // ---- was the reference good enough?  (NaN -- a masked key against the initial reference of -inf -- and
+    // +inf -- anything against that reference -- both fail the comparison as written.)
+    bool trip = false;
 #pragma unroll
-    for (int n = 0; n < NQ; ++n) run_sum[n] = sum[n][0] + sum[n][1];
+    for (int n = 0; n < NQ; ++n) {
+      sum[n][0] += sum[n][1];
+      trip |= __builtin_amdgcn_ballot_w64(!(sum[n][0] <= kTripSum)) != 0;
+    }
+    any_rescale = trip;
+    if (__builtin_expect(trip, 0)) {
+      // Some query of the wave needs a new reference (always in the first block).  Now the maximum of the block
+      // is taken, per query over both lane halves; a query moves its reference to it only if it lies more than
+      // kMaxLag powers of two above the old one (every lane that tripped does: its largest probability
+      // exceeded kTripSum / 16 = 2^kMaxLag).  Then the block's probabilities are formed again.
+#pragma unroll
+      for (int n = 0; n < NQ; ++n) {
+        settle_mfma(sacc[n]);
+        const float a0 = max3(sacc[n][0], sacc[n][1], sacc[n][2]), a1 = max3(sacc[n][3], sacc[n][4], sacc[n][5]);
+        const float a2 = max3(sacc[n][6], sacc[n][7], sacc[n][8]), a3 = max3(sacc[n][9], sacc[n][10], sacc[n][11]);
+        const float a4 = max3(sacc[n][12], sacc[n][13], sacc[n][14]);
+        const float b0 = max3(a0, a1, a2), b1 = max3(a3, a4, sacc[n][15]);
+        const float full = half_max(max3(b0, b1, b1)) * scale_log2e;  // finite: key 0 of the block is valid for every query
+        const float new_mc = full - run_mc[n] > kMaxLag ? full : run_mc[n];
+        alpha[n] = __builtin_amdgcn_exp2f(run_mc[n] - new_mc);  // 1 when unchanged, 0 on the first block
+        run_sum[n] *= alpha[n];
+        run_mc[n] = new_mc;
+        float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; v += 2) {
+          const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[n][v], scale_log2e, -new_mc));
+          const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[n][v + 1], scale_log2e, -new_mc));
+          s0 += p0;
+          s1 += p1;
+          pf[n][v >> 3][v & 7] = (__bf16)p0;
+          pf[n][v >> 3][(v & 7) + 1] = (__bf16)p1;
+        }
+        sum[n][0] = s0 + s1;
+      }
+    }
+#pragma unroll
+    for (int n = 0; n < NQ; ++n) run_sum[n] += sum[n][0];
     off_prev = off_cur;
     off_cur = off_next;
     off_next = ring_next(off_next, kBlkBytes);
@@ -597,7 +628,7 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
       const bf16x4 lo = lds_read_tr16(vp + (16 * u) * RB);
-      const bf16x4 hi = lds_read_tr16(vp + (16 * u + 8) * RB);
+      const bf16x4 hi = lds_read_tr16(vp + (16 * u) * RB + hi_off(d));
       bf16x8 a;
       a[0] = lo[0]; a[1] = lo[1]; a[2] = lo[2]; a[3] = lo[3];
       a[4] = hi[0]; a[5] = hi[1]; a[6] = hi[2]; a[7] = hi[3];
