@@ -7,6 +7,7 @@
 // free or undefined behaviour in the metadata code stops a test run.
 #include <cstdio>
 #include <cstdlib>
+#include <algorithm>
 #include <vector>
 
 #include "amskv_internal.hpp"
@@ -148,6 +149,39 @@ static void walk_budget(const Sched& sc) {
   amskv_cache_destroy(h);
 }
 
+// Token windows (sliding window, sinks + window): one budget per layer, scales larger than it are cut.
+static void walk_token_window(const Sched& sc) {
+  const int n = (int)sc.sides.size();
+  std::vector<amskv_layer_budget> wins;
+  for (int w : {1, 5, 17, 60, 170, 700})
+    for (int sinks : {0, 1, 5, 30})
+      if (sinks <= w) wins.push_back({w, w, sinks, 0.f});
+  const int L = (int)wins.size(), B = 2, H = 2, D = 64;
+  amskv_schedule s{n, sc.sides.data(), sc.sides.data(), B, AMSKV_DTYPE_BF16};
+  amskv_policy p{L, nullptr, 0.f, AMSKV_LAYOUT_COMPACT, 0, 0, AMSKV_MODE_TOKEN_WINDOW, wins.data()};
+  amskv_cache* h = nullptr;
+  CHECK(amskv_cache_create(L, H, D, &s, &p, nullptr, 0, &h) == AMSKV_OK && h);
+  if (!h) return;
+  int64_t seen = 0;
+  for (int step = 0; step < n; ++step) {
+    seen += sc.sides[step] * sc.sides[step];
+    for (int l = 0; l < L; ++l) {
+      CHECK(amskv_append_scale(h, l, step, nullptr, nullptr, nullptr) == AMSKV_OK);
+      if ((step + l) % 2 == 0) CHECK(amskv_cache_settle(h, l, nullptr) == AMSKV_OK);
+      // a query finishes the iteration too: afterwards the layer holds min(seen, window) tokens
+      const int64_t want = std::min<int64_t>(seen, wins[l].c_max);
+      if ((step + l) % 2 == 0) CHECK(amskv_cache_bytes_held(h, l, 1) == 2 * 2 * (int64_t)B * H * D * want);
+    }
+  }
+  amskv_policy two = p;
+  amskv_layer_budget uneven{3, 9, 0, 0.f};
+  two.n_layers = 1;
+  two.budget = &uneven;
+  uint64_t need = 0;
+  CHECK(amskv_cache_required_bytes(1, H, D, &s, &two, &need) == AMSKV_ERR_INVALID_ARG);  // a window is one budget
+  amskv_cache_destroy(h);
+}
+
 static void bad_arguments() {
   const int32_t sides[3] = {1, 2, 3};
   amskv_layer_policy pol{1, 1, 0};
@@ -176,6 +210,7 @@ int main() {
       for (int borrow : {0, 1})
         for (int fuse : {0, 1}) walk_window(sc, layout, borrow, fuse);
     walk_budget(sc);
+    walk_token_window(sc);
   }
   bad_arguments();
   std::printf("host sanitizer driver: %d check(s) failed\n", failures);
