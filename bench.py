@@ -320,23 +320,26 @@ def standalone_append(amskv, torch, x, dev, pols):
 
 
 def density_probe(amskv, torch, x, res):
-    """The attention-density by-product (Section 4.1) of the last step, one call per layer."""
+    """The attention-density by-product (Section 4.1) of the last step: one enqueued call per layer, the masses of all
+    layers read back with one wait at the end."""
     w = x.w
     B, H, D, L = w.batch, w.heads, w.head_dim, w.layers
     S = len(w.tokens)
     cache = res["cache"]
+    outs = torch.empty(L, H * amskv.AMSKV_MAX_SCALES, dtype=torch.float32, device="cuda")
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    amskv.amskv_attention_density(cache, 0, S - 1, x.Qp[0][S - 1], H, stream=x.stream)   # warm-up
+    amskv.amskv_attention_density_enqueue(cache, 0, S - 1, x.Qp[0][S - 1], outs[0], x.stream)   # warm-up
     e0.record()
-    for l in range(L):
-        dl, _ = amskv.amskv_attention_density(cache, l, S - 1, x.Qp[l][S - 1], H, stream=x.stream)
+    lens = [amskv.amskv_attention_density_enqueue(cache, l, S - 1, x.Qp[l][S - 1], outs[l], x.stream) for l in range(L)]
     e1.record()
     torch.cuda.synchronize()
     d_ms = e0.elapsed_time(e1) / L
     d_fl = sum(2.0 * B * H * w.tokens[S - 1] * res["kv_len"][l][S - 1] * D for l in range(L)) / L
-    return {"what": "per-head softmax mass per cached token of each kept scale, last step, one call per layer "
-                    "(kernels + result copy + wait)", "ms_per_call": d_ms, "tflops_qk": d_fl / (d_ms * 1e-3) / 1e12,
-            "last_layer_head0_density_per_kept_scale": [round(v, 4) for v in dl[0]]}
+    last = outs[L - 1].cpu().numpy().reshape(H, amskv.AMSKV_MAX_SCALES)[0, : len(lens[-1])]
+    return {"what": "per-head softmax mass per cached token of each kept scale, last step, one enqueued call per layer "
+                    "(kernels + device-to-device result copy; one wait for all layers)", "ms_per_call": d_ms,
+            "tflops_qk": d_fl / (d_ms * 1e-3) / 1e12,
+            "last_layer_head0_density_per_kept_scale": [round(float(m) / n, 4) for m, n in zip(last, lens[-1])]}
 
 
 def workload_record(w, mode, layout_name, borrow, fuse, res):

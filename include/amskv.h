@@ -277,11 +277,21 @@ int32_t amskv_interscale_similarity_enqueue_static(amskv_cache* cache, int32_t l
  *   density_host  mass divided by the number of key tokens of the group: the printed definition
  *                 read with A^(j->i) holding one row per query of scale j and one column per key
  *                 of scale i (mass / T_s, the other reading, follows from mass_host)
- * bf16 caches only; at most AMSKV_MAX_SCALES groups; fp32 arithmetic on the exact bf16 products,
- * fixed reduction order (deterministic).  Reads Q, the cache and a borrowed scale; writes only its
- * workspace inside the arena.  Waits for `stream` before returning. */
+ * At most AMSKV_MAX_SCALES groups.  bf16 caches: matrix instructions, fp32 arithmetic on the exact
+ * bf16 products; fp32 caches: fp32 dot products on the vector ALUs.  Fixed reduction order
+ * (deterministic).  Reads Q, the cache and a borrowed scale; writes only its workspace inside the
+ * arena.  Waits for `stream` before returning. */
 int32_t amskv_attention_density(amskv_cache* cache, int32_t layer, int32_t s, const void* Q_dev,
                                 float* density_host, float* mass_host, int32_t* n_seg, void* stream);
+
+/* The same computation without the wait, for callers that analyse many layers: the masses
+ * (heads * AMSKV_MAX_SCALES floats, entry [h * AMSKV_MAX_SCALES + i]) are left in mass_out_dev, a
+ * caller-owned device buffer (16-byte aligned), in stream order; *n_seg and, if not NULL,
+ * tok_len[0 .. *n_seg) (the key tokens of each group: density = mass / tok_len) are host outputs
+ * valid on return.  The workspace inside the arena is shared by all layers: calls on one cache
+ * must be ordered on one stream. */
+int32_t amskv_attention_density_enqueue(amskv_cache* cache, int32_t layer, int32_t s, const void* Q_dev,
+                                        float* mass_out_dev, int32_t* n_seg, int32_t* tok_len, void* stream);
 
 /* Resident segments of a layer, ascending scale id: n_seg entries written to each
  * caller array of at least AMSKV_MAX_SCALES elements.  tok_offset is the position of the

@@ -36,6 +36,7 @@ EXPORTED = [
     "amskv_cache_bytes_held", "amskv_cache_capacity_tokens", "amskv_cache_export",
     "amskv_cache_reset", "amskv_cache_destroy", "amskv_status_string",
     "amskv_cache_segments", "amskv_cache_budget_tokens", "amskv_cache_settle", "amskv_attention_density",
+    "amskv_attention_density_enqueue",
     "amskv_cache_set_io_layout", "amskv_interscale_similarity_enqueue", "amskv_interscale_similarity_collect",
     "amskv_interscale_similarity_enqueue_static",
 ]
@@ -118,6 +119,8 @@ def load_library() -> C.CDLL:
     lib.amskv_cache_settle.restype = i32
     lib.amskv_attention_density.argtypes = [vp, i32, i32, vp, pf, pf, C.POINTER(i32), vp]
     lib.amskv_attention_density.restype = i32
+    lib.amskv_attention_density_enqueue.argtypes = [vp, i32, i32, vp, vp, C.POINTER(i32), C.POINTER(i32), vp]
+    lib.amskv_attention_density_enqueue.restype = i32
     lib.amskv_cache_set_io_layout.argtypes = [vp, i32, i64, i64, i64]
     lib.amskv_cache_set_io_layout.restype = i32
     lib.amskv_interscale_similarity_enqueue.argtypes = [vp, i32, i32, i32, vp]
@@ -239,6 +242,16 @@ def amskv_attention_density(cache, layer, s, Q, heads, stream=None):
            "amskv_attention_density")
     rows = lambda a: [[a[h * AMSKV_MAX_SCALES + i] for i in range(n.value)] for h in range(heads)]
     return rows(d), rows(m)
+
+
+def amskv_attention_density_enqueue(cache, layer, s, Q, mass_out, stream=None):
+    """mass_out: device float32 tensor of heads * AMSKV_MAX_SCALES elements, filled in stream order.
+    Returns the key-token count of every group (density = mass / count)."""
+    n = C.c_int32(0)
+    ln = (C.c_int32 * _MAX_SEGMENTS)()
+    _check(load_library().amskv_attention_density_enqueue(cache, layer, s, _ptr(Q), _ptr(mass_out), C.byref(n), ln,
+                                                          _stream(stream)), "amskv_attention_density_enqueue")
+    return [int(ln[i]) for i in range(n.value)]
 
 
 def amskv_interscale_similarity_enqueue(cache, layer, s, want_v=True, stream=None):

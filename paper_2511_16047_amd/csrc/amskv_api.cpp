@@ -884,11 +884,11 @@ int32_t amskv_interscale_similarity_collect(amskv_cache* c, float* cosK_host, fl
   return AMSKV_OK;
 }
 
-int32_t amskv_attention_density(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev, float* density_host,
-                                float* mass_host, int32_t* n_seg, void* stream) {
-  if (bad_layer(c, layer) || s < 0 || s >= c->n_scales || !Q_dev || misaligned(Q_dev) || (!density_host && !mass_host))
-    return AMSKV_ERR_INVALID_ARG;
-  if (c->dtype != AMSKV_DTYPE_BF16) return AMSKV_ERR_INVALID_ARG;
+// Checks and launch shared by the two forms of the density call; the per-head masses end up at *totals (device,
+// inside the arena's workspace) and *table describes the groups.
+static int density_launch(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev, hipStream_t st, SegTable* table,
+                          float** totals) {
+  if (bad_layer(c, layer) || s < 0 || s >= c->n_scales || !Q_dev || misaligned(Q_dev)) return AMSKV_ERR_INVALID_ARG;
   if (int rc = finish_iteration(c, layer)) return rc;
   LayerState& L = c->layer[layer];
   if (s != L.last_scale) return AMSKV_ERR_ORDER;
@@ -901,15 +901,26 @@ int32_t amskv_attention_density(amskv_cache* c, int32_t layer, int32_t s, const 
   const int64_t n_qblk = (c->tokens[s] + 31) / 32;
   if ((int64_t)c->batch * c->heads * n_qblk > INT32_MAX) return AMSKV_ERR_INVALID_ARG;
   float* partial = (float*)(c->arena + c->dens_off);
-  float* totals = partial + (uint64_t)c->batch * c->heads * n_qblk * AMSKV_MAX_SCALES;
-  hipStream_t st = (hipStream_t)stream;
+  *totals = partial + (uint64_t)c->batch * c->heads * n_qblk * AMSKV_MAX_SCALES;
   const CallerIo io{caller_map(c, c->tokens[s], c->q_tok), RowMap{0, 0, 0}, caller_map(c, L.segs.back().len, c->kv_tok),
                     c->heads};
-  hipError_t e = amskv::launch_density(Q_dev, c->arena + L.k_off, c->batch, c->heads, c->tokens[s], c->head_dim, L.cap,
-                                       t, ext, io, c->softmax_scale, partial, totals, st);
+  hipError_t e = amskv::launch_density(Q_dev, c->arena + L.k_off, c->batch, c->heads, c->tokens[s], c->head_dim, c->dtype,
+                                       L.cap, t, ext, io, c->softmax_scale, partial, *totals, st);
   if (e != hipSuccess) return AMSKV_ERR_HIP;
+  *table = t;
+  return AMSKV_OK;
+}
+
+int32_t amskv_attention_density(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev, float* density_host,
+                                float* mass_host, int32_t* n_seg, void* stream) {
+  if (!density_host && !mass_host) return AMSKV_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  SegTable t;
+  float* totals = nullptr;
+  int rc = density_launch(c, layer, s, Q_dev, st, &t, &totals);
+  if (rc) return rc;
   std::vector<float> host((size_t)c->heads * AMSKV_MAX_SCALES);
-  e = hipMemcpyAsync(host.data(), totals, host.size() * sizeof(float), hipMemcpyDeviceToHost, st);
+  hipError_t e = hipMemcpyAsync(host.data(), totals, host.size() * sizeof(float), hipMemcpyDeviceToHost, st);
   if (e != hipSuccess) return AMSKV_ERR_HIP;
   e = hipStreamSynchronize(st);
   if (e != hipSuccess) return AMSKV_ERR_HIP;
@@ -920,6 +931,23 @@ int32_t amskv_attention_density(amskv_cache* c, int32_t layer, int32_t s, const 
       if (density_host) density_host[h * AMSKV_MAX_SCALES + p] = m / (float)t.len[p];
     }
   if (n_seg) *n_seg = t.n;
+  return AMSKV_OK;
+}
+
+int32_t amskv_attention_density_enqueue(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev, float* mass_out_dev,
+                                        int32_t* n_seg, int32_t* tok_len, void* stream) {
+  if (!mass_out_dev || misaligned(mass_out_dev) || !n_seg) return AMSKV_ERR_INVALID_ARG;
+  hipStream_t st = (hipStream_t)stream;
+  SegTable t;
+  float* totals = nullptr;
+  int rc = density_launch(c, layer, s, Q_dev, st, &t, &totals);
+  if (rc) return rc;
+  if (hipMemcpyAsync(mass_out_dev, totals, (size_t)c->heads * AMSKV_MAX_SCALES * sizeof(float), hipMemcpyDeviceToDevice,
+                     st) != hipSuccess)
+    return AMSKV_ERR_HIP;
+  *n_seg = t.n;
+  if (tok_len)
+    for (int p = 0; p < t.n; ++p) tok_len[p] = t.len[p];
   return AMSKV_OK;
 }
 

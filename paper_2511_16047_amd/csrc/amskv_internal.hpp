@@ -133,8 +133,8 @@ hipError_t launch_similarity_static(const ScaleRef& cur, const ScaleRef& prev, i
                                     float* out_dev, hipStream_t st);
 
 // attention density: pieces = one table entry per group of keys (nothing merged); partial_ws holds
-// batch*heads*ceil(t_q/32)*AMSKV_MAX_SCALES floats, out_dev heads*AMSKV_MAX_SCALES floats; bf16 only
-hipError_t launch_density(const void* q, const void* kc, int batch, int heads, int t_q, int head_dim,
+// batch*heads*ceil(t_q/32)*AMSKV_MAX_SCALES floats, out_dev heads*AMSKV_MAX_SCALES floats
+hipError_t launch_density(const void* q, const void* kc, int batch, int heads, int t_q, int head_dim, int dtype,
                           int64_t cap_tokens, const SegTable& pieces, const ExtKV& ext, const CallerIo& io,
                           float softmax_scale, float* partial_ws, float* out_dev, hipStream_t st);
 

@@ -100,6 +100,82 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void density_partial_kernel(
   }
 }
 
+// The same quantity for fp32 caches, on the vector ALUs (the fp32 path is the reference-precision path, not a
+// tuned one): same units, same parking scheme, so workspace and second kernel are shared.  A lane keeps its
+// query row in registers and takes every second key of a group (keys j = h mod 2); K rows are read as
+// 16-byte chunks that all lanes of a half share.  Each lane runs its own online softmax; the two halves of
+// a query meet only at the end.
+template <int D>
+__global__ __launch_bounds__(64 * kWavesPerGroup) void density_partial_f32_kernel(
+    const float* __restrict__ q, const char* __restrict__ kc, int t_q, long long cap_tokens, SegTable seg,
+    ExtKV ext_kv, CallerIo io, float scale_log2e, int n_qblk, int n_units, float* __restrict__ partial) {
+  constexpr int RB = D * 4;
+  __shared__ float park_sum[kWavesPerGroup][AMSKV_MAX_SCALES][64];
+  __shared__ float park_max[kWavesPerGroup][AMSKV_MAX_SCALES][64];
+
+  const int wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int unit = blockIdx.x * kWavesPerGroup + wave;
+  if (unit >= n_units) return;
+  const int r = lane & 31, h = lane >> 5;
+  const long long bh = unit / n_qblk;
+  const int q_base = (unit % n_qblk) * 32;
+  const char* kb = kc + bh * cap_tokens * RB;
+  const char* xk = (const char*)ext_kv.k + unit_offset(io.kv, bh, io.heads);
+  const char* q_unit = (const char*)q + unit_offset(io.q, bh, io.heads);
+
+  float4 qr[D / 4];
+  {
+    const int row = min(q_base + r, t_q - 1);
+#pragma unroll
+    for (int d = 0; d < D / 4; ++d) qr[d] = *reinterpret_cast<const float4*>(q_unit + row * io.q.tok + 16 * d);
+  }
+
+  float run_max = -INFINITY;  // of the keys this lane has seen
+  for (int p = 0; p < seg.n; ++p) {
+    const int len = seg.len[p];
+    const int vs = seg.virt_start[p];
+    const bool outside = vs >= seg.ext_start;
+    const long long tok = outside ? io.kv.tok : (long long)RB;
+    const char* base = outside ? xk + (vs - seg.ext_start) * tok : kb + (long long)seg.phys_off[p] * RB;
+    float ssum = 0.f;
+    for (int j = h; j < len; j += 2) {
+      const float4* kp = reinterpret_cast<const float4*>(base + j * tok);
+      float dot = 0.f;
+#pragma unroll
+      for (int d = 0; d < D / 4; ++d) {
+        const float4 kk = kp[d];
+        dot = fmaf(qr[d].x, kk.x, dot);
+        dot = fmaf(qr[d].y, kk.y, dot);
+        dot = fmaf(qr[d].z, kk.z, dot);
+        dot = fmaf(qr[d].w, kk.w, dot);
+      }
+      const float new_max = fmaxf(run_max, dot);
+      ssum = ssum * __builtin_amdgcn_exp2f((run_max - new_max) * scale_log2e) +
+             __builtin_amdgcn_exp2f((dot - new_max) * scale_log2e);
+      run_max = new_max;
+    }
+    park_sum[wave][p][lane] = ssum;  // 0 with a maximum of -inf while this half has seen no key
+    park_max[wave][p][lane] = run_max;
+  }
+
+  const float top = fmaxf(run_max, __shfl_xor(run_max, 32, 64));  // finite: key 0 belongs to half 0
+  float total = 0.f;
+  for (int p = 0; p < seg.n; ++p) {
+    float w = park_sum[wave][p][lane] * __builtin_amdgcn_exp2f((park_max[wave][p][lane] - top) * scale_log2e);
+    w += __shfl_xor(w, 32, 64);
+    park_sum[wave][p][lane] = w;
+    total += w;
+  }
+  const float inv = q_base + r < t_q ? 1.0f / total : 0.f;
+  for (int p = 0; p < seg.n; ++p) {
+    float m = park_sum[wave][p][lane] * inv;
+#pragma unroll
+    for (int d = 16; d >= 1; d >>= 1) m += __shfl_xor(m, d, 64);
+    if (lane == 0) partial[(long long)unit * AMSKV_MAX_SCALES + p] = m;
+  }
+}
+
 // out[h][p] = (1/B) * sum over batch and query blocks of partial[(b,h), block][p], fixed order:
 // thread = p + 16*part walks every kParts-th unit of the head, then a tree over the parts in LDS.
 constexpr int kParts = 16;
@@ -128,14 +204,20 @@ __global__ __launch_bounds__(16 * kParts) void density_total_kernel(const float*
 
 }  // namespace
 
-hipError_t launch_density(const void* q, const void* kc, int batch, int heads, int t_q, int head_dim,
+hipError_t launch_density(const void* q, const void* kc, int batch, int heads, int t_q, int head_dim, int dtype,
                           int64_t cap_tokens, const SegTable& pieces, const ExtKV& ext, const CallerIo& io,
                           float softmax_scale, float* partial_ws, float* out_dev, hipStream_t st) {
   const float c = softmax_scale * 1.4426950408889634f;
   const int n_qblk = (t_q + 31) / 32;
   const long long n_units = (long long)batch * heads * n_qblk;
   dim3 grid((unsigned)((n_units + kWavesPerGroup - 1) / kWavesPerGroup)), block(64 * kWavesPerGroup);
-  if (head_dim == 64)
+  if (dtype == AMSKV_DTYPE_F32 && head_dim == 64)
+    hipLaunchKernelGGL(density_partial_f32_kernel<64>, grid, block, 0, st, (const float*)q, (const char*)kc, t_q,
+                       (long long)cap_tokens, pieces, ext, io, c, n_qblk, (int)n_units, partial_ws);
+  else if (dtype == AMSKV_DTYPE_F32)
+    hipLaunchKernelGGL(density_partial_f32_kernel<128>, grid, block, 0, st, (const float*)q, (const char*)kc, t_q,
+                       (long long)cap_tokens, pieces, ext, io, c, n_qblk, (int)n_units, partial_ws);
+  else if (head_dim == 64)
     hipLaunchKernelGGL(density_partial_kernel<64>, grid, block, 0, st, (const __bf16*)q, (const char*)kc, t_q,
                        (long long)cap_tokens, pieces, ext, io, c, n_qblk, (int)n_units, partial_ws);
   else

@@ -29,7 +29,7 @@ hipError_t launch_similarity(const ScaleRef&, const ScaleRef&, int, int, int, in
                              hipStream_t) { std::abort(); }
 hipError_t launch_similarity_static(const ScaleRef&, const ScaleRef&, int, int, int, int, int, int, int, int, float*,
                                     hipStream_t) { std::abort(); }
-hipError_t launch_density(const void*, const void*, int, int, int, int, int64_t, const SegTable&, const ExtKV&,
+hipError_t launch_density(const void*, const void*, int, int, int, int, int, int64_t, const SegTable&, const ExtKV&,
                           const CallerIo&, float, float*, float*, hipStream_t) { std::abort(); }
 }  // namespace amskv
 extern "C" hipError_t hipMemcpyAsync(void*, const void*, size_t, hipMemcpyKind, hipStream_t) { std::abort(); }

@@ -1,5 +1,6 @@
-"""GPU parity of the attention density (Section 4.1) against the oracle: fp32 arithmetic on exact bf16
-products versus fp64, so mass and density agree to rtol 2e-4 / atol 1e-5; the group list is bit-exact."""
+"""GPU parity of the attention density (Section 4.1) against the oracle: fp32 arithmetic (on exact bf16
+products, or fp32 dot products for fp32 caches) versus fp64, so mass and density agree to rtol 2e-4 / atol 1e-5;
+the group list is bit-exact."""
 import numpy as np
 import pytest
 import torch
@@ -146,16 +147,15 @@ def test_density_uniform_queries_and_errors():
         assert e.value.status == amskv.AMSKV_ERR_ORDER
     finally:
         amskv.amskv_cache_destroy(h)
-    # fp32 caches are not covered
+    # an fp32 cache with one cached token: all of the single query's mass lands on it
     need = amskv.amskv_cache_required_bytes(1, H, D, (1, 2), (1, 2), B, amskv.AMSKV_DTYPE_F32, [pol])
     arena = torch.empty(need, dtype=torch.uint8, device="cuda")
     h = amskv.amskv_cache_create(1, H, D, (1, 2), (1, 2), B, amskv.AMSKV_DTYPE_F32, [pol], arena=arena)
     try:
         x = torch.zeros(B, H, 1, D, device="cuda")
         amskv.amskv_append_scale(h, 0, 0, x, x)
-        with pytest.raises(amskv.AmskvError) as e:
-            amskv.amskv_attention_density(h, 0, 0, x, H)
-        assert e.value.status == amskv.AMSKV_ERR_INVALID_ARG
+        dens, mass = amskv.amskv_attention_density(h, 0, 0, x, H)
+        assert np.array_equal(np.asarray(mass), np.ones((H, 1))) and np.array_equal(np.asarray(dens), np.ones((H, 1)))
     finally:
         amskv.amskv_cache_destroy(h)
 
@@ -195,5 +195,61 @@ def test_density_full_batch_launch_configuration():
         assert np.allclose(np.asarray(got_m), want_m, rtol=2e-4, atol=1e-5)
         assert np.allclose(np.asarray(got_d), want_d, rtol=2e-4, atol=1e-5)
         assert np.allclose(np.asarray(got_m).sum(axis=-1), tokens[s], rtol=1e-4)
+    finally:
+        amskv.amskv_cache_destroy(h)
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_density_fp32_cache(D):
+    """fp32 caches: dot products on the vector ALUs in fp32 against the oracle's fp64, odd group lengths (a lane
+    half that sees no key of a group, a one-token first scale), borrowed final scale, ragged query count."""
+    F32 = amskv.AMSKV_DTYPE_F32
+    sides = (1, 2, 3, 5, 7)
+    tokens = [x * x for x in sides]
+    B, H = 2, 2
+    pols = [(1, 1, False), (0, 0, True)]
+    q, k, v = inp.correlated_qkv(sides, B, H, D, "f32", inp.layer_seed(8, 300 + D), 0.6)
+    k_all = np.concatenate([_f64(x) for x in k], axis=-2)
+    qd, kd, vd = ([x.cuda() for x in t] for t in (q, k, v))
+    need = amskv.amskv_cache_required_bytes(len(pols), H, D, sides, sides, B, F32, pols, 0.0, amskv.AMSKV_LAYOUT_COMPACT, True)
+    arena = torch.empty(need, dtype=torch.uint8, device="cuda")
+    arena.fill_(0xFF)
+    h = amskv.amskv_cache_create(len(pols), H, D, sides, sides, B, F32, pols, 0.0, amskv.AMSKV_LAYOUT_COMPACT, arena=arena,
+                                 borrow_unretained=True)
+    try:
+        for s in range(len(sides)):
+            for l, pol in enumerate(pols):
+                amskv.amskv_append_scale(h, l, s, kd[s], vd[s])
+                pieces, rows = _window_view(tokens, pol, s)
+                _check(h, l, s, tokens, qd[s], k_all, H, pieces, rows)
+    finally:
+        amskv.amskv_cache_destroy(h)
+
+
+def test_density_enqueue_matches_the_waiting_call():
+    """The form without a wait leaves the same bits in the caller's device buffer, layer after layer on one stream."""
+    B, H, D = 2, 3, 64
+    tokens = [x * x for x in VAR]
+    pols = [(2, 2, False), (0, 0, True)]
+    q, k, v = inp.correlated_qkv(VAR, B, H, D, "bf16", inp.layer_seed(8, 77), 0.7)
+    qd, kd, vd = ([x.cuda() for x in t] for t in (q, k, v))
+    need = amskv.amskv_cache_required_bytes(len(pols), H, D, VAR, VAR, B, BF16, pols)
+    arena = torch.empty(need, dtype=torch.uint8, device="cuda")
+    h = amskv.amskv_cache_create(len(pols), H, D, VAR, VAR, B, BF16, pols, arena=arena)
+    try:
+        for s in range(len(VAR)):
+            for l in range(len(pols)):
+                amskv.amskv_append_scale(h, l, s, kd[s], vd[s])
+        s = len(VAR) - 1
+        outs = [torch.full((H * amskv.AMSKV_MAX_SCALES,), float("nan"), dtype=torch.float32, device="cuda") for _ in pols]
+        lens = [amskv.amskv_attention_density_enqueue(h, l, s, qd[s], outs[l]) for l in range(len(pols))]
+        torch.cuda.synchronize()
+        for l, pol in enumerate(pols):
+            assert lens[l] == [tokens[kk] for kk in orc.kept_scales(pol, s)]
+            _, want_m = amskv.amskv_attention_density(h, l, s, qd[s], H)
+            got = outs[l].cpu().numpy().reshape(H, amskv.AMSKV_MAX_SCALES)[:, : len(lens[l])]
+            assert np.array_equal(got, np.asarray(want_m, dtype=np.float32))
+        with pytest.raises(amskv.AmskvError):
+            amskv.amskv_attention_density_enqueue(h, 0, s, qd[s], None)
     finally:
         amskv.amskv_cache_destroy(h)
