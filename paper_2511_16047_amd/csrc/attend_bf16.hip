@@ -333,9 +333,13 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
   // fused append: the workgroup of the first query tile also fills the current scale's slot
   const bool write_back = ext_kv.wb_off >= 0 && q_tile == 0;
 
-  // ---- prologue: fill the whole ring (the steady state keeps kAhead tiles in flight; at the start nothing is
-  // in use yet, and the first tiles are what the workgroup waits for), then the Q fragments with ordinary
-  // loads; everything is in flight together, and the Q values are settled once, before the tile loop.
+  // ---- prologue.  What the first matrix instruction waits for is kept small: the wave's own Q rows and tile 0.
+  // Q goes through LDS like the tiles (direct-to-LDS loads, so every wait below is an explicit count and the
+  // first block does not wait for younger tile loads, as it would behind compiler-tracked register loads): each
+  // wave fetches its 32*NQ rows into a private piece of the last two ring slots, which the tile stream reaches
+  // only after the first barriers, and reads its fragments from there once.  Then kAhead tiles are requested;
+  // from the first barrier on the steady rule applies: the barrier of tile `it` frees the slot of tile it-2, and
+  // tile it+kAhead is requested into it.
   typename Loader::Stream stream;
   Loader::init(stream, wave, lane);
   // ring positions (byte offsets, the same in the K and the V ring), all wave-uniform
@@ -345,46 +349,60 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
     off += by;
     return off == kRing ? 0 : off;
   };
+  constexpr int kQBytes = 32 * NQ * RB;   // Q rows of one wave
+  constexpr int kQLoads = kQBytes / 1024;
+  constexpr int CPR = Loader::CPR;
+  static_assert(kWaves % 2 == 0 && (kWaves / 2) * kQBytes <= 2 * kTileBytes, "Q staging fits the last two slots of each ring");
+  char* q_stage = (wave < kWaves / 2 ? lds_k : lds_v) + (kStages - 2) * kTileBytes + (wave % (kWaves / 2)) * kQBytes;
+  if (wave_active) {
+    // lane i of load j fills chunk position i % CPR of row j * (64 / CPR) + i / CPR; rows past T_q re-read the
+    // last row (their results are never stored); same swizzle as the tiles
+    const char* q_unit = (const char*)q + unit_offset(io.q, bh, io.heads);
 #pragma unroll
-  for (int st = 0; st < kStages; ++st)
+    for (int j = 0; j < kQLoads; ++j) {
+      const int row = j * (64 / CPR) + lane / CPR;
+      const long long at = (long long)min(q_base + row, t_q - 1) * io.q.tok + 16 * ((lane % CPR) ^ swizzle<D>(row));
+      lds_dma16(q_unit + at, q_stage + j * 1024);
+    }
+  }
+#pragma unroll
+  for (int st = 0; st < kAhead; ++st)
     if (st < n_tiles) {
       Loader::issue(stream, kb, vb, xk, xv, x_tok, lds_k + fetch_off, lds_v + fetch_off, t_kv, seg, wave, lane);
       fetch_off = ring_next(fetch_off, kTileBytes);
     }
-  // Q fragments: B operand of S^T = K Q^T; lane (r,h) holds Q[row r][16t + 8h .. +8).  Query rows
-  // past T_q re-read the last row; their results are never stored.
-  const char* q_unit = (const char*)q + unit_offset(io.q, bh, io.heads);
+  // Q fragments: B operand of S^T = K Q^T; lane (r,h) holds Q[row r][16t + 8h .. +8)
   bf16x8 qf[NQ][KS];
+  if (wave_active) {
+    if (kAhead == 2 && n_tiles >= 2) wait_vmcnt<2 * VM>();  // the Q loads are the oldest: everything but the tiles has landed
+    else wait_vmcnt<VM>();
 #pragma unroll
-  for (int n = 0; n < NQ; ++n) {
-    const int row = min(q_base + 32 * n + r, t_q - 1);
+    for (int n = 0; n < NQ; ++n)
 #pragma unroll
-    for (int t = 0; t < KS; ++t) qf[n][t] = *reinterpret_cast<const bf16x8*>(q_unit + row * io.q.tok + 32 * t + 16 * h);
+      for (int t = 0; t < KS; ++t) {
+        qf[n][t] = *reinterpret_cast<const bf16x8*>(q_stage + (32 * n + r) * RB + 16 * ((2 * t + h) ^ swizzle<D>(32 * n + r)));
+        settle(qf[n][t]);  // read before the barrier behind which other waves may request tiles into this piece
+      }
   }
 
   // Tile `it` becomes readable: this wave's loads of it have landed (younger tiles may stay in flight), the
-  // barrier extends that to every wave's part, and it also retires the oldest ring slot, which the next tile
-  // to fetch goes into.  Called for it = 0, 1, ... by every wave of the workgroup.
-  // Fetch schedule: tiles 0..kStages-1 are requested in the prologue; from it = 2 on (the first barrier that
-  // retires a slot) tile it+kAhead is requested here, so it+1 .. it+kAhead are in flight behind the barrier.
-  // steady: the caller knows that it >= 2 and that tile it+kAhead exists (nothing to test on the common path).
+  // barrier extends that to every wave's part, and it also retires the slot of tile it-2, which tile it+kAhead
+  // is requested into.  Called for it = 0, 1, ... by every wave of the workgroup.
+  // steady: the caller knows that tile it+kAhead exists (nothing to test on the common path).
   auto tile_sync = [&](int it, auto steady) {
     constexpr bool kSteady = decltype(steady)::value;
     if (kSteady) {
       wait_vmcnt<VM*(kAhead - 1)>();
     } else {
-      // tiles requested so far, minus those up to `it`, may stay in flight
-      const int ahead = min(n_tiles, max(kStages, it + kAhead)) - (it + 1);
-      if (ahead >= 3 && kStages >= 4) wait_vmcnt<VM * 3>();
-      else if (ahead == 2) wait_vmcnt<VM * 2>();
-      else if (ahead == 1) wait_vmcnt<VM>();
+      // tiles requested so far beyond `it` may stay in flight
+      if (kAhead == 2 && it + 1 < n_tiles) wait_vmcnt<VM>();
       else wait_vmcnt<0>();
     }
     __syncthreads();
     if (write_back && (it + 1) * kTileKeys > seg.ext_start)
       Loader::write_back(stream, kb, vb, lds_k + sync_off, lds_v + sync_off, it * kTileKeys, t_kv, seg, ext_kv.wb_off, wave, lane);
     sync_off = ring_next(sync_off, kTileBytes);
-    if (kSteady || (it >= 2 && it + kAhead < n_tiles)) {
+    if (kSteady || it + kAhead < n_tiles) {
       Loader::issue(stream, kb, vb, xk, xv, x_tok, lds_k + fetch_off, lds_v + fetch_off, t_kv, seg, wave, lane);
       fetch_off = ring_next(fetch_off, kTileBytes);
     }
@@ -397,11 +415,6 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
     for (int it = 1; it < n_tiles; ++it) tile_sync(it, no);
     return;
   }
-
-#pragma unroll
-  for (int n = 0; n < NQ; ++n)
-#pragma unroll
-    for (int t = 0; t < KS; ++t) settle(qf[n][t]);
 
   f32x16 oacc[NQ][DB];
 #pragma unroll
@@ -588,14 +601,9 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
 
   const bool ragged = (t_kv & 31) != 0;
   if (kPrefetchK) {
-    // two blocks per tile.  First the tiles whose barrier has nothing to test (the tile it fetches exists),
+    // two blocks per tile.  First the tiles whose barrier has nothing to test (the tile it requests exists),
     // then the ones near the end of the stream, then the last tile (1 or 2 blocks).
     int it = 0;
-    if (n_tiles > 1) {  // the barrier of tile 1 belongs to the start-up schedule
-      block_step(no, no, yes, false);
-      block_step(yes, no, yes, false);
-      it = 1;
-    }
     for (; it + 1 + kAhead < n_tiles; ++it) {
       block_step(no, no, yes, false);
       block_step(yes, yes, yes, false);
