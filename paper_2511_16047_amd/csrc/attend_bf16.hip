@@ -374,7 +374,9 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
   // Q fragments: B operand of S^T = K Q^T; lane (r,h) holds Q[row r][16t + 8h .. +8)
   bf16x8 qf[NQ][KS];
   if (wave_active) {
-    if (kAhead == 2 && n_tiles >= 2) wait_vmcnt<2 * VM>();  // the Q loads are the oldest: everything but the tiles has landed
+    // the Q loads are the oldest: once no more than the tile loads are outstanding, Q has landed
+    if (kAhead >= 3 && n_tiles >= 3) wait_vmcnt<3 * VM>();
+    else if (kAhead >= 2 && n_tiles >= 2) wait_vmcnt<2 * VM>();
     else wait_vmcnt<VM>();
 #pragma unroll
     for (int n = 0; n < NQ; ++n)
@@ -394,8 +396,10 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
     if (kSteady) {
       wait_vmcnt<VM*(kAhead - 1)>();
     } else {
-      // tiles requested so far beyond `it` may stay in flight
-      if (kAhead == 2 && it + 1 < n_tiles) wait_vmcnt<VM>();
+      // tiles requested so far beyond `it` may stay in flight: min(n_tiles - it - 1, kAhead - 1) of them
+      const int ahead = min(n_tiles - it - 1, kAhead - 1);
+      if (kAhead >= 3 && ahead == 2) wait_vmcnt<2 * VM>();
+      else if (kAhead >= 2 && ahead == 1) wait_vmcnt<VM>();
       else wait_vmcnt<0>();
     }
     __syncthreads();
