@@ -9,9 +9,9 @@
 // V~ stream from HBM once per tile.  Each wave owns 32*NQ query rows and keeps their Q fragments
 // in registers for the whole kernel.  Per 32-key block it computes the TRANSPOSED score block
 // S^T = K Q^T (M = keys, N = queries): in the 32x32 accumulator layout every lane then holds 16
-// keys of ONE query (column = lane%32), so the row max / row sum of the softmax are in-lane
-// reductions plus a single exchange between the two lane halves, and the probabilities are
-// already in the register layout the second product needs as its B operand:
+// keys of ONE query (column = lane%32), so the row sum (and, when it is needed, the row max) of
+// the softmax are in-lane reductions plus a single exchange between the two lane halves, and the
+// probabilities are already in the register layout the second product needs as its B operand:
 // O^T += V^T P^T (M = head dim, K = keys, N = queries).  P never touches LDS.
 //
 // The accumulator row held in slot v of lane l is 8*(v/4) + 4*(l/32) + v%4, so the 8 values a
@@ -39,7 +39,9 @@
 // last valid row (finite data) and their scores are set to -inf.  A borrowed current scale is the
 // tail of the virtual concatenation and its rows are fetched from the caller's K/V instead.
 // The ring holds tile t-1 (its last block's V is still being multiplied), t (in use) and the tiles in
-// flight: t+1 and t+2 at head dim 64, t+1 alone at head dim 128 (see kAhead).
+// flight: t+1 and t+2 at head dim 64, t+1 alone at head dim 128 (see kAhead).  The query rows take the
+// same road once, at the start: direct-to-LDS loads into a piece of the ring no tile has reached yet,
+// then one read of the fragments into registers, so that every wait in the kernel is an explicit count.
 #include "amskv_internal.hpp"
 
 namespace amskv {
