@@ -158,16 +158,13 @@ int64_t compact_capacity(const amskv_layer_policy& p, const int32_t* tokens, int
 
 // PLANNED layout: the schedule and the policy fix, at create time, the interval of steps
 // [k, last_k] during which scale k is resident.  Give every stored scale a slot such that
-// scales with overlapping lifetimes never overlap in memory (largest scale first, lowest free
-// offset), so eviction needs no data movement at all.  Returns the capacity reached.
-int64_t plan_slots(const amskv_layer_policy& p, const int32_t* tokens, int n_scales, bool borrow,
-                   int32_t* off_out) {
-  std::vector<int> order;
-  for (int i = 0; i < n_scales; ++i) {
-    off_out[i] = -1;
-    if (stored(p, i, n_scales, borrow)) order.push_back(i);
-  }
-  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return tokens[a] > tokens[b]; });
+// scales with overlapping lifetimes never overlap in memory, so eviction needs no data movement
+// at all.  plan_slots returns the capacity reached.
+// One first-fit placement: the stored scales are taken in `order`, each at the lowest offset that is free over its
+// whole residency interval.
+int64_t place_slots(const amskv_layer_policy& p, const int32_t* tokens, int n_scales, const std::vector<int>& order,
+                    int32_t* off_out) {
+  for (int i = 0; i < n_scales; ++i) off_out[i] = -1;
   std::vector<char> placed(n_scales, 0);
   int64_t cap = 0;
   for (int k : order) {
@@ -189,6 +186,57 @@ int64_t plan_slots(const amskv_layer_policy& p, const int32_t* tokens, int n_sca
     cap = std::max(cap, at + tokens[k]);
   }
   return cap;
+}
+
+// How broken up the kept scales are under a placement: over all steps, the number of physically separate runs
+// the queries of the step stream (kept scales in ascending order, neighbours merged when they touch), weighted by
+// the step's query count.
+int64_t placement_cost(const amskv_layer_policy& p, const int32_t* tokens, int n_scales, const int32_t* off) {
+  int64_t cost = 0;
+  for (int s = 0; s < n_scales; ++s) {
+    int runs = 0;
+    int64_t end = -1;
+    for (int k = 0; k <= s; ++k) {
+      if (!resident(p, s, k)) continue;
+      if (off[k] < 0 || off[k] != end) ++runs;  // a scale read in place is a run of its own
+      end = off[k] < 0 ? -1 : (int64_t)off[k] + tokens[k];
+    }
+    cost += (int64_t)runs * tokens[s];
+  }
+  return cost;
+}
+
+int64_t plan_slots(const amskv_layer_policy& p, const int32_t* tokens, int n_scales, bool borrow,
+                   int32_t* off_out) {
+  std::vector<int> stored_scales;
+  for (int i = 0; i < n_scales; ++i)
+    if (stored(p, i, n_scales, borrow)) stored_scales.push_back(i);
+  // Candidate orders for the first-fit placement.  Largest first packs windows of unequal scales tightest.
+  // Ascending puts scales back to back wherever lifetimes allow (a layer that keeps everything becomes one
+  // contiguous run per (b,h)).  Condensed scales first, then the others by descending last step, makes the scales
+  // that the last -- largest -- steps read sit next to each other in reading order.  The smallest capacity wins;
+  // among equals, the placement whose steps stream the fewest separate runs (one table entry and one long burst
+  // per run).
+  std::vector<std::vector<int>> orders(3, stored_scales);
+  std::stable_sort(orders[0].begin(), orders[0].end(), [&](int a, int b) { return tokens[a] > tokens[b]; });
+  std::stable_sort(orders[2].begin(), orders[2].end(), [&](int a, int b) {
+    const bool ca = a < p.n_condensed || p.keep_all, cb = b < p.n_condensed || p.keep_all;
+    if (ca != cb) return ca;
+    if (ca) return a < b;
+    return last_step_resident(p, a, n_scales) > last_step_resident(p, b, n_scales);
+  });
+  int64_t best_cap = -1, best_cost = 0;
+  for (const std::vector<int>& order : orders) {
+    int32_t off[AMSKV_MAX_SCALES];
+    const int64_t cap = place_slots(p, tokens, n_scales, order, off);
+    const int64_t cost = placement_cost(p, tokens, n_scales, off);
+    if (best_cap < 0 || cap < best_cap || (cap == best_cap && cost < best_cost)) {
+      best_cap = cap;
+      best_cost = cost;
+      std::copy(off, off + n_scales, off_out);
+    }
+  }
+  return best_cap;
 }
 
 struct Plan {

@@ -77,6 +77,34 @@ def test_planned_layout_is_overlap_free_fixed_and_tight(sides):
         amskv.amskv_cache_destroy(h)
 
 
+@pytest.mark.parametrize("borrow", [False, True])
+def test_planned_layout_keeps_reading_order_contiguous_where_it_costs_nothing(borrow):
+    """Among the placements of least capacity the one whose steps stream the fewest separate runs is taken: a layer that
+    keeps everything holds its scales back to back in ascending order, and under {0,1} + window 2 the scales the last
+    step reads form one run."""
+    tokens = [s * s for s in VAR]
+    st = orc.scale_starts(tokens)
+    pols = [(0, 0, True), (2, 2, False)]
+    h = amskv.amskv_cache_create(len(pols), 3, 64, VAR, VAR, 2, amskv.AMSKV_DTYPE_BF16, pols, 0.0, amskv.AMSKV_LAYOUT_PLANNED,
+                                 borrow_unretained=borrow)
+    try:
+        for s in range(len(VAR)):
+            for l in range(len(pols)):
+                amskv.amskv_append_scale(h, l, s)
+        keep_all = [x for x in amskv.amskv_cache_layout(h, 0) if x[1] >= 0]
+        assert [(k, o) for k, o, _ in keep_all] == [(k, st[k]) for k, _, _ in keep_all]
+        window = [x for x in amskv.amskv_cache_layout(h, 1) if x[1] >= 0]
+        at = 0
+        for k, o, n in window:                      # ascending scale id = reading order
+            assert o == at
+            at += n
+        for l, pol in enumerate(pols):
+            want = orc.stored_capacity(tokens, pol) if borrow else orc.cache_capacity(tokens, pol)
+            assert amskv.amskv_cache_capacity_tokens(h, l) == want
+    finally:
+        amskv.amskv_cache_destroy(h)
+
+
 @pytest.mark.parametrize("layout", [amskv.AMSKV_LAYOUT_COMPACT, amskv.AMSKV_LAYOUT_PLANNED])
 def test_borrow_unretained_layout(layout):
     sides = VAR
