@@ -6,10 +6,11 @@
 // One WAVE owns one unit = (b, h, block of 32 query rows); the four waves of a workgroup are
 // independent (no barrier, no shared data).  K fragments are loaded straight from the cache into
 // registers in the A-operand layout of v_mfma_f32_32x32x16_bf16 (lane (r,h) reads 16 bytes of
-// key row r), so K never touches LDS; the only LDS use is one 32-key block of V per wave, which
-// the transposing read ds_read_b64_tr_b16 needs as its source.  The loads of block g+1 are issued
-// right after the first product of block g has consumed the K registers, so they overlap the
-// softmax and the second product.  Same transposed formulation (S^T = K Q^T, O^T += V^T P^T) and
+// key row r), so K never touches LDS; the only LDS use is two 32-key blocks of V per wave, which
+// the transposing read ds_read_b64_tr_b16 needs as its source and which direct-to-LDS loads fill
+// without passing through registers (that is what lets four waves per SIMD be resident at head
+// dim 64).  The loads of block g+1 are issued right after the first product of block g has
+// consumed the K registers, so they overlap the softmax and the second product.  Same transposed formulation (S^T = K Q^T, O^T += V^T P^T) and
 // the same segment-table walk as the streaming kernel; plain online softmax.
 #include "amskv_internal.hpp"
 
@@ -31,6 +32,15 @@ __device__ __forceinline__ bf16x4 lds_read_tr16(const char* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((AMSKV_LDS bf16x4*)(p));
 }
 
+// One wave-wide direct-to-LDS load: lane i's 16 bytes at `g` land at lds_wave_base + 16*i (wave-uniform base,
+// through M0).  Inline assembly: the compiler does not count it among its outstanding loads, which is safe
+// here because every V load is issued BEFORE the K register loads of the same block -- loads complete in
+// order, so the wait the compiler places in front of the first use of those K registers covers it.
+__device__ __forceinline__ void lds_dma16(const char* g, char* lds_wave_base) {
+  const unsigned m0v = (unsigned)(size_t)(AMSKV_LDS char*)lds_wave_base;
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(m0v) : "memory", "m0");
+}
+
 __device__ __forceinline__ float max3(float a, float b, float c) {
   float r;
   asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
@@ -44,10 +54,10 @@ __device__ __forceinline__ float max3(float a, float b, float c) {
 // it after the matrix instructions and before every later use.
 __device__ __forceinline__ void settle_mfma(f32x16& acc) { asm volatile("s_nop 11" : "+v"(acc)); }
 
-// Register budget: three waves per SIMD at head dim 64 and two at 128 are the most that fit without spilling;
+// Register budget: four waves per SIMD at head dim 64 and two at 128 are the most that fit without spilling;
 // every step up in resident waves measured faster on these latency-bound launches.
 template <int D>
-__global__ __launch_bounds__(64 * kWavesPerGroup, D == 64 ? 3 : 2) void attend_bf16_small_kernel(
+__global__ __launch_bounds__(64 * kWavesPerGroup, D == 64 ? 4 : 2) void attend_bf16_small_kernel(
     const __bf16* __restrict__ q, __bf16* __restrict__ o, char* __restrict__ kc, char* __restrict__ vc,
     int t_q, long long cap_tokens, SegTable seg, ExtKV ext_kv, CallerIo io, float scale_log2e, int n_qblk, int n_units) {
   constexpr int RB = D * 2;
@@ -56,9 +66,9 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, D == 64 ? 3 : 2) void attend_b
   constexpr int DB = D / 32;
   constexpr int VCH = 32 * CPR / 64;  // 16-byte chunks of a 32-key V block per lane
 
-  __shared__ __align__(16) char lds_v[kWavesPerGroup][32 * RB];
+  __shared__ __align__(1024) char lds_v[kWavesPerGroup][2][32 * RB];  // per wave: the block in use and the one in flight
 
-  const int wave = threadIdx.x >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   const int unit = blockIdx.x * kWavesPerGroup + wave;
   if (unit >= n_units) return;  // waves are independent: nothing below synchronises across waves
@@ -75,7 +85,6 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, D == 64 ? 3 : 2) void attend_b
   const long long x_tok = io.kv.tok;
   const char* q_unit = (const char*)q + unit_offset(io.q, bh, io.heads);
   char* o_unit = (char*)o + unit_offset(io.o, bh, io.heads);
-  char* my_v = lds_v[wave];
   const bool write_back = ext_kv.wb_off >= 0 && q_base == 0;
 
   bf16x8 qf[KS];
@@ -86,21 +95,23 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, D == 64 ? 3 : 2) void attend_b
   }
 
   bf16x8 kf[KS];
-  u32x4 vch[VCH];
+  // lane i of V load k fills chunk position i % CPR of row k * (64 / CPR) + i / CPR with the global chunk that the
+  // XOR swizzle (same as the streaming kernel's at head dim 64) assigns to that position
   auto load_block = [&](int g) {
     const int j0 = 32 * g;
+    char* dst = lds_v[wave][g & 1];
+#pragma unroll
+    for (int k = 0; k < VCH; ++k) {
+      const int row = k * (64 / CPR) + lane / CPR, c = (lane % CPR) ^ (row & 7);
+      bool vext;
+      const long long vrow = locate_row(seg, min(j0 + row, t_kv - 1), vext);
+      lds_dma16((vext ? xv + vrow * x_tok : vb + vrow * RB) + 16 * c, dst + k * 1024);
+    }
     bool kext;
     const long long krow = locate_row(seg, min(j0 + r, t_kv - 1), kext);
     const char* kp = kext ? xk + krow * x_tok : kb + krow * RB;
 #pragma unroll
     for (int t = 0; t < KS; ++t) kf[t] = *reinterpret_cast<const bf16x8*>(kp + 32 * t + 16 * h);
-#pragma unroll
-    for (int k = 0; k < VCH; ++k) {
-      const int id = k * 64 + lane, row = id / CPR, c = id % CPR;
-      bool vext;
-      const long long vrow = locate_row(seg, min(j0 + row, t_kv - 1), vext);
-      vch[k] = *reinterpret_cast<const u32x4*>((vext ? xv + vrow * x_tok : vb + vrow * RB) + 16 * c);
-    }
   };
   load_block(0);
 
@@ -115,12 +126,10 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, D == 64 ? 3 : 2) void attend_b
   const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
 
   for (int g = 0; g < n_blocks; ++g) {
-    // stage this block's V rows for the transposing reads (same XOR swizzle as the streaming kernel)
-#pragma unroll
-    for (int k = 0; k < VCH; ++k) {
-      const int id = k * 64 + lane, row = id / CPR, c = id % CPR;
-      *reinterpret_cast<u32x4*>(my_v + row * RB + 16 * (c ^ (row & 7))) = vch[k];
-    }
+    // every load of block g (the V rows in LDS and the K registers) has landed; an explicit point, because the
+    // compiler does not know that the V loads wrote LDS and could otherwise move reads of it above its own wait
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    const char* my_v = lds_v[wave][g & 1];
     f32x16 sacc;
 #pragma unroll
     for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
@@ -136,9 +145,10 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, D == 64 ? 3 : 2) void attend_b
       }
 #pragma unroll
       for (int k = 0; k < VCH; ++k) {
-        const int id = k * 64 + lane, row = id / CPR, c = id % CPR;
+        const int row = k * (64 / CPR) + lane / CPR, c = (lane % CPR) ^ (row & 7);
         if (j0 + row >= seg.ext_start && j0 + row < t_kv)
-          *reinterpret_cast<u32x4*>(vb + (long long)(ext_kv.wb_off + j0 + row - seg.ext_start) * RB + 16 * c) = vch[k];
+          *reinterpret_cast<u32x4*>(vb + (long long)(ext_kv.wb_off + j0 + row - seg.ext_start) * RB + 16 * c) =
+              *reinterpret_cast<const u32x4*>(my_v + k * 1024 + 16 * lane);
       }
     }
     if (g + 1 < n_blocks) load_block(g + 1);  // in flight during the softmax and the second product

@@ -26,7 +26,7 @@ def test_resource_remarks_are_parsed():
 @pytest.mark.parametrize("row,word", [
     ({"name": "attend_bf16_kernel<64, 1, 8, 64, 4>", "scratch": 0, "occupancy": 3}, "promise 4"),
     ({"name": "attend_bf16_kernel<128, 1, 4, 32, 3>", "scratch": 12, "occupancy": 3}, "scratch"),
-    ({"name": "attend_bf16_small_kernel<64>", "scratch": 0, "occupancy": 2}, "promise 3"),
+    ({"name": "attend_bf16_small_kernel<64>", "scratch": 0, "occupancy": 3}, "promise 4"),
     ({"name": "compact_kernel", "scratch": 4, "occupancy": 8}, "scratch"),
 ])
 def test_a_spill_or_a_missed_occupancy_fails_the_build(row, word):
