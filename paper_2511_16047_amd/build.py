@@ -31,7 +31,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip", "-W
 # Waves per SIMD a kernel must reach (the last template argument of the streaming attention kernel is that
 # promise; the coarse-scale and density kernels state theirs in __launch_bounds__).
 MIN_OCCUPANCY = [
-    (re.compile(r"attend_bf16_kernel<\d+, \d+, \d+, \d+, (\d+)>"), None),     # None: take group 1
+    (re.compile(r"attend_bf16_kernel<\d+, \d+, \d+, \d+, (\d+)[,>]"), None),     # None: take group 1
     (re.compile(r"attend_bf16_small_kernel<64>"), 4),
     (re.compile(r"attend_bf16_small_kernel<128>"), 2),
 ]
@@ -71,9 +71,9 @@ def kernel_resources(compiler_output: str):
         filt = filt if os.path.exists(filt) else "c++filt"
         names = subprocess.run([filt] + [r["name"] for r in rows], stdout=subprocess.PIPE, text=True).stdout.splitlines()
         for r, n in zip(rows, names):
-            m = re.search(r"N_1\d+([A-Za-z_]\w*?)I((?:Li\d+E)+)E", n)
+            m = re.search(r"N_1\d+([A-Za-z_]\w*?)I((?:L[ib]\d+E)+)E", n)
             if n.startswith("_Z") and m:     # a type this c++filt does not know (__bf16): integer template arguments by hand
-                n = "%s<%s>" % (m.group(1), ", ".join(re.findall(r"Li(\d+)E", m.group(2))))
+                n = "%s<%s>" % (m.group(1), ", ".join(re.findall(r"L[ib](\d+)E", m.group(2))))
             n = n.replace("(anonymous namespace)::", "").replace("void ", "").replace("amskv::", "")
             r["name"] = n.split("(")[0]
     return rows

@@ -1,0 +1,94 @@
+"""GPU parity of the bf16 attention of the mid scales (33..128 query rows at head dim 64) at unit counts far
+above what the chip holds at once (several rounds of workgroups per compute unit), which the small parity cases
+never reach.  A few distinct units are repeated over a large batch: every copy must come out bit-identical to
+the first -- whatever round its workgroup ran in, whatever ran beside it -- and the first is held against the
+oracle to the usual bar.
+
+Bar: bit-exact between the copies and for the cache contents; max-abs 2e-2 (bf16) against the oracle.
+"""
+import numpy as np
+import pytest
+import torch
+
+import amskv_inputs as inp
+import paper_2511_16047_amd as amskv
+from oracle import amskv_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-2
+H, D = 6, 64
+
+
+def _f64(t):
+    return t.detach().to("cpu", torch.float64).numpy()
+
+
+def _same_bits(t):
+    """every batch entry of t equals entry 0 bit for bit"""
+    v = t.contiguous().view(torch.int16)
+    return bool((v == v[0:1]).all().item())
+
+
+def _run(sides, copies, policy, layout, borrow=False, fuse=False):
+    tokens = [s * s for s in sides]
+    q1, k1, v1 = inp.correlated_qkv(sides, 1, H, D, "bf16", inp.layer_seed(9, copies + len(sides)), 0.7)
+    rep = lambda xs: [x.cuda().repeat(copies, 1, 1, 1).contiguous() for x in xs]
+    q, k, v = rep(q1), rep(k1), rep(v1)
+    pols = [policy]
+    need = amskv.amskv_cache_required_bytes(1, H, D, sides, sides, copies, amskv.AMSKV_DTYPE_BF16, pols, 0.0, layout, borrow, fuse)
+    arena = torch.empty(need, dtype=torch.uint8, device="cuda")
+    arena.fill_(0xFF)
+    h = amskv.amskv_cache_create(1, H, D, sides, sides, copies, amskv.AMSKV_DTYPE_BF16, pols, 0.0, layout, arena=arena,
+                                 borrow_unretained=borrow, fuse_append=fuse)
+    try:
+        outs = []
+        for s in range(len(sides)):
+            amskv.amskv_append_scale(h, 0, s, k[s], v[s])
+            o = torch.full_like(q[s], float("nan"))
+            amskv.amskv_attend(h, 0, s, q[s], o)
+            outs.append(o)
+        torch.cuda.synchronize()
+        want = orc.attend_all_steps([_f64(x) for x in q1], [_f64(x) for x in k1], [_f64(x) for x in v1], tokens, policy, None)
+        worst = 0.0
+        for s in range(len(sides)):
+            assert _same_bits(outs[s]), "step %d: a copy differs from the first" % s
+            got = _f64(outs[s][0:1])
+            assert np.isfinite(got).all()
+            err = float(np.abs(got - want[s]).max())
+            worst = max(worst, err)
+            assert err <= TOL, "step %d max-abs %.3e" % (s, err)
+        # the cache the steps left behind (the fused append writes it from inside the attention kernel)
+        kept = orc.kept_scales(policy, len(sides) - 1)
+        tk = sum(tokens[j] for j in kept)
+        ko = torch.empty(copies, H, tk, D, dtype=torch.bfloat16, device="cuda")
+        vo = torch.empty_like(ko)
+        amskv.amskv_cache_export(h, 0, ko, vo)
+        torch.cuda.synchronize()
+        assert torch.equal(ko, torch.cat([k[j] for j in kept], dim=-2)) and torch.equal(vo, torch.cat([v[j] for j in kept], dim=-2))
+    finally:
+        amskv.amskv_cache_destroy(h)
+    return worst
+
+
+# 36, 49, 81 and 121 query rows: two, two, one and no idle waves in the four-wave workgroup; 36..287 keys
+SIDES = (6, 7, 9, 11)
+
+
+@pytest.mark.parametrize("copies", [180, 500], ids=["1080_units", "3000_units"])
+@pytest.mark.parametrize("policy,layout,borrow,fuse", [
+    ((0, 0, True), amskv.AMSKV_LAYOUT_COMPACT, False, False),
+    ((1, 1, False), amskv.AMSKV_LAYOUT_PLANNED, False, False),
+    ((1, 1, False), amskv.AMSKV_LAYOUT_PLANNED, True, True),
+    ((1, 2, False), amskv.AMSKV_LAYOUT_COMPACT, True, False),
+], ids=["keep_all", "window", "window_fused_append", "window_borrowed"])
+def test_copies_match_the_first(copies, policy, layout, borrow, fuse):
+    worst = _run(SIDES, copies, policy, layout, borrow, fuse)
+    print("%d units: worst max-abs %.3e" % (copies * H, worst))
+
+
+def test_short_streams():
+    # 36..68 keys: two or three tiles per unit
+    _run((6, 2, 1), 400, (0, 0, True), amskv.AMSKV_LAYOUT_COMPACT)
+    _run((6,), 400, (0, 0, True), amskv.AMSKV_LAYOUT_COMPACT)
+    _run((8, 2), 400, (1, 1, False), amskv.AMSKV_LAYOUT_PLANNED, True, True)
