@@ -336,10 +336,32 @@ def density_probe(amskv, torch, x, res):
     d_ms = e0.elapsed_time(e1) / L
     d_fl = sum(2.0 * B * H * w.tokens[S - 1] * res["kv_len"][l][S - 1] * D for l in range(L)) / L
     last = outs[L - 1].cpu().numpy().reshape(H, amskv.AMSKV_MAX_SCALES)[0, : len(lens[-1])]
+    # the same masses as a by-product of the step's own attention launch (amskv_attend_density) against that launch alone
+    outs2 = torch.empty_like(outs)
+    t = []
+    for with_density in (False, True, False, True):
+        e0.record()
+        for l in range(L):
+            if with_density:
+                amskv.amskv_attend_density(cache, l, S - 1, x.Qp[l][S - 1], x.Op[S - 1], outs2[l], x.stream)
+            else:
+                amskv.amskv_attend(cache, l, S - 1, x.Qp[l][S - 1], x.Op[S - 1], x.stream)
+        e1.record()
+        torch.cuda.synchronize()
+        t.append(e0.elapsed_time(e1) / L)
+    n_max = max(len(n) for n in lens)
+    a = outs.view(L, H, amskv.AMSKV_MAX_SCALES)[:, :, :n_max].double()
+    b = outs2.view(L, H, amskv.AMSKV_MAX_SCALES)[:, :, :n_max].double()
+    ok = torch.tensor([[i < len(n) for i in range(n_max)] for n in lens], device=a.device)[:, None, :]
+    dev_rel = float((((a - b).abs() / a.abs().clamp_min(1e-30)) * ok).max())
     return {"what": "per-head softmax mass per cached token of each kept scale, last step, one enqueued call per layer "
                     "(kernels + device-to-device result copy; one wait for all layers)", "ms_per_call": d_ms,
             "tflops_qk": d_fl / (d_ms * 1e-3) / 1e12,
-            "last_layer_head0_density_per_kept_scale": [round(float(m) / n, 4) for m, n in zip(last, lens[-1])]}
+            "last_layer_head0_density_per_kept_scale": [round(float(m) / n, 4) for m, n in zip(last, lens[-1])],
+            "as_by_product_of_the_attention_launch": {
+                "what": "amskv_attend_density against amskv_attend at the last step, ms per layer call (second of two passes each)",
+                "attend_ms": t[2], "attend_density_ms": t[3], "extra_ms": t[3] - t[2],
+                "max_rel_difference_to_the_stand_alone_masses": dev_rel}}
 
 
 def workload_record(w, mode, layout_name, borrow, fuse, res):

@@ -293,6 +293,20 @@ int32_t amskv_attention_density(amskv_cache* cache, int32_t layer, int32_t s, co
 int32_t amskv_attention_density_enqueue(amskv_cache* cache, int32_t layer, int32_t s, const void* Q_dev,
                                         float* mass_out_dev, int32_t* n_seg, int32_t* tok_len, void* stream);
 
+/* amskv_attend(layer, s) and the attention density of that step (Section 4.1) in one call: O_dev as
+ * amskv_attend leaves it, and in mass_out_dev / *n_seg / tok_len what amskv_attention_density_enqueue
+ * would report when called just before -- the groups are the layer's segments as the step's attention
+ * sees them, before the step's own bookkeeping (fused append, Algorithm 1's iteration).
+ * bf16 caches and steps of more than 32 tokens: the density is a by-product of the attention launch
+ * itself -- its kernel keeps, per query row, the sum of exp over the keys of each group next to
+ * the softmax statistics it keeps anyway, so Q, K and V are read once and nothing but the per-block
+ * partial masses is written beyond O (and the fused append).  O comes out bit-identical to
+ * amskv_attend's.  Steps of at most 32 tokens and fp32 caches: the two calls, density first.
+ * Status codes and residency rules of amskv_attend; workspace and ordering rule of
+ * amskv_attention_density_enqueue. */
+int32_t amskv_attend_density(amskv_cache* cache, int32_t layer, int32_t s, const void* Q_dev, void* O_dev,
+                             float* mass_out_dev, int32_t* n_seg, int32_t* tok_len, void* stream);
+
 /* Resident segments of a layer, ascending scale id: n_seg entries written to each
  * caller array of at least AMSKV_MAX_SCALES elements.  tok_offset is the position of the
  * segment inside the [cap_l] token axis of the layer's K and V regions, or -1 for a scale

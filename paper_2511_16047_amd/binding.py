@@ -36,7 +36,7 @@ EXPORTED = [
     "amskv_cache_bytes_held", "amskv_cache_capacity_tokens", "amskv_cache_export",
     "amskv_cache_reset", "amskv_cache_destroy", "amskv_status_string",
     "amskv_cache_segments", "amskv_cache_budget_tokens", "amskv_cache_settle", "amskv_attention_density",
-    "amskv_attention_density_enqueue",
+    "amskv_attention_density_enqueue", "amskv_attend_density",
     "amskv_cache_set_io_layout", "amskv_interscale_similarity_enqueue", "amskv_interscale_similarity_collect",
     "amskv_interscale_similarity_enqueue_static",
 ]
@@ -121,6 +121,8 @@ def load_library() -> C.CDLL:
     lib.amskv_attention_density.restype = i32
     lib.amskv_attention_density_enqueue.argtypes = [vp, i32, i32, vp, vp, C.POINTER(i32), C.POINTER(i32), vp]
     lib.amskv_attention_density_enqueue.restype = i32
+    lib.amskv_attend_density.argtypes = [vp, i32, i32, vp, vp, vp, C.POINTER(i32), C.POINTER(i32), vp]
+    lib.amskv_attend_density.restype = i32
     lib.amskv_cache_set_io_layout.argtypes = [vp, i32, i64, i64, i64]
     lib.amskv_cache_set_io_layout.restype = i32
     lib.amskv_interscale_similarity_enqueue.argtypes = [vp, i32, i32, i32, vp]
@@ -251,6 +253,16 @@ def amskv_attention_density_enqueue(cache, layer, s, Q, mass_out, stream=None):
     ln = (C.c_int32 * _MAX_SEGMENTS)()
     _check(load_library().amskv_attention_density_enqueue(cache, layer, s, _ptr(Q), _ptr(mass_out), C.byref(n), ln,
                                                           _stream(stream)), "amskv_attention_density_enqueue")
+    return [int(ln[i]) for i in range(n.value)]
+
+
+def amskv_attend_density(cache, layer, s, Q, O, mass_out, stream=None):
+    """amskv_attend plus the step's attention density: mass_out as for amskv_attention_density_enqueue.
+    Returns the key-token count of every group."""
+    n = C.c_int32(0)
+    ln = (C.c_int32 * _MAX_SEGMENTS)()
+    _check(load_library().amskv_attend_density(cache, layer, s, _ptr(Q), _ptr(O), _ptr(mass_out), C.byref(n), ln,
+                                               _stream(stream)), "amskv_attend_density")
     return [int(ln[i]) for i in range(n.value)]
 
 

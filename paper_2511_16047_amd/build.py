@@ -32,6 +32,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip", "-W
 # promise; the coarse-scale and density kernels state theirs in __launch_bounds__).
 MIN_OCCUPANCY = [
     (re.compile(r"attend_bf16_kernel<\d+, \d+, \d+, \d+, (\d+)[,>]"), None),     # None: take group 1
+    (re.compile(r"attend_density_bf16_kernel<\d+, \d+, \d+, \d+, (\d+)[,>]"), None),
     (re.compile(r"attend_bf16_small_kernel<64>"), 4),
     (re.compile(r"attend_bf16_small_kernel<128>"), 2),
 ]

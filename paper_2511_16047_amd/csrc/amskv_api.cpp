@@ -791,8 +791,13 @@ int32_t amskv_append_scale(amskv_cache* c, int32_t layer, int32_t s, const void*
   return AMSKV_OK;
 }
 
-int32_t amskv_attend(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev, void* O_dev,
-                     void* stream) {
+static int density_launch(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev, hipStream_t st, SegTable* table,
+                          float** totals);
+
+// The attention of step s; with mass_out_dev also the attention density of the step's queries over the groups of
+// keys as they are before the step's own bookkeeping (what amskv_attention_density_enqueue would report just before).
+static int attend_step(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev, void* O_dev, void* stream,
+                       float* mass_out_dev, int32_t* n_seg, int32_t* tok_len) {
   if (bad_layer(c, layer) || s < 0 || s >= c->n_scales || !Q_dev || !O_dev || misaligned(Q_dev) || misaligned(O_dev))
     return AMSKV_ERR_INVALID_ARG;
   if (int rc = finish_iteration(c, layer)) return rc;
@@ -804,6 +809,30 @@ int32_t amskv_attend(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev
   ExtKV ext;
   const SegTable t = seg_table(L, &ext);
   if (t.ext_start < t.total && !ext.k) return AMSKV_ERR_NO_DEVICE_MEMORY;  // borrowed scale appended without data
+  // density: one group per entry of the layer's list; as a by-product of this very launch where the kernel has
+  // that form (bf16, more query rows than the coarse-scale kernel takes), else by the stand-alone kernels first
+  amskv::GroupEnds groups;
+  std::memset(&groups, 0, sizeof(groups));
+  bool by_product = false;
+  if (mass_out_dev) {
+    if (L.segs.size() > (size_t)AMSKV_MAX_SCALES) return AMSKV_ERR_INVALID_ARG;
+    by_product = c->dtype == AMSKV_DTYPE_BF16 && amskv::attend_density_fused(c->tokens[s]);
+    int32_t v = 0;
+    for (const Segment& g : L.segs) {
+      v += g.len;
+      if (tok_len) tok_len[groups.n] = g.len;
+      groups.end[groups.n++] = v;
+    }
+    *n_seg = groups.n;
+    if (!by_product) {
+      SegTable pieces;
+      float* totals = nullptr;
+      if (int rc = density_launch(c, layer, s, Q_dev, (hipStream_t)stream, &pieces, &totals)) return rc;
+      if (hipMemcpyAsync(mass_out_dev, totals, (size_t)c->heads * AMSKV_MAX_SCALES * sizeof(float), hipMemcpyDeviceToDevice,
+                         (hipStream_t)stream) != hipSuccess)
+        return AMSKV_ERR_HIP;
+    }
+  }
   Segment& newest = L.segs.back();
   if (newest.pending) ext.wb_off = newest.off;  // fused append: this launch also fills the slot
   // token-budget mode: when the scale fits the budget in force next to what is cached, Algorithm 1 keeps all of
@@ -819,7 +848,11 @@ int32_t amskv_attend(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev
   const CallerIo io{caller_map(c, c->tokens[s], c->q_tok), caller_map(c, c->tokens[s], c->o_tok),
                     caller_map(c, newest.len, c->kv_tok), c->heads};
   hipError_t e;
-  if (c->dtype == AMSKV_DTYPE_BF16)
+  if (by_product)
+    e = amskv::launch_attend_density_bf16(Q_dev, O_dev, c->arena + L.k_off, c->arena + L.v_off, c->batch, c->heads,
+                                          c->tokens[s], c->head_dim, L.cap, t, ext, io, c->softmax_scale, groups,
+                                          (float*)(c->arena + c->dens_off), mass_out_dev, (hipStream_t)stream);
+  else if (c->dtype == AMSKV_DTYPE_BF16)
     e = amskv::launch_attend_bf16(Q_dev, O_dev, c->arena + L.k_off, c->arena + L.v_off, bh,
                                   c->tokens[s], c->head_dim, L.cap, t, ext, io, c->softmax_scale,
                                   (hipStream_t)stream);
@@ -835,6 +868,16 @@ int32_t amskv_attend(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev
   // what is left of the iteration (anything, unless this launch wrote the whole scale to its place) waits for the next call on the layer
   if (c->mode == AMSKV_MODE_TOKEN_BUDGET) return roll_budget(c, L, (hipStream_t)stream, appended_at, true);
   return AMSKV_OK;
+}
+
+int32_t amskv_attend(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev, void* O_dev, void* stream) {
+  return attend_step(c, layer, s, Q_dev, O_dev, stream, nullptr, nullptr, nullptr);
+}
+
+int32_t amskv_attend_density(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev, void* O_dev, float* mass_out_dev,
+                             int32_t* n_seg, int32_t* tok_len, void* stream) {
+  if (!mass_out_dev || misaligned(mass_out_dev) || !n_seg) return AMSKV_ERR_INVALID_ARG;
+  return attend_step(c, layer, s, Q_dev, O_dev, stream, mass_out_dev, n_seg, tok_len);
 }
 
 // Checks shared by the two ways of asking for Eq. 3; on success cur/prev point at the two whole scales.

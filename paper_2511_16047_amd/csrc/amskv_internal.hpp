@@ -23,6 +23,13 @@ struct SegTable {
   int32_t len[AMSKV_MAX_SCALES];
 };
 
+// Groups of keys of the virtual concatenation, for the attention density: group i covers virtual rows
+// [end[i-1], end[i]) (from 0 for the first); end[n-1] == SegTable::total.
+struct GroupEnds {
+  int32_t n;
+  int32_t end[AMSKV_MAX_SCALES];
+};
+
 // External (borrowed) K and V of the current scale in the caller's buffers (rows located by
 // CallerIo::kv), or null pointers.
 // wb_off >= 0 asks the attention kernel to also write the scale it streams from k/v into the
@@ -93,6 +100,14 @@ __device__ __forceinline__ int locate_row(const SegTable& seg, int j, bool& ext)
 hipError_t launch_attend_bf16(const void* q, void* o, void* kc, void* vc, int bh,
                               int t_q, int head_dim, int64_t cap_tokens, const SegTable& seg,
                               const ExtKV& ext, const CallerIo& io, float softmax_scale, hipStream_t st);
+// The attention of a step with the attention density of its queries as a by-product: as launch_attend_bf16, plus
+// the per-head masses of the groups in out_dev (heads * AMSKV_MAX_SCALES floats; workspace as for launch_density).
+// Exists for t_q above the coarse-scale kernel's range only: attend_density_fused(t_q) tells.
+bool attend_density_fused(int t_q);
+hipError_t launch_attend_density_bf16(const void* q, void* o, void* kc, void* vc, int batch, int heads, int t_q, int head_dim,
+                                      int64_t cap_tokens, const SegTable& seg, const ExtKV& ext, const CallerIo& io,
+                                      float softmax_scale, const GroupEnds& groups, float* partial_ws, float* out_dev,
+                                      hipStream_t st);
 hipError_t launch_attend_bf16_small(const void* q, void* o, void* kc, void* vc, int bh,
                                     int t_q, int head_dim, int64_t cap_tokens, const SegTable& seg,
                                     const ExtKV& ext, const CallerIo& io, float softmax_scale, hipStream_t st);
@@ -137,5 +152,8 @@ hipError_t launch_similarity_static(const ScaleRef& cur, const ScaleRef& prev, i
 hipError_t launch_density(const void* q, const void* kc, int batch, int heads, int t_q, int head_dim, int dtype,
                           int64_t cap_tokens, const SegTable& pieces, const ExtKV& ext, const CallerIo& io,
                           float softmax_scale, float* partial_ws, float* out_dev, hipStream_t st);
+// its second stage alone: out[h][p] = mean over the batch of the sum over the query blocks of partial_ws
+hipError_t launch_density_total(const float* partial_ws, int batch, int heads, int n_qblk, int n_groups, float* out_dev,
+                                hipStream_t st);
 
 }  // namespace amskv

@@ -274,10 +274,14 @@ struct Flag {
   static constexpr bool value = B;
 };
 
-template <int D, int NQ, int kWaves, int kTileKeys, int kMinWavesPerSimd>
-__global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_kernel(
+// The work of one workgroup.  kDensity: also leave, per 32-row query block, the softmax mass that lands on each
+// group of keys (Section 4.1's attention density as a by-product of the step's own attention; `groups` holds the
+// first virtual row past each group, `partial` one float per (b, h, query block, group)).
+template <int D, int NQ, int kWaves, int kTileKeys, bool kDensity>
+__device__ __forceinline__ void attend_unit(
     const __bf16* __restrict__ q, __bf16* __restrict__ o, char* __restrict__ kc, char* __restrict__ vc,
-    int t_q, long long cap_tokens, SegTable seg, ExtKV ext_kv, CallerIo io, float scale_log2e, int n_bh, int n_qtiles) {
+    int t_q, long long cap_tokens, const SegTable& seg, const ExtKV& ext_kv, const CallerIo& io, float scale_log2e, int n_bh,
+    int n_qtiles, const GroupEnds& groups, float* __restrict__ partial) {
   using Loader = TileLoader<D, kWaves, kTileKeys>;
   constexpr int RB = D * 2;   // bytes per token row
   constexpr int KS = D / 16;  // K-steps of the first product
@@ -296,10 +300,13 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
   constexpr int VM = Loader::kVmPerTile;
   // Fetch the K fragments of block g+1 into registers while the softmax of block g runs (16 registers at head
   // dim 64; the head-dim-128 configuration has none to spare, and one-block tiles would need a fifth ring slot).
-  constexpr bool kPrefetchK = D == 64 && kBlocksPerTile == 2;
+  // (the density variant keeps the plain loop: one block at a time, the tile barrier in front of a tile's first block)
+  constexpr bool kPrefetchK = D == 64 && kBlocksPerTile == 2 && !kDensity;
 
   __shared__ __align__(1024) char lds_k[kRing];
   __shared__ __align__(1024) char lds_v[kRing];
+  // density: per wave and query row, the sum of exp over the keys of each finished group, in the row's current reference
+  __shared__ float park[kDensity ? kWaves * NQ : 1][AMSKV_MAX_SCALES][32];
 
   const int tid = threadIdx.x;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -430,11 +437,15 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
 #pragma unroll
       for (int v = 0; v < 16; ++v) oacc[n][d][v] = 0.f;
   float run_mc[NQ], run_sum[NQ];  // softmax reference times c = softmax scale * log2(e); sum of 2^(s*c - reference)
+  // density: this lane's sum over the keys of the group being walked, the group, its end, the block's first row
+  float seg_acc[NQ];
+  int cur_group = 0, next_end = kDensity ? groups.end[0] : 0, blk_start = 0;
   bf16x8 pf[NQ][2];  // probabilities of the previous block, two K-steps of 16 keys
 #pragma unroll
   for (int n = 0; n < NQ; ++n) {
     run_mc[n] = -INFINITY;
     run_sum[n] = 0.f;
+    seg_acc[n] = 0.f;
 #pragma unroll
     for (int u = 0; u < 2; ++u)
 #pragma unroll
@@ -584,6 +595,11 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
         const float new_mc = full - run_mc[n] > kMaxLag ? full : run_mc[n];
         alpha[n] = __builtin_amdgcn_exp2f(run_mc[n] - new_mc);  // 1 when unchanged, 0 on the first block
         run_sum[n] *= alpha[n];
+        if constexpr (kDensity) {  // what was summed against the old reference moves with it
+          seg_acc[n] *= alpha[n];
+          if (h == 0)
+            for (int p = 0; p < cur_group; ++p) park[wave * NQ + n][p][r] *= alpha[n];
+        }
         run_mc[n] = new_mc;
         float s0 = 0.f, s1 = 0.f;
 #pragma unroll
@@ -597,6 +613,40 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
         }
         sum[n][0] = s0 + s1;
       }
+    }
+    if constexpr (kDensity) {
+      // Groups of keys that end inside (or with) this block: the lane's sum over the group = what it gathered in
+      // the blocks before + its probabilities of this block up to the cut (formed again, exactly, for the keys
+      // below the cut; the whole block's sum when the cut is the block's end) - what earlier cuts of this block took.
+      float taken[NQ];
+#pragma unroll
+      for (int n = 0; n < NQ; ++n) taken[n] = 0.f;
+      while (next_end <= blk_start + 32) {
+        const int cut = next_end - blk_start;  // 1..32, wave-uniform
+#pragma unroll
+        for (int n = 0; n < NQ; ++n) {
+          float upto = sum[n][0];
+          if (cut < 32) {
+            upto = 0.f;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int key = 8 * (v >> 2) + 4 * h + (v & 3);
+              const float pv = __builtin_amdgcn_exp2f(fmaf(sacc[n][v], scale_log2e, -run_mc[n]));
+              upto += key < cut ? pv : 0.f;
+            }
+          }
+          float gsum = seg_acc[n] + (upto - taken[n]);
+          gsum += __shfl_xor(gsum, 32, 64);  // the two lane halves hold different keys of the same query
+          if (h == 0) park[wave * NQ + n][cur_group][r] = gsum;
+          seg_acc[n] = 0.f;
+          taken[n] = upto;
+        }
+        ++cur_group;
+        next_end = cur_group < groups.n ? groups.end[cur_group] : 0x7fffffff;
+      }
+#pragma unroll
+      for (int n = 0; n < NQ; ++n) seg_acc[n] += sum[n][0] - taken[n];
+      blk_start += 32;
     }
 #pragma unroll
     for (int n = 0; n < NQ; ++n) run_sum[n] += sum[n][0];
@@ -670,7 +720,36 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_ker
           *reinterpret_cast<bf16x4*>(dst + 32 * d + 8 * g + 4 * h) = w;
         }
     }
+    if constexpr (kDensity) {
+      // mass of the query block on group p = sum over its valid rows of (sum of exp over the group) / (sum over all keys)
+      const int n_qblk = (t_q + 31) >> 5;
+      const long long qblk = bh * n_qblk + (q_base >> 5) + n;
+      for (int p = 0; p < groups.n; ++p) {
+        float m = h == 0 && row < t_q ? park[wave * NQ + n][p][r] * inv : 0.f;
+#pragma unroll
+        for (int d = 16; d >= 1; d >>= 1) m += __shfl_xor(m, d, 64);  // over the 32 query rows (lower lane half)
+        if (lane == 0) partial[qblk * AMSKV_MAX_SCALES + p] = m;
+      }
+    }
   }
+}
+
+template <int D, int NQ, int kWaves, int kTileKeys, int kMinWavesPerSimd>
+__global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_kernel(
+    const __bf16* __restrict__ q, __bf16* __restrict__ o, char* __restrict__ kc, char* __restrict__ vc,
+    int t_q, long long cap_tokens, SegTable seg, ExtKV ext_kv, CallerIo io, float scale_log2e, int n_bh, int n_qtiles) {
+  attend_unit<D, NQ, kWaves, kTileKeys, false>(q, o, kc, vc, t_q, cap_tokens, seg, ext_kv, io, scale_log2e, n_bh, n_qtiles,
+                                               GroupEnds{}, nullptr);
+}
+
+// The same step with the attention density of its own queries as a by-product (no second pass over Q and K).
+template <int D, int NQ, int kWaves, int kTileKeys, int kMinWavesPerSimd>
+__global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_density_bf16_kernel(
+    const __bf16* __restrict__ q, __bf16* __restrict__ o, char* __restrict__ kc, char* __restrict__ vc,
+    int t_q, long long cap_tokens, SegTable seg, ExtKV ext_kv, CallerIo io, float scale_log2e, int n_bh, int n_qtiles,
+    GroupEnds groups, float* __restrict__ partial) {
+  attend_unit<D, NQ, kWaves, kTileKeys, true>(q, o, kc, vc, t_q, cap_tokens, seg, ext_kv, io, scale_log2e, n_bh, n_qtiles,
+                                              groups, partial);
 }
 
 template <int D, int NQ, int kWaves, int kTileKeys, int kMinWavesPerSimd>
@@ -685,7 +764,41 @@ hipError_t launch(const void* q, void* o, void* kc, void* vc, int bh, int t_q, i
   return hipGetLastError();
 }
 
+template <int D, int NQ, int kWaves, int kTileKeys, int kMinWavesPerSimd>
+hipError_t launch_density_variant(const void* q, void* o, void* kc, void* vc, int bh, int t_q, int64_t cap_tokens,
+                                  const SegTable& seg, const ExtKV& ext, const CallerIo& io, float c, const GroupEnds& groups,
+                                  float* partial, hipStream_t st) {
+  constexpr int BM = kWaves * 32 * NQ;
+  const int n_qtiles = (t_q + BM - 1) / BM;
+  dim3 grid((unsigned)(((bh + 7) / 8) * 8 * n_qtiles)), block(64 * kWaves);
+  hipLaunchKernelGGL((attend_density_bf16_kernel<D, NQ, kWaves, kTileKeys, kMinWavesPerSimd>), grid, block, 0, st,
+                     (const __bf16*)q, (__bf16*)o, (char*)kc, (char*)vc, t_q, (long long)cap_tokens, seg, ext, io, c,
+                     bh, n_qtiles, groups, partial);
+  return hipGetLastError();
+}
+
 }  // namespace
+
+bool attend_density_fused(int t_q) { return t_q > kSmallTq; }
+
+hipError_t launch_attend_density_bf16(const void* q, void* o, void* kc, void* vc, int batch, int heads, int t_q, int head_dim,
+                                      int64_t cap_tokens, const SegTable& seg, const ExtKV& ext, const CallerIo& io,
+                                      float softmax_scale, const GroupEnds& groups, float* partial_ws, float* out_dev,
+                                      hipStream_t st) {
+  if (!attend_density_fused(t_q)) return hipErrorInvalidValue;
+  const float c = softmax_scale * 1.4426950408889634f;
+  const int bh = batch * heads;
+  // Four waves of 32 rows and 32-key tiles at either head dim (the ring shares LDS with the per-row group sums,
+  // and the block step holds its scores a little longer: three and two waves per SIMD); more than 128 query rows
+  // are split over workgroups with ids 8 apart, which re-read K~ and V~ from their XCD's L2.
+  hipError_t e;
+  if (head_dim == 64)
+    e = launch_density_variant<64, 1, 4, 32, 3>(q, o, kc, vc, bh, t_q, cap_tokens, seg, ext, io, c, groups, partial_ws, st);
+  else
+    e = launch_density_variant<128, 1, 4, 32, 2>(q, o, kc, vc, bh, t_q, cap_tokens, seg, ext, io, c, groups, partial_ws, st);
+  if (e != hipSuccess) return e;
+  return launch_density_total(partial_ws, batch, heads, (t_q + 31) / 32, groups.n, out_dev, st);
+}
 
 hipError_t launch_attend_bf16(const void* q, void* o, void* kc, void* vc, int bh, int t_q,
                               int head_dim, int64_t cap_tokens, const SegTable& seg, const ExtKV& ext, const CallerIo& io,

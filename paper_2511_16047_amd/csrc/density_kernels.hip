@@ -225,7 +225,12 @@ hipError_t launch_density(const void* q, const void* kc, int batch, int heads, i
                        (long long)cap_tokens, pieces, ext, io, c, n_qblk, (int)n_units, partial_ws);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(density_total_kernel, dim3(heads), dim3(16 * kParts), 0, st, partial_ws, batch, heads, n_qblk, pieces.n,
+  return launch_density_total(partial_ws, batch, heads, n_qblk, pieces.n, out_dev, st);
+}
+
+hipError_t launch_density_total(const float* partial_ws, int batch, int heads, int n_qblk, int n_groups, float* out_dev,
+                                hipStream_t st) {
+  hipLaunchKernelGGL(density_total_kernel, dim3(heads), dim3(16 * kParts), 0, st, partial_ws, batch, heads, n_qblk, n_groups,
                      out_dev);
   return hipGetLastError();
 }

@@ -253,3 +253,117 @@ def test_density_enqueue_matches_the_waiting_call():
             amskv.amskv_attention_density_enqueue(h, 0, s, qd[s], None)
     finally:
         amskv.amskv_cache_destroy(h)
+
+
+def _mass_rows(buf, H, n):
+    return buf.cpu().numpy().reshape(H, amskv.AMSKV_MAX_SCALES)[:, :n].astype(np.float64)
+
+
+def _bits(t):
+    it = torch.int16 if t.dtype == torch.bfloat16 else torch.int32
+    return t.contiguous().view(it).cpu().numpy()
+
+
+@pytest.mark.parametrize("flags", [dict(), dict(layout=amskv.AMSKV_LAYOUT_PLANNED, borrow_unretained=True, fuse_append=True)],
+                         ids=["compact", "planned_borrow_fuse"])
+@pytest.mark.parametrize("D,dtype", [(64, "bf16"), (128, "bf16"), (64, "f32")])
+def test_attend_density_in_one_call(D, dtype, flags):
+    """amskv_attend_density: O bit-identical to amskv_attend on a twin cache, the masses against the oracle, the
+    caches bit-identical afterwards.  The schedule covers the by-product form (more than 32 queries; two workgroups
+    per unit from 169 queries on at head dim 64, at 169 and 256 at head dim 128) and the two-call form (coarse
+    scales; the whole fp32 case); groups of 1 and 4 keys end inside the first 32-key block."""
+    B, H = 2, 3
+    DT = amskv.AMSKV_DTYPE_BF16 if dtype == "bf16" else amskv.AMSKV_DTYPE_F32
+    tokens = [x * x for x in VAR]
+    pols = [(2, 2, False), (0, 0, True), (1, 0, False)]
+    q, k, v = inp.correlated_qkv(VAR, B, H, D, dtype, inp.layer_seed(8, 500 + D), 0.7)
+    k_all = np.concatenate([_f64(x) for x in k], axis=-2)
+    qd, kd, vd = ([x.cuda() for x in t] for t in (q, k, v))
+    kw = dict(flags)
+    layout = kw.pop("layout", amskv.AMSKV_LAYOUT_COMPACT)
+    need = amskv.amskv_cache_required_bytes(len(pols), H, D, VAR, VAR, B, DT, pols, 0.0, layout, **kw)
+    arenas = [torch.empty(need, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    for a in arenas:
+        a.fill_(0xFF)
+    one, two = (amskv.amskv_cache_create(len(pols), H, D, VAR, VAR, B, DT, pols, 0.0, layout, arena=a, **kw) for a in arenas)
+    st = orc.scale_starts(tokens)
+    try:
+        for s in range(len(VAR)):
+            for l, pol in enumerate(pols):
+                for h in (one, two):
+                    amskv.amskv_append_scale(h, l, s, kd[s], vd[s])
+                o1 = torch.full_like(qd[s], float("nan"))
+                o2 = torch.full_like(qd[s], float("nan"))
+                mass = torch.full((H * amskv.AMSKV_MAX_SCALES,), float("nan"), dtype=torch.float32, device="cuda")
+                lens = amskv.amskv_attend_density(one, l, s, qd[s], o1, mass)
+                amskv.amskv_attend(two, l, s, qd[s], o2)
+                torch.cuda.synchronize()
+                kept = orc.kept_scales(pol, s)
+                assert lens == [tokens[j] for j in kept]
+                assert np.array_equal(_bits(o1), _bits(o2)), "O differs at step %d layer %d" % (s, l)
+                pieces, rows = _window_view(tokens, pol, s)
+                _, want_m = orc.attention_density(_f64(qd[s]), k_all, rows, pieces)
+                got_m = _mass_rows(mass, H, len(lens))
+                assert np.allclose(got_m, want_m, rtol=2e-4, atol=1e-5), (s, l, np.abs(got_m - want_m).max())
+                assert np.allclose(got_m.sum(axis=-1), tokens[s], rtol=1e-4)
+        for l, pol in enumerate(pols):
+            tk = sum(tokens[j] for j in orc.kept_scales(pol, len(VAR) - 1))
+            exp = [torch.empty(B, H, tk, D, dtype=kd[0].dtype, device="cuda") for _ in range(4)]
+            amskv.amskv_cache_export(one, l, exp[0], exp[1])
+            amskv.amskv_cache_export(two, l, exp[2], exp[3])
+            torch.cuda.synchronize()
+            assert torch.equal(exp[0], exp[2]) and torch.equal(exp[1], exp[3])
+    finally:
+        amskv.amskv_cache_destroy(one)
+        amskv.amskv_cache_destroy(two)
+
+
+def test_attend_density_token_budget_and_token_major():
+    """The by-product form over partial groups (head and tail of one scale cached apart, a current scale read in
+    place from token-major tensors), against the oracle's own token lists; then the step's iteration runs as after
+    amskv_attend (the next append sees the trimmed list)."""
+    sides = (6, 3, 4, 5, 2, 7)
+    tokens = [x * x for x in sides]
+    B, H, D = 2, 2, 64
+    q, k, v = inp.correlated_qkv(sides, B, H, D, "bf16", inp.layer_seed(8, 601), 0.6)
+    k_all = np.concatenate([_f64(x) for x in k], axis=-2)
+    budgets = [(40, 40, 10, -2.0), (30, 60, 20, 2.0)]
+    need = amskv.amskv_cache_required_bytes(2, H, D, sides, sides, B, BF16, None, 0.3, budgets=budgets)
+    arena = torch.empty(need, dtype=torch.uint8, device="cuda")
+    h = amskv.amskv_cache_create(2, H, D, sides, sides, B, BF16, None, 0.3, arena=arena, budgets=budgets)
+    stride = 3 * H * D
+    amskv.amskv_cache_set_io_layout(h, amskv.AMSKV_IO_TOKEN_MAJOR, stride, stride, H * D)
+    traces = [orc.alg1_cache_trace(tokens, b[0], b[1], b[2], [b[3] > 1.0] * len(sides)) for b in budgets]
+    masks = [orc.alg1_allow_mask(tokens, t) for t in traces]
+    st = orc.scale_starts(tokens)
+    cat = lambda xs: np.concatenate([_f64(x) for x in xs], axis=-2)
+    want_o = [orc.masked_attention(cat(q), cat(k), cat(v), m, 0.3) for m in masks]
+    keep = []   # K/V of a scale stay the caller's until the step's iteration has run
+    try:
+        for s in range(len(sides)):
+            # fused projection output [B][T][3][H][D]
+            packed = torch.stack([x.permute(0, 2, 1, 3) for x in (q[s], k[s], v[s])], dim=2).contiguous().cuda()
+            keep.append(packed)
+            flat = packed.view(-1)
+            qp, kp, vp = flat, flat[H * D:], flat[2 * H * D:]
+            for l in range(2):
+                amskv.amskv_append_scale(h, l, s, kp, vp)
+                ids = (traces[l][s - 1][0] if s else []) + list(range(st[s], st[s] + tokens[s]))
+                pieces = _runs_by_scale(ids, tokens)
+                rows = masks[l][st[s]: st[s] + tokens[s]]
+                o = torch.full((B, tokens[s], H * D), float("nan"), dtype=torch.bfloat16, device="cuda")
+                mass = torch.full((H * amskv.AMSKV_MAX_SCALES,), float("nan"), dtype=torch.float32, device="cuda")
+                lens = amskv.amskv_attend_density(h, l, s, qp, o, mass)
+                torch.cuda.synchronize()
+                assert lens == [n for _, n in pieces]
+                _, want_m = orc.attention_density(_f64(q[s]), k_all, rows, pieces, 0.3)
+                got_m = _mass_rows(mass, H, len(lens))
+                assert np.allclose(got_m, want_m, rtol=2e-4, atol=1e-5), (s, l, np.abs(got_m - want_m).max())
+                got_o = _f64(o.view(B, tokens[s], H, D).permute(0, 2, 1, 3))
+                assert np.abs(got_o - want_o[l][..., st[s]: st[s] + tokens[s], :]).max() <= 2e-2
+                # the iteration of the step has run or will run with the next call: the list is the oracle's
+                segs = amskv.amskv_cache_segments(h, l)
+                got_ids = [st[sc] + first + i for sc, first, _, ln in segs for i in range(ln)]
+                assert got_ids == traces[l][s][0]
+    finally:
+        amskv.amskv_cache_destroy(h)
