@@ -132,6 +132,15 @@ typedef struct {
  * until the attend call they are the only copy, and similarity/export read them in place.
  * Device work of one layer must be enqueued on one stream (or be ordered by the caller).
  *
+ * Stream capture.  In scale-window mode amskv_append_scale, amskv_attend, amskv_attend_density (bf16),
+ * amskv_interscale_similarity_enqueue and amskv_interscale_similarity_enqueue_static enqueue kernels
+ * only -- no memory copies, memsets, events or waits -- so a caller whose Q, K, V and O live in
+ * fixed buffers may issue a whole image's calls (amskv_cache_reset first) on a stream under HIP graph
+ * capture and replay the graph per image: the host side of the calls (kept sets, slots, kernel
+ * arguments) runs once, at capture, and is the same for every image.  Calls that return results to
+ * the host (_collect, the waiting forms, amskv_cache_export to the host's eyes) and the token modes,
+ * whose host decisions depend on device results (Eq. 3), are not capturable.
+ *
  * mode = AMSKV_MODE_TOKEN_BUDGET.  The cache of a layer is a list of tokens, oldest first, kept
  * back to back from offset 0 of the layer's regions (layout must be AMSKV_LAYOUT_COMPACT,
  * borrow_unretained and fuse_append must be 0; the capacity of a layer is c_max tokens).
