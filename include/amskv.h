@@ -132,8 +132,9 @@ typedef struct {
  * until the attend call they are the only copy, and similarity/export read them in place.
  * Device work of one layer must be enqueued on one stream (or be ordered by the caller).
  *
- * Stream capture.  In scale-window mode amskv_append_scale, amskv_attend, amskv_attend_density (bf16),
- * amskv_interscale_similarity_enqueue and amskv_interscale_similarity_enqueue_static enqueue kernels
+ * Stream capture.  In scale-window mode amskv_append_scale, amskv_attend, amskv_attend_density,
+ * amskv_attention_density_enqueue, amskv_interscale_similarity_enqueue and
+ * amskv_interscale_similarity_enqueue_static enqueue kernels
  * only -- no memory copies, memsets, events or waits -- so a caller whose Q, K, V and O live in
  * fixed buffers may issue a whole image's calls (amskv_cache_reset first) on a stream under HIP graph
  * capture and replay the graph per image: the host side of the calls (kept sets, slots, kernel

@@ -792,7 +792,7 @@ int32_t amskv_append_scale(amskv_cache* c, int32_t layer, int32_t s, const void*
 }
 
 static int density_launch(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev, hipStream_t st, SegTable* table,
-                          float** totals);
+                          float** totals, float* out_dev);
 
 // The attention of step s; with mass_out_dev also the attention density of the step's queries over the groups of
 // keys as they are before the step's own bookkeeping (what amskv_attention_density_enqueue would report just before).
@@ -827,10 +827,7 @@ static int attend_step(amskv_cache* c, int32_t layer, int32_t s, const void* Q_d
     if (!by_product) {
       SegTable pieces;
       float* totals = nullptr;
-      if (int rc = density_launch(c, layer, s, Q_dev, (hipStream_t)stream, &pieces, &totals)) return rc;
-      if (hipMemcpyAsync(mass_out_dev, totals, (size_t)c->heads * AMSKV_MAX_SCALES * sizeof(float), hipMemcpyDeviceToDevice,
-                         (hipStream_t)stream) != hipSuccess)
-        return AMSKV_ERR_HIP;
+      if (int rc = density_launch(c, layer, s, Q_dev, (hipStream_t)stream, &pieces, &totals, mass_out_dev)) return rc;
     }
   }
   Segment& newest = L.segs.back();
@@ -975,10 +972,10 @@ int32_t amskv_interscale_similarity_collect(amskv_cache* c, float* cosK_host, fl
   return AMSKV_OK;
 }
 
-// Checks and launch shared by the two forms of the density call; the per-head masses end up at *totals (device,
-// inside the arena's workspace) and *table describes the groups.
+// Checks and launch shared by the forms of the density call; the per-head masses end up at out_dev, or, when that
+// is null, inside the arena's workspace; *totals is where, and *table describes the groups.
 static int density_launch(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev, hipStream_t st, SegTable* table,
-                          float** totals) {
+                          float** totals, float* out_dev) {
   if (bad_layer(c, layer) || s < 0 || s >= c->n_scales || !Q_dev || misaligned(Q_dev)) return AMSKV_ERR_INVALID_ARG;
   if (int rc = finish_iteration(c, layer)) return rc;
   LayerState& L = c->layer[layer];
@@ -992,7 +989,7 @@ static int density_launch(amskv_cache* c, int32_t layer, int32_t s, const void* 
   const int64_t n_qblk = (c->tokens[s] + 31) / 32;
   if ((int64_t)c->batch * c->heads * n_qblk > INT32_MAX) return AMSKV_ERR_INVALID_ARG;
   float* partial = (float*)(c->arena + c->dens_off);
-  *totals = partial + (uint64_t)c->batch * c->heads * n_qblk * AMSKV_MAX_SCALES;
+  *totals = out_dev ? out_dev : partial + (uint64_t)c->batch * c->heads * n_qblk * AMSKV_MAX_SCALES;
   const CallerIo io{caller_map(c, c->tokens[s], c->q_tok), RowMap{0, 0, 0}, caller_map(c, L.segs.back().len, c->kv_tok),
                     c->heads};
   hipError_t e = amskv::launch_density(Q_dev, c->arena + L.k_off, c->batch, c->heads, c->tokens[s], c->head_dim, c->dtype,
@@ -1008,7 +1005,7 @@ int32_t amskv_attention_density(amskv_cache* c, int32_t layer, int32_t s, const 
   hipStream_t st = (hipStream_t)stream;
   SegTable t;
   float* totals = nullptr;
-  int rc = density_launch(c, layer, s, Q_dev, st, &t, &totals);
+  int rc = density_launch(c, layer, s, Q_dev, st, &t, &totals, nullptr);
   if (rc) return rc;
   std::vector<float> host((size_t)c->heads * AMSKV_MAX_SCALES);
   hipError_t e = hipMemcpyAsync(host.data(), totals, host.size() * sizeof(float), hipMemcpyDeviceToHost, st);
@@ -1031,11 +1028,8 @@ int32_t amskv_attention_density_enqueue(amskv_cache* c, int32_t layer, int32_t s
   hipStream_t st = (hipStream_t)stream;
   SegTable t;
   float* totals = nullptr;
-  int rc = density_launch(c, layer, s, Q_dev, st, &t, &totals);
+  int rc = density_launch(c, layer, s, Q_dev, st, &t, &totals, mass_out_dev);
   if (rc) return rc;
-  if (hipMemcpyAsync(mass_out_dev, totals, (size_t)c->heads * AMSKV_MAX_SCALES * sizeof(float), hipMemcpyDeviceToDevice,
-                     st) != hipSuccess)
-    return AMSKV_ERR_HIP;
   *n_seg = t.n;
   if (tok_len)
     for (int p = 0; p < t.n; ++p) tok_len[p] = t.len[p];

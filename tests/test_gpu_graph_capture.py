@@ -53,6 +53,9 @@ def test_captured_steps_replay_like_the_eager_calls(flags):
     sums = torch.full((L, H * 4), float("nan"), dtype=torch.float32, device="cuda")
     O_eager = [[torch.empty_like(Q[l][s]) for s in range(S)] for l in range(L)]
     sums_eager = torch.empty_like(sums)
+    # attention density of layer 0 at a coarse step (stand-alone kernels inside the call) and at a later one (by-product)
+    mass = torch.full((S, H * amskv.AMSKV_MAX_SCALES), float("nan"), dtype=torch.float32, device="cuda")
+    mass_eager = torch.empty_like(mass)
 
     def load(data):
         for l in range(L):
@@ -61,12 +64,15 @@ def test_captured_steps_replay_like_the_eager_calls(flags):
                 K[l][s].copy_(data[l][1][s])
                 V[l][s].copy_(data[l][2][s])
 
-    def steps(cache, out, sm, stream):
+    def steps(cache, out, sm, ms, stream):
         amskv.amskv_cache_reset(cache)
         for s in range(S):
             for l in range(L):
                 amskv.amskv_append_scale(cache, l, s, K[l][s], V[l][s], stream)
-                amskv.amskv_attend(cache, l, s, Q[l][s], out[l][s], stream)
+                if l == 0 and s in (2, 7):
+                    amskv.amskv_attend_density(cache, l, s, Q[l][s], out[l][s], ms[s], stream)
+                else:
+                    amskv.amskv_attend(cache, l, s, Q[l][s], out[l][s], stream)
                 if s == 5:   # Eq. 3 between scales 5 and 4, partial sums in the library's static array, result in sm
                     amskv.amskv_interscale_similarity_enqueue_static(cache, l, s, False, sm[l], stream)
 
@@ -76,11 +82,11 @@ def test_captured_steps_replay_like_the_eager_calls(flags):
     try:
         # warm the path once outside the capture (first-call work such as the static array's address lookup)
         with torch.cuda.stream(side):
-            steps(cache_g, O, sums, side.cuda_stream)
+            steps(cache_g, O, sums, mass, side.cuda_stream)
         side.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=side):
-            steps(cache_g, O, sums, torch.cuda.current_stream().cuda_stream)
+            steps(cache_g, O, sums, mass, torch.cuda.current_stream().cuda_stream)
         for rep in range(3):
             data = draw(rep + 1)
             load(data)
@@ -88,16 +94,21 @@ def test_captured_steps_replay_like_the_eager_calls(flags):
                 for s in range(S):
                     O[l][s].fill_(float("nan"))
             sums.fill_(float("nan"))
+            mass.fill_(float("nan"))
             torch.cuda.synchronize()
             graph.replay()
             torch.cuda.synchronize()
             # eager calls on a twin cache, same inputs (the program's own work between the replays)
-            steps(cache_e, O_eager, sums_eager, None)
+            steps(cache_e, O_eager, sums_eager, mass_eager, None)
             torch.cuda.synchronize()
             for l in range(L):
                 for s in range(S):
                     assert torch.equal(O[l][s].view(torch.int16), O_eager[l][s].view(torch.int16)), (rep, l, s)
             assert torch.equal(sums.view(torch.int32), sums_eager.view(torch.int32)), rep
+            for s in (2, 7):
+                assert torch.equal(mass[s].view(torch.int32), mass_eager[s].view(torch.int32)), (rep, s)
+                n = len(orc.kept_scales(pols[0], s))
+                assert abs(float(mass[s].view(H, -1)[0, :n].sum()) - tokens[s]) <= 1e-3 * tokens[s]
             if rep == 1:
                 for l, pol in enumerate(pols):
                     want = orc.attend_all_steps([_f64(x) for x in data[l][0]], [_f64(x) for x in data[l][1]],
