@@ -382,7 +382,7 @@ def density_probe(amskv, torch, x, res):
     ok = torch.tensor([[i < len(n) for i in range(n_max)] for n in lens], device=a.device)[:, None, :]
     dev_rel = float((((a - b).abs() / a.abs().clamp_min(1e-30)) * ok).max())
     return {"what": "per-head softmax mass per cached token of each kept scale, last step, one enqueued call per layer "
-                    "(kernels + device-to-device result copy; one wait for all layers)", "ms_per_call": d_ms,
+                    "(two kernels, the masses written straight into the caller's buffer; one wait for all layers)", "ms_per_call": d_ms,
             "tflops_qk": d_fl / (d_ms * 1e-3) / 1e12,
             "last_layer_head0_density_per_kept_scale": [round(float(m) / n, 4) for m, n in zip(last, lens[-1])],
             "as_by_product_of_the_attention_launch": {
