@@ -475,6 +475,7 @@ __device__ __forceinline__ void attend_unit(
   int off_prev = 0, off_cur = 0, off_next = kBlkBytes == kRing ? 0 : kBlkBytes;
   float alpha[NQ];
   bool any_rescale = false;  // the rescale decided at block g is applied at the top of block g+1
+  bool first_block = true;
 #pragma unroll
   for (int n = 0; n < NQ; ++n) alpha[n] = 1.f;
 
@@ -542,45 +543,52 @@ __device__ __forceinline__ void attend_unit(
     // of the blocks before, and the sum of the lane's 16 new ones tells whether that was good enough: while it
     // stays below kTripSum no score exceeded the reference by more than log2(kTripSum) powers of two, which is
     // far inside the range of fp32 and bf16, and the block costs no maximum at all.
+    // The first block of a unit has no reference yet and nothing to multiply (pf = 0): it goes straight to the
+    // path that takes the maximum.
     float sum[NQ][2];
 #pragma unroll
     for (int n = 0; n < NQ; ++n) sum[n][0] = sum[n][1] = 0.f;
+    const bool first = first_block;
+    first_block = false;
+    bool trip = true;
+    if (!first) {
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
+      for (int u = 0; u < 2; ++u) {
 #pragma unroll
-      for (int d = 0; d < DB; ++d) {
-        const char* vp = lds_v + off_prev + v_base[d];
-        const bf16x4 lo = lds_read_tr16(vp + (16 * u) * RB);
-        const bf16x4 hi = lds_read_tr16(vp + (16 * u) * RB + hi_off(d));
-        bf16x8 a;
-        a[0] = lo[0]; a[1] = lo[1]; a[2] = lo[2]; a[3] = lo[3];
-        a[4] = hi[0]; a[5] = hi[1]; a[6] = hi[2]; a[7] = hi[3];
+        for (int d = 0; d < DB; ++d) {
+          const char* vp = lds_v + off_prev + v_base[d];
+          const bf16x4 lo = lds_read_tr16(vp + (16 * u) * RB);
+          const bf16x4 hi = lds_read_tr16(vp + (16 * u) * RB + hi_off(d));
+          bf16x8 a;
+          a[0] = lo[0]; a[1] = lo[1]; a[2] = lo[2]; a[3] = lo[3];
+          a[4] = hi[0]; a[5] = hi[1]; a[6] = hi[2]; a[7] = hi[3];
 #pragma unroll
-        for (int n = 0; n < NQ; ++n) oacc[n][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[n][u], oacc[n][d], 0, 0, 0);
-      }
-#pragma unroll
-      for (int n = 0; n < NQ; ++n)
-#pragma unroll
-        for (int v = 8 * u; v < 8 * u + 8; v += 2) {
-          const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[n][v], scale_log2e, -run_mc[n]));
-          const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[n][v + 1], scale_log2e, -run_mc[n]));
-          sum[n][0] += p0;
-          sum[n][1] += p1;
-          pf[n][u][v & 7] = (__bf16)p0;
-          pf[n][u][(v & 7) + 1] = (__bf16)p1;
+          for (int n = 0; n < NQ; ++n) oacc[n][d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[n][u], oacc[n][d], 0, 0, 0);
         }
-    }
-    // ---- was the reference good enough?  (NaN -- a masked key against the initial reference of -inf -- and
-    // +inf -- anything against that reference -- both fail the comparison as written.)
-    bool trip = false;
 #pragma unroll
-    for (int n = 0; n < NQ; ++n) {
-      sum[n][0] += sum[n][1];
-      trip |= __builtin_amdgcn_ballot_w64(!(sum[n][0] <= kTripSum)) != 0;
+        for (int n = 0; n < NQ; ++n)
+#pragma unroll
+          for (int v = 8 * u; v < 8 * u + 8; v += 2) {
+            const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[n][v], scale_log2e, -run_mc[n]));
+            const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[n][v + 1], scale_log2e, -run_mc[n]));
+            sum[n][0] += p0;
+            sum[n][1] += p1;
+            pf[n][u][v & 7] = (__bf16)p0;
+            pf[n][u][(v & 7) + 1] = (__bf16)p1;
+          }
+      }
+      // ---- was the reference good enough?  (NaN -- a masked key against the initial reference of -inf -- and
+      // +inf -- anything against that reference -- both fail the comparison as written.)
+      trip = false;
+#pragma unroll
+      for (int n = 0; n < NQ; ++n) {
+        sum[n][0] += sum[n][1];
+        trip |= __builtin_amdgcn_ballot_w64(!(sum[n][0] <= kTripSum)) != 0;
+      }
     }
-    any_rescale = trip;
+    any_rescale = trip && !first;  // the first block leaves zeros in the accumulators: nothing to rescale
     if (__builtin_expect(trip, 0)) {
-      // Some query of the wave needs a new reference (always in the first block).  Now the maximum of the block
+      // Some query of the wave needs a new reference (or this is the first block).  Now the maximum of the block
       // is taken, per query over both lane halves; a query moves its reference to it only if it lies more than
       // kMaxLag powers of two above the old one (every lane that tripped does: its largest probability
       // exceeded kTripSum / 16 = 2^kMaxLag).  Then the block's probabilities are formed again.
