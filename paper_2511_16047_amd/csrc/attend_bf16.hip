@@ -157,9 +157,20 @@ struct TileLoader {
     long long step;     // bytes from a row to the row kTileKeys further on, in that segment
     bool scalar_ok;     // the scalar-base form of the load can address the segment (32-bit lane offsets)
     unsigned voff[kLoadsPerWave];  // per lane: byte offset of this lane's 16 bytes of load i from row `first`
-    // lane constants: row (inside the wave's part) and swizzled 16-byte chunk this lane fetches in load i
-    unsigned row[kLoadsPerWave], chunk[kLoadsPerWave];
   };
+  // Lane constants of load i, formed again where the rare paths need them (not held in registers): the row inside
+  // the wave's part and the byte offset of the swizzled 16-byte chunk this lane fetches.
+  // (the lane id goes through an empty asm so that nothing derived from it is kept from the prologue on)
+  __device__ static __forceinline__ int fresh(int lane) {
+    asm volatile("" : "+v"(lane));
+    return lane;
+  }
+  __device__ static __forceinline__ unsigned lane_row(int i, int lane) { return i * kRowsPerLoad + fresh(lane) / CPR; }
+  __device__ static __forceinline__ unsigned lane_chunk(int wave, int i, int lane) {
+    lane = fresh(lane);
+    const int row = (wave * kLoadsPerWave + i) * kRowsPerLoad + lane / CPR;  // row inside the tile
+    return 16u * ((lane % CPR) ^ swizzle<D>(row));
+  }
 
   __device__ static __forceinline__ void init(Stream& s, int wave, int lane) {
     s.first = wave * kRowsPerWave;
@@ -168,17 +179,12 @@ struct TileLoader {
     s.step = 0;
     s.scalar_ok = false;
 #pragma unroll
-    for (int i = 0; i < kLoadsPerWave; ++i) {
-      const int row = (wave * kLoadsPerWave + i) * kRowsPerLoad + lane / CPR;  // row inside the tile
-      s.chunk[i] = 16u * ((lane % CPR) ^ swizzle<D>(row));
-      s.row[i] = i * kRowsPerLoad + lane / CPR;
-      s.voff[i] = 0;
-    }
+    for (int i = 0; i < kLoadsPerWave; ++i) s.voff[i] = 0;
   }
 
   // Segment that holds virtual row s.first (< total), on the scalar unit.
   __device__ static __forceinline__ void find(Stream& s, const SegTable& seg, const char* kb, const char* vb, const char* xk,
-                                              const char* xv, long long x_tok) {
+                                              const char* xv, long long x_tok, int wave, int lane) {
     int end = seg.virt_start[0] + seg.len[0], delta = seg.phys_off[0] - seg.virt_start[0];
     for (int g = 1; g < seg.n; ++g)
       if (s.first >= seg.virt_start[g]) {
@@ -198,7 +204,7 @@ struct TileLoader {
     s.step = stride * kTileKeys;
     s.scalar_ok = stride < (1ll << 24);
 #pragma unroll
-    for (int i = 0; i < kLoadsPerWave; ++i) s.voff[i] = s.row[i] * (unsigned)stride + s.chunk[i];
+    for (int i = 0; i < kLoadsPerWave; ++i) s.voff[i] = lane_row(i, lane) * (unsigned)stride + lane_chunk(wave, i, lane);
   }
 
   // Fetch the wave's part of the next tile of the virtual concatenation into one ring slot (tiles are
@@ -208,7 +214,7 @@ struct TileLoader {
                                                long long x_tok, char* lds_k, char* lds_v, int t_kv, const SegTable& seg,
                                                int wave, int lane) {
     const int first = s.first;
-    if (__builtin_expect(first >= s.end && first < t_kv, 0)) find(s, seg, kb, vb, xk, xv, x_tok);
+    if (__builtin_expect(first >= s.end && first < t_kv, 0)) find(s, seg, kb, vb, xk, xv, x_tok, wave, lane);
     s.first = first + kTileKeys;
     if (__builtin_expect(first + kRowsPerWave <= s.end && s.scalar_ok, 1)) {
       // every row of the wave's part lies in one segment: scalar base, lane-constant offsets
@@ -227,10 +233,10 @@ struct TileLoader {
 #pragma unroll
     for (int i = 0; i < kLoadsPerWave; ++i) {
       const int blk = wave * kLoadsPerWave + i;  // which 1 KB block of the tile
-      const int row = blk * kRowsPerLoad + lane / CPR;
+      const int row = blk * kRowsPerLoad + fresh(lane) / CPR;
       bool ext;
       const int row_at = locate_row(seg, min(j0 + row, t_kv - 1), ext);
-      const long long off = (long long)row_at * (ext ? x_tok : (long long)RB) + s.chunk[i];
+      const long long off = (long long)row_at * (ext ? x_tok : (long long)RB) + lane_chunk(wave, i, lane);
       lds_dma16((ext ? xk : kb) + off, lds_k + blk * 1024);
       lds_dma16((ext ? xv : vb) + off, lds_v + blk * 1024);
     }
@@ -250,7 +256,7 @@ struct TileLoader {
 #pragma unroll
       for (int i = 0; i < kLoadsPerWave; ++i) {
         const int blk = wave * kLoadsPerWave + i;
-        const unsigned off = s.row[i] * RB + s.chunk[i];
+        const unsigned off = lane_row(i, lane) * RB + lane_chunk(wave, i, lane);
         *reinterpret_cast<uint4*>(kb + at + off) = *reinterpret_cast<const uint4*>(lds_k + blk * 1024 + 16 * lane);
         *reinterpret_cast<uint4*>(vb + at + off) = *reinterpret_cast<const uint4*>(lds_v + blk * 1024 + 16 * lane);
       }
@@ -259,9 +265,9 @@ struct TileLoader {
 #pragma unroll
     for (int i = 0; i < kLoadsPerWave; ++i) {
       const int blk = wave * kLoadsPerWave + i;
-      const int j = j0 + blk * kRowsPerLoad + lane / CPR;
+      const int j = j0 + blk * kRowsPerLoad + fresh(lane) / CPR;
       if (j >= seg.ext_start && j < t_kv) {
-        const long long dst = (long long)(wb_off + j - seg.ext_start) * RB + s.chunk[i];
+        const long long dst = (long long)(wb_off + j - seg.ext_start) * RB + lane_chunk(wave, i, lane);
         *reinterpret_cast<uint4*>(kb + dst) = *reinterpret_cast<const uint4*>(lds_k + blk * 1024 + 16 * lane);
         *reinterpret_cast<uint4*>(vb + dst) = *reinterpret_cast<const uint4*>(lds_v + blk * 1024 + 16 * lane);
       }
@@ -801,7 +807,7 @@ hipError_t launch_attend_density_bf16(const void* q, void* o, void* kc, void* vc
   // are split over workgroups with ids 8 apart, which re-read K~ and V~ from their XCD's L2.
   hipError_t e;
   if (head_dim == 64)
-    e = launch_density_variant<64, 1, 4, 32, 3>(q, o, kc, vc, bh, t_q, cap_tokens, seg, ext, io, c, groups, partial_ws, st);
+    e = launch_density_variant<64, 1, 4, 32, 4>(q, o, kc, vc, bh, t_q, cap_tokens, seg, ext, io, c, groups, partial_ws, st);
   else
     e = launch_density_variant<128, 1, 4, 32, 2>(q, o, kc, vc, bh, t_q, cap_tokens, seg, ext, io, c, groups, partial_ws, st);
   if (e != hipSuccess) return e;
