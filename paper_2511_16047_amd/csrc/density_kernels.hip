@@ -177,23 +177,32 @@ __global__ __launch_bounds__(64 * kWavesPerGroup) void density_partial_f32_kerne
 }
 
 // out[h][p] = (1/B) * sum over batch and query blocks of partial[(b,h), block][p], fixed order:
-// thread = p + 16*part walks every kParts-th unit of the head, then a tree over the parts in LDS.
-constexpr int kParts = 16;
+// thread = p + 16*part walks every kParts-th unit of the head, four independent sums at a time (the loads are
+// what the kernel waits for), then a tree over the parts in LDS.
+constexpr int kParts = 64;
 __global__ __launch_bounds__(16 * kParts) void density_total_kernel(const float* __restrict__ partial, int batch,
                                                                     int heads, int n_qblk, int n_seg,
                                                                     float* __restrict__ out) {
   __shared__ float red[kParts][16];
   const int hd = blockIdx.x;
   const int p = threadIdx.x & 15, part = threadIdx.x >> 4;
-  float acc = 0.f;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
   if (p < n_seg) {
     const int per_head = batch * n_qblk;
-    for (int i = part; i < per_head; i += kParts) {
+    auto at = [&](int i) {
       const int b = i / n_qblk, blk = i - b * n_qblk;
-      acc += partial[(((long long)b * heads + hd) * n_qblk + blk) * AMSKV_MAX_SCALES + p];
+      return partial[(((long long)b * heads + hd) * n_qblk + blk) * AMSKV_MAX_SCALES + p];
+    };
+    int i = part;
+    for (; i + 3 * kParts < per_head; i += 4 * kParts) {
+      acc[0] += at(i);
+      acc[1] += at(i + kParts);
+      acc[2] += at(i + 2 * kParts);
+      acc[3] += at(i + 3 * kParts);
     }
+    for (; i < per_head; i += kParts) acc[0] += at(i);
   }
-  red[part][p] = acc;
+  red[part][p] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
   __syncthreads();
   for (int m = kParts / 2; m > 0; m >>= 1) {
     if (part < m) red[part][p] += red[part + m][p];
