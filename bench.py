@@ -15,9 +15,10 @@ cache-demanding layers chosen by the similarity call (mean cosine < 0.5 -> keep 
 Prints ONE JSON line.  `value` is attention TFLOP/s over the whole step (FLOPs of the kept keys
 only, 4*B*H*T_q*T_kv*D per launch; the time includes append/evict and similarity).  Besides the
 headline fields the line carries
-  modes            the same inputs under three policies -- vanilla (every layer keeps everything), the
-                   benchmark's layer mix, every layer cache-efficient ({0,1} + window 2) -- with ms per
-                   step, attention ms and KV bytes each: the attention-latency comparison
+  modes            the same inputs under four policies -- vanilla (every layer keeps everything), the
+                   benchmark's layer mix, every layer cache-efficient ({0,1} + window 2), every layer at the
+                   paper's smallest budget ({0,1} + window 1) -- with ms per step, attention ms and KV bytes
+                   each: the attention-latency comparison
   other_workloads  the other shapes the contract names (VAR-d16 stack at batch 32, Infinity-2B shape at
                    batch 8, VAR-d30 at batch 128), each with its own roofline object
 (skipped with --quick, or when --workload / --mode select something else than the default).
@@ -524,14 +525,17 @@ def main():
                            "kv_bytes_held": out["kv_bytes_held"], "kv_bytes_held_excluding_current_scale": res["held_paper"],
                            "attention_flops_per_step": res["flops"], "cache_demanding_layers": out["config"]["cache_demanding_layers"]}}
         for name, p, what in (("vanilla", [(0, 0, True)] * L, "every layer keeps every scale"),
-                              ("efficient", list(w.policies), "every layer condensed {0,1} + window 2")):
+                              ("efficient", list(w.policies), "every layer condensed {0,1} + window 2"),
+                              ("efficient_window_1", [(2, 1, False)] * L,
+                               "every layer condensed {0,1} + the one preceding scale: the paper's C_min (first two scales + "
+                               "penultimate scale) expressed in scales")):
             r = measure(amskv, torch, x, dev, name, p, None, layout_name, borrow, fuse, max(3, args.steps // 3), 1, n_inst=2)
             release(amskv, r)
             modes[name] = {"what": what, "ms_per_step": r["ms_per_step"], "attend_ms_per_step": r["attend_ms"],
                            "kv_bytes_held": r["held"], "kv_bytes_held_excluding_current_scale": r["held_paper"],
                            "attention_flops_per_step": r["flops"], "cache_demanding_layers": sum(1 for q in p if q[2])}
         van = modes["vanilla"]
-        for name in ("amskv", "efficient"):
+        for name in ("amskv", "efficient", "efficient_window_1"):
             m = modes[name]
             m["attention_latency_reduction_vs_vanilla"] = 1.0 - m["attend_ms_per_step"] / van["attend_ms_per_step"]
             m["kv_reduction_vs_vanilla"] = 1.0 - m["kv_bytes_held"] / van["kv_bytes_held"]
