@@ -27,7 +27,12 @@
 // the probabilities of a block are formed against the reference the earlier blocks left, and only
 // when the sum of a lane's new probabilities shows that some score lay far above it (more than
 // 2^kMaxLag times) is the block's maximum taken, the reference moved and the block redone; the
-// accumulator rescale this requires is applied one step later.  The common block takes no maximum.
+// accumulator rescale this requires is applied one step later.  The common block takes no maximum.  A unit's
+// first block, which has no reference and nothing to multiply yet, goes straight to the maximum path.
+//
+// Density variant (attend_density_bf16_kernel): the same body with one more running sum per lane, over the keys of
+// the group of cached keys the stream is in; at the end of a group the per-row sum is parked in LDS, and the
+// epilogue turns the parked sums into the softmax mass per group (Section 4.1) next to O.
 //
 // Memory.  The kernel is HBM-bound at VAR shapes (arithmetic intensity T_q*T_kv/(T_q+T_kv)
 // flop/byte, below the chip's ridge), so the tile loop keeps tiles in flight (two at head dim 64):
