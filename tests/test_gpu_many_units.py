@@ -1,4 +1,4 @@
-"""GPU parity of the bf16 attention of the mid scales (33..128 query rows at head dim 64) at unit counts far
+"""GPU parity of the bf16 attention of the mid and last scales (33..256 query rows at head dim 64) at unit counts far
 above what the chip holds at once (several rounds of workgroups per compute unit), which the small parity cases
 never reach.  A few distinct units are repeated over a large batch: every copy must come out bit-identical to
 the first -- whatever round its workgroup ran in, whatever ran beside it -- and the first is held against the
@@ -84,6 +84,17 @@ SIDES = (6, 7, 9, 11)
 ], ids=["keep_all", "window", "window_fused_append", "window_borrowed"])
 def test_copies_match_the_first(copies, policy, layout, borrow, fuse):
     worst = _run(SIDES, copies, policy, layout, borrow, fuse)
+    print("%d units: worst max-abs %.3e" % (copies * H, worst))
+
+
+@pytest.mark.parametrize("copies", [100, 260], ids=["600_units", "1560_units"])
+@pytest.mark.parametrize("policy,layout,borrow,fuse", [
+    ((0, 0, True), amskv.AMSKV_LAYOUT_COMPACT, False, False),
+    ((1, 1, False), amskv.AMSKV_LAYOUT_PLANNED, True, True),
+], ids=["keep_all", "window_fused_append"])
+def test_copies_match_the_first_at_the_last_scales(copies, policy, layout, borrow, fuse):
+    # 144, 196 and 256 query rows (the eight-wave kernel; three, one and no idle waves), 144..596 keys
+    worst = _run((12, 14, 16), copies, policy, layout, borrow, fuse)
     print("%d units: worst max-abs %.3e" % (copies * H, worst))
 
 
