@@ -159,7 +159,7 @@ def dominant_kernel_name(w, tokens):
 
 
 def measure(amskv, torch, x, dev, mode, pols, budgets, layout_name, borrow, fuse, steps, warmup, per_scale=False, n_inst=3,
-            windows=None):
+            windows=None, graph_replay=True):
     """Timed steps, then instrumented passes with HIP events around every launch on the launch stream."""
     w = x.w
     B, H, D, L = w.batch, w.heads, w.head_dim, w.layers
@@ -208,7 +208,7 @@ def measure(amskv, torch, x, dev, mode, pols, budgets, layout_name, borrow, fuse
     # host side of the calls -- kept sets, slots, arguments -- then runs once, at capture).  Reported beside the
     # headline, never as it: what a serving loop with fixed buffers would see.
     graph_ms = None
-    if not token_mode:
+    if not token_mode and graph_replay:
         side = torch.cuda.Stream()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=side):
@@ -427,6 +427,9 @@ def main():
                          "step fills the scale's slot while it streams the scale)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--quick", action="store_true", help="headline measurement only: no modes, no other workloads")
+    ap.add_argument("--path-only", action="store_true",
+                    help="with --quick: nothing but the passes of the path itself (no stand-alone append pass, no density "
+                         "probe, no graph replay), so that a profiler's per-kernel means are means over the path's own launches")
     ap.add_argument("--per-scale", action="store_true", help="print a per-scale timing table to stderr")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 4 GiB device copy five times (reference dispatch of known size for "
@@ -482,9 +485,9 @@ def main():
         pols = mix
 
     res = measure(amskv, torch, x, dev, args.mode, pols, budgets, layout_name, borrow, fuse, args.steps, args.warmup,
-                  per_scale=args.per_scale, windows=windows)
-    sa = standalone_append(amskv, torch, x, dev, pols if pols is not None else list(w.policies))
-    dens = density_probe(amskv, torch, x, res) if pols is not None else None
+                  per_scale=args.per_scale, windows=windows, graph_replay=not args.path_only)
+    sa = None if args.path_only else standalone_append(amskv, torch, x, dev, pols if pols is not None else list(w.policies))
+    dens = density_probe(amskv, torch, x, res) if pols is not None and not args.path_only else None
     roof = res["roofline"]
 
     out = {
