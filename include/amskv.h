@@ -46,7 +46,8 @@ typedef enum {
   AMSKV_ERR_ARENA_TOO_SMALL = -4, /* arena_bytes < amskv_cache_required_bytes                 */
   AMSKV_ERR_HIP = -5,             /* a HIP runtime call failed (launch, copy, sync)          */
   AMSKV_ERR_NO_DEVICE_MEMORY = -6,/* device work asked of a plan-only cache (arena == NULL)  */
-  AMSKV_ERR_STATIC_LIMIT = -7     /* batch * heads beyond what the static workspace holds    */
+  AMSKV_ERR_STATIC_LIMIT = -7,    /* batch * heads beyond what the static workspace holds    */
+  AMSKV_ERR_NO_HOST_MEMORY = -8   /* a host allocation failed; destroy the cache             */
 } amskv_status;
 
 enum { AMSKV_DTYPE_F32 = 0, AMSKV_DTYPE_BF16 = 1 };

@@ -22,6 +22,7 @@ AMSKV_ERR_ARENA_TOO_SMALL = -4
 AMSKV_ERR_HIP = -5
 AMSKV_ERR_NO_DEVICE_MEMORY = -6
 AMSKV_ERR_STATIC_LIMIT = -7
+AMSKV_ERR_NO_HOST_MEMORY = -8
 AMSKV_STATIC_MAX_UNITS = 16384
 AMSKV_DTYPE_F32, AMSKV_DTYPE_BF16 = 0, 1
 AMSKV_LAYOUT_COMPACT, AMSKV_LAYOUT_PLANNED = 0, 1

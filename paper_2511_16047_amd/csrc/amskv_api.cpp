@@ -620,13 +620,14 @@ const char* amskv_status_string(int32_t st) {
     case AMSKV_ERR_HIP: return "HIP runtime error";
     case AMSKV_ERR_NO_DEVICE_MEMORY: return "plan-only cache has no device memory";
     case AMSKV_ERR_STATIC_LIMIT: return "batch * heads exceeds AMSKV_STATIC_MAX_UNITS, the size of the static workspace";
+    case AMSKV_ERR_NO_HOST_MEMORY: return "host memory allocation failed";
     default: return "unknown status";
   }
 }
 
 int32_t amskv_cache_required_bytes(int32_t layers, int32_t heads, int32_t head_dim,
                                    const amskv_schedule* sc, const amskv_policy* po,
-                                   uint64_t* bytes_out) {
+                                   uint64_t* bytes_out) try {
   if (!bytes_out) return AMSKV_ERR_INVALID_ARG;
   int rc = validate(layers, heads, head_dim, sc, po);
   if (rc) return rc;
@@ -634,11 +635,13 @@ int32_t amskv_cache_required_bytes(int32_t layers, int32_t heads, int32_t head_d
   build_plan(layers, heads, head_dim, sc, po, &pl);
   *bytes_out = pl.total;
   return AMSKV_OK;
+} catch (const std::bad_alloc&) {
+  return AMSKV_ERR_NO_HOST_MEMORY;  // nothing of the call may have taken effect on the host state that matters: callers destroy the cache
 }
 
 int32_t amskv_cache_create(int32_t layers, int32_t heads, int32_t head_dim,
                            const amskv_schedule* sc, const amskv_policy* po, void* arena_dev,
-                           uint64_t arena_bytes, amskv_cache** out) {
+                           uint64_t arena_bytes, amskv_cache** out) try {
   if (!out) return AMSKV_ERR_INVALID_ARG;
   *out = nullptr;
   int rc = validate(layers, heads, head_dim, sc, po);
@@ -650,7 +653,13 @@ int32_t amskv_cache_create(int32_t layers, int32_t heads, int32_t head_dim,
     if (arena_bytes < pl.total) return AMSKV_ERR_ARENA_TOO_SMALL;
   }
   amskv_cache* c = new (std::nothrow) amskv_cache();
-  if (!c) return AMSKV_ERR_INVALID_ARG;
+  if (!c) return AMSKV_ERR_NO_HOST_MEMORY;
+  struct Owner {  // destroys the half-built cache on every way out but the last
+    amskv_cache* c;
+    ~Owner() {
+      if (c) amskv_cache_destroy(c);
+    }
+  } owner{c};
   c->layers = layers;
   c->heads = heads;
   c->head_dim = head_dim;
@@ -694,17 +703,17 @@ int32_t amskv_cache_create(int32_t layers, int32_t heads, int32_t head_dim,
     bool ok = hipHostMalloc((void**)&c->theta_host, (size_t)layers * heads * 4 * sizeof(float), hipHostMallocDefault) == hipSuccess;
     for (int l = 0; ok && l < layers; ++l)
       ok = hipEventCreateWithFlags(&c->layer[l].test_done, hipEventDisableTiming) == hipSuccess;
-    if (!ok) {
-      amskv_cache_destroy(c);
-      return AMSKV_ERR_HIP;
-    }
+    if (!ok) return AMSKV_ERR_HIP;
   }
+  owner.c = nullptr;
   *out = c;
   return AMSKV_OK;
+} catch (const std::bad_alloc&) {
+  return AMSKV_ERR_NO_HOST_MEMORY;  // nothing of the call may have taken effect on the host state that matters: callers destroy the cache
 }
 
 int32_t amskv_append_scale(amskv_cache* c, int32_t layer, int32_t s, const void* K_dev,
-                           const void* V_dev, void* stream) {
+                           const void* V_dev, void* stream) try {
   if (bad_layer(c, layer) || s < 0 || s >= c->n_scales) return AMSKV_ERR_INVALID_ARG;
   if ((K_dev == nullptr) != (V_dev == nullptr) || misaligned(K_dev) || misaligned(V_dev)) return AMSKV_ERR_INVALID_ARG;
   LayerState& L = c->layer[layer];
@@ -789,6 +798,8 @@ int32_t amskv_append_scale(amskv_cache* c, int32_t layer, int32_t s, const void*
   L.last_evicted.swap(evicted);
   L.last_scale = s;
   return AMSKV_OK;
+} catch (const std::bad_alloc&) {
+  return AMSKV_ERR_NO_HOST_MEMORY;  // nothing of the call may have taken effect on the host state that matters: callers destroy the cache
 }
 
 static int density_launch(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev, hipStream_t st, SegTable* table,
@@ -867,14 +878,18 @@ static int attend_step(amskv_cache* c, int32_t layer, int32_t s, const void* Q_d
   return AMSKV_OK;
 }
 
-int32_t amskv_attend(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev, void* O_dev, void* stream) {
+int32_t amskv_attend(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev, void* O_dev, void* stream) try {
   return attend_step(c, layer, s, Q_dev, O_dev, stream, nullptr, nullptr, nullptr);
+} catch (const std::bad_alloc&) {
+  return AMSKV_ERR_NO_HOST_MEMORY;  // nothing of the call may have taken effect on the host state that matters: callers destroy the cache
 }
 
 int32_t amskv_attend_density(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev, void* O_dev, float* mass_out_dev,
-                             int32_t* n_seg, int32_t* tok_len, void* stream) {
+                             int32_t* n_seg, int32_t* tok_len, void* stream) try {
   if (!mass_out_dev || misaligned(mass_out_dev) || !n_seg) return AMSKV_ERR_INVALID_ARG;
   return attend_step(c, layer, s, Q_dev, O_dev, stream, mass_out_dev, n_seg, tok_len);
+} catch (const std::bad_alloc&) {
+  return AMSKV_ERR_NO_HOST_MEMORY;  // nothing of the call may have taken effect on the host state that matters: callers destroy the cache
 }
 
 // Checks shared by the two ways of asking for Eq. 3; on success cur/prev point at the two whole scales.
@@ -910,7 +925,7 @@ static void similarity_outputs(const amskv_cache* c, int s, bool has_v, const fl
 }
 
 int32_t amskv_interscale_similarity(amskv_cache* c, int32_t layer, int32_t s, float* cosK_host,
-                                    float* cosV_host, float* sums_host, void* stream) {
+                                    float* cosV_host, float* sums_host, void* stream) try {
   if (!cosK_host) return AMSKV_ERR_INVALID_ARG;
   const Segment *cur, *prev;
   int rc = similarity_operands(c, layer, s, &cur, &prev);
@@ -920,17 +935,21 @@ int32_t amskv_interscale_similarity(amskv_cache* c, int32_t layer, int32_t s, fl
   if (rc) return rc;
   similarity_outputs(c, s, cosV_host != nullptr, host.data(), cosK_host, cosV_host, sums_host);
   return AMSKV_OK;
+} catch (const std::bad_alloc&) {
+  return AMSKV_ERR_NO_HOST_MEMORY;  // nothing of the call may have taken effect on the host state that matters: callers destroy the cache
 }
 
-int32_t amskv_interscale_similarity_enqueue(amskv_cache* c, int32_t layer, int32_t s, int32_t want_v, void* stream) {
+int32_t amskv_interscale_similarity_enqueue(amskv_cache* c, int32_t layer, int32_t s, int32_t want_v, void* stream) try {
   const Segment *cur, *prev;
   int rc = similarity_operands(c, layer, s, &cur, &prev);
   if (rc) return rc;
   return similarity_launch(c, c->layer[layer], layer, *cur, *prev, s, want_v != 0, (hipStream_t)stream);
+} catch (const std::bad_alloc&) {
+  return AMSKV_ERR_NO_HOST_MEMORY;  // nothing of the call may have taken effect on the host state that matters: callers destroy the cache
 }
 
 int32_t amskv_interscale_similarity_enqueue_static(amskv_cache* c, int32_t layer, int32_t s, int32_t want_v,
-                                                   float* sums_out_dev, void* stream) {
+                                                   float* sums_out_dev, void* stream) try {
   if (!sums_out_dev || misaligned(sums_out_dev)) return AMSKV_ERR_INVALID_ARG;
   const Segment *cur, *prev;
   int rc = similarity_operands(c, layer, s, &cur, &prev);
@@ -941,10 +960,12 @@ int32_t amskv_interscale_similarity_enqueue_static(amskv_cache* c, int32_t layer
                                                  c->batch, c->heads, c->head_dim, c->dtype, c->side_h[s], c->side_w[s],
                                                  c->side_h[s - 1], c->side_w[s - 1], sums_out_dev, (hipStream_t)stream);
   return e == hipSuccess ? AMSKV_OK : AMSKV_ERR_HIP;
+} catch (const std::bad_alloc&) {
+  return AMSKV_ERR_NO_HOST_MEMORY;  // nothing of the call may have taken effect on the host state that matters: callers destroy the cache
 }
 
 int32_t amskv_interscale_similarity_collect(amskv_cache* c, float* cosK_host, float* cosV_host, float* sums_host,
-                                            void* stream) {
+                                            void* stream) try {
   if (!c || !cosK_host) return AMSKV_ERR_INVALID_ARG;
   if (!c->arena) return AMSKV_ERR_NO_DEVICE_MEMORY;
   const size_t per_layer = 2 * (size_t)c->heads * 4;
@@ -970,6 +991,8 @@ int32_t amskv_interscale_similarity_collect(amskv_cache* c, float* cosK_host, fl
     similarity_outputs(c, L.sim_scale, L.sim_has_v, host.data() + per_layer * l, ck, cv, sm);
   }
   return AMSKV_OK;
+} catch (const std::bad_alloc&) {
+  return AMSKV_ERR_NO_HOST_MEMORY;  // nothing of the call may have taken effect on the host state that matters: callers destroy the cache
 }
 
 // Checks and launch shared by the forms of the density call; the per-head masses end up at out_dev, or, when that
@@ -1000,7 +1023,7 @@ static int density_launch(amskv_cache* c, int32_t layer, int32_t s, const void* 
 }
 
 int32_t amskv_attention_density(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev, float* density_host,
-                                float* mass_host, int32_t* n_seg, void* stream) {
+                                float* mass_host, int32_t* n_seg, void* stream) try {
   if (!density_host && !mass_host) return AMSKV_ERR_INVALID_ARG;
   hipStream_t st = (hipStream_t)stream;
   SegTable t;
@@ -1020,10 +1043,12 @@ int32_t amskv_attention_density(amskv_cache* c, int32_t layer, int32_t s, const 
     }
   if (n_seg) *n_seg = t.n;
   return AMSKV_OK;
+} catch (const std::bad_alloc&) {
+  return AMSKV_ERR_NO_HOST_MEMORY;  // nothing of the call may have taken effect on the host state that matters: callers destroy the cache
 }
 
 int32_t amskv_attention_density_enqueue(amskv_cache* c, int32_t layer, int32_t s, const void* Q_dev, float* mass_out_dev,
-                                        int32_t* n_seg, int32_t* tok_len, void* stream) {
+                                        int32_t* n_seg, int32_t* tok_len, void* stream) try {
   if (!mass_out_dev || misaligned(mass_out_dev) || !n_seg) return AMSKV_ERR_INVALID_ARG;
   hipStream_t st = (hipStream_t)stream;
   SegTable t;
@@ -1034,10 +1059,12 @@ int32_t amskv_attention_density_enqueue(amskv_cache* c, int32_t layer, int32_t s
   if (tok_len)
     for (int p = 0; p < t.n; ++p) tok_len[p] = t.len[p];
   return AMSKV_OK;
+} catch (const std::bad_alloc&) {
+  return AMSKV_ERR_NO_HOST_MEMORY;  // nothing of the call may have taken effect on the host state that matters: callers destroy the cache
 }
 
 int32_t amskv_cache_layout(const amskv_cache* c, int32_t layer, int32_t* n_seg, int32_t* scale_id,
-                           int64_t* tok_offset, int32_t* tok_len) {
+                           int64_t* tok_offset, int32_t* tok_len) try {
   if (bad_layer(c, layer) || !n_seg) return AMSKV_ERR_INVALID_ARG;
   if (int rc = finish_iteration(c, layer)) return rc;
   const LayerState& L = c->layer[layer];
@@ -1048,10 +1075,12 @@ int32_t amskv_cache_layout(const amskv_cache* c, int32_t layer, int32_t* n_seg, 
     if (tok_len) tok_len[i] = L.segs[i].len;
   }
   return AMSKV_OK;
+} catch (const std::bad_alloc&) {
+  return AMSKV_ERR_NO_HOST_MEMORY;  // nothing of the call may have taken effect on the host state that matters: callers destroy the cache
 }
 
 int32_t amskv_cache_segments(const amskv_cache* c, int32_t layer, int32_t* n_seg, int32_t* scale_id,
-                             int32_t* first_token, int64_t* tok_offset, int32_t* tok_len) {
+                             int32_t* first_token, int64_t* tok_offset, int32_t* tok_len) try {
   if (bad_layer(c, layer) || !n_seg) return AMSKV_ERR_INVALID_ARG;
   if (int rc = finish_iteration(c, layer)) return rc;
   const LayerState& L = c->layer[layer];
@@ -1063,6 +1092,8 @@ int32_t amskv_cache_segments(const amskv_cache* c, int32_t layer, int32_t* n_seg
     if (tok_len) tok_len[i] = L.segs[i].len;
   }
   return AMSKV_OK;
+} catch (const std::bad_alloc&) {
+  return AMSKV_ERR_NO_HOST_MEMORY;  // nothing of the call may have taken effect on the host state that matters: callers destroy the cache
 }
 
 int64_t amskv_cache_budget_tokens(const amskv_cache* c, int32_t layer) {
@@ -1072,15 +1103,17 @@ int64_t amskv_cache_budget_tokens(const amskv_cache* c, int32_t layer) {
   return c->mode == AMSKV_MODE_TOKEN_BUDGET ? (int64_t)L.c_bgt : L.cap;
 }
 
-int32_t amskv_cache_settle(amskv_cache* c, int32_t layer, void* stream) {
+int32_t amskv_cache_settle(amskv_cache* c, int32_t layer, void* stream) try {
   if (bad_layer(c, layer)) return AMSKV_ERR_INVALID_ARG;
   LayerState& L = c->layer[layer];
   if (c->mode == AMSKV_MODE_TOKEN_BUDGET) return roll_budget(c, L, (hipStream_t)stream);
   return flush_pending(c, L, (hipStream_t)stream);
+} catch (const std::bad_alloc&) {
+  return AMSKV_ERR_NO_HOST_MEMORY;  // nothing of the call may have taken effect on the host state that matters: callers destroy the cache
 }
 
 int32_t amskv_cache_last_evicted(const amskv_cache* c, int32_t layer, int32_t* n_evicted,
-                                 int32_t* scale_id) {
+                                 int32_t* scale_id) try {
   if (bad_layer(c, layer) || !n_evicted) return AMSKV_ERR_INVALID_ARG;
   if (int rc = finish_iteration(c, layer)) return rc;
   const LayerState& L = c->layer[layer];
@@ -1088,6 +1121,8 @@ int32_t amskv_cache_last_evicted(const amskv_cache* c, int32_t layer, int32_t* n
   if (scale_id)
     for (size_t i = 0; i < L.last_evicted.size(); ++i) scale_id[i] = L.last_evicted[i];
   return AMSKV_OK;
+} catch (const std::bad_alloc&) {
+  return AMSKV_ERR_NO_HOST_MEMORY;  // nothing of the call may have taken effect on the host state that matters: callers destroy the cache
 }
 
 int64_t amskv_cache_bytes_held(const amskv_cache* c, int32_t layer, int32_t include_current) {
@@ -1106,7 +1141,7 @@ int64_t amskv_cache_capacity_tokens(const amskv_cache* c, int32_t layer) {
 }
 
 int32_t amskv_cache_export(const amskv_cache* c, int32_t layer, void* K_out_dev, void* V_out_dev,
-                           void* stream) {
+                           void* stream) try {
   if (bad_layer(c, layer) || (!K_out_dev && !V_out_dev)) return AMSKV_ERR_INVALID_ARG;
   if (!c->arena) return AMSKV_ERR_NO_DEVICE_MEMORY;
   if (int rc = finish_iteration(c, layer)) return rc;
@@ -1119,10 +1154,12 @@ int32_t amskv_cache_export(const amskv_cache* c, int32_t layer, void* K_out_dev,
                                       c->batch * c->heads, c->head_dim * c->elem_bytes, L.cap, t, ext,
                                       caller_map(c, L.segs.back().len, c->kv_tok), c->heads, (hipStream_t)stream);
   return e == hipSuccess ? AMSKV_OK : AMSKV_ERR_HIP;
+} catch (const std::bad_alloc&) {
+  return AMSKV_ERR_NO_HOST_MEMORY;  // nothing of the call may have taken effect on the host state that matters: callers destroy the cache
 }
 
 int32_t amskv_cache_set_io_layout(amskv_cache* c, int32_t io_layout, int64_t q_token_stride, int64_t kv_token_stride,
-                                  int64_t o_token_stride) {
+                                  int64_t o_token_stride) try {
   if (!c || (io_layout != AMSKV_IO_HEAD_MAJOR && io_layout != AMSKV_IO_TOKEN_MAJOR)) return AMSKV_ERR_INVALID_ARG;
   for (const LayerState& L : c->layer)
     if (L.last_scale >= 0) return AMSKV_ERR_ORDER;  // recorded K/V pointers would change meaning
@@ -1138,9 +1175,11 @@ int32_t amskv_cache_set_io_layout(amskv_cache* c, int32_t io_layout, int64_t q_t
   }
   c->io_layout = io_layout;
   return AMSKV_OK;
+} catch (const std::bad_alloc&) {
+  return AMSKV_ERR_NO_HOST_MEMORY;  // nothing of the call may have taken effect on the host state that matters: callers destroy the cache
 }
 
-int32_t amskv_cache_reset(amskv_cache* c) {
+int32_t amskv_cache_reset(amskv_cache* c) try {
   if (!c) return AMSKV_ERR_INVALID_ARG;
   for (LayerState& L : c->layer) {
     L.segs.clear();
@@ -1152,6 +1191,8 @@ int32_t amskv_cache_reset(amskv_cache* c) {
     L.sim_scale = -1;
   }
   return AMSKV_OK;
+} catch (const std::bad_alloc&) {
+  return AMSKV_ERR_NO_HOST_MEMORY;  // nothing of the call may have taken effect on the host state that matters: callers destroy the cache
 }
 
 void amskv_cache_destroy(amskv_cache* c) {

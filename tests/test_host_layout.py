@@ -226,6 +226,7 @@ def test_status_codes():
     finally:
         amskv.amskv_cache_destroy(h)
     assert amskv.status_string(0) == "ok" and "order" in amskv.status_string(-2)
+    assert "host memory" in amskv.status_string(amskv.AMSKV_ERR_NO_HOST_MEMORY)
 
 
 # ------------------------------------------------------------------ token-budget mode (Algorithms 1 and 2, literal)
