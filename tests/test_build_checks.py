@@ -33,3 +33,14 @@ def test_a_spill_or_a_missed_occupancy_fails_the_build(row, word):
     with pytest.raises(build.ResourceError) as e:
         build.check_resources([row])
     assert word in str(e.value)
+
+
+def test_public_header_is_plain_c():
+    """include/amskv.h is the boundary: it must compile by itself as C99 and as C++11 (no torch, no HIP types)."""
+    import os
+    import subprocess
+    header = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "amskv.h")
+    for cmd in (["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", header],
+                ["g++", "-std=c++11", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c++", header]):
+        p = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        assert p.returncode == 0, p.stdout
