@@ -20,7 +20,8 @@ headline fields the line carries
                    paper's smallest budget ({0,1} + window 1) -- with ms per step, attention ms and KV bytes
                    each: the attention-latency comparison
   other_workloads  the other shapes the contract names (VAR-d16 stack at batch 32, Infinity-2B shape at
-                   batch 8, VAR-d30 at batch 128), each with its own roofline object
+                   batch 8, VAR-d30 at batch 128) and VAR-d30 at batch 512 (twice the largest batch the paper
+                   reports; inputs and cache resident in one device's HBM), each with its own roofline object
 (skipped with --quick, or when --workload / --mode select something else than the default).
 """
 from __future__ import annotations
@@ -555,7 +556,7 @@ def main():
         del x
         torch.cuda.empty_cache()
         others = []
-        for key, batch, st in (("var_d30", 128, 5), ("var_d16", 0, 10), ("infinity_2b", 0, 3)):
+        for key, batch, st in (("var_d30", 128, 5), ("var_d30", 512, 3), ("var_d16", 0, 10), ("infinity_2b", 0, 3)):
             y = Inputs(key, batch, dev)
             p = probe_policies(amskv, torch, y, dev) if key == "var_d30" else list(y.w.policies)
             r = measure(amskv, torch, y, dev, "amskv", p, None, layout_name, borrow, fuse, st, 1, n_inst=2)
