@@ -367,3 +367,32 @@ def test_attend_density_token_budget_and_token_major():
                 assert got_ids == traces[l][s][0]
     finally:
         amskv.amskv_cache_destroy(h)
+
+
+def test_attend_density_argument_checks():
+    B, H, D = 1, 2, 64
+    sides = (1, 2, 7)
+    q, k, v = inp.iid_qkv(sides, B, H, D, "bf16", inp.layer_seed(8, 9))
+    qd, kd, vd = ([x.cuda() for x in t] for t in (q, k, v))
+    pol = (1, 1, False)
+    need = amskv.amskv_cache_required_bytes(1, H, D, sides, sides, B, BF16, [pol])
+    arena = torch.empty(need, dtype=torch.uint8, device="cuda")
+    h = amskv.amskv_cache_create(1, H, D, sides, sides, B, BF16, [pol], arena=arena)
+    mass = torch.empty(H * amskv.AMSKV_MAX_SCALES + 4, dtype=torch.float32, device="cuda")
+    try:
+        for s in range(len(sides)):
+            amskv.amskv_append_scale(h, 0, s, kd[s], vd[s])
+            o = torch.empty_like(qd[s])
+            if s < len(sides) - 1:
+                amskv.amskv_attend(h, 0, s, qd[s], o)
+        s = len(sides) - 1
+        o = torch.empty_like(qd[s])
+        for bad in (dict(mass=None), dict(mass=mass.data_ptr() + 4), dict(s=s - 1), dict(q=None), dict(o=None)):
+            with pytest.raises(amskv.AmskvError) as e:
+                amskv.amskv_attend_density(h, 0, bad.get("s", s), bad.get("q", qd[s]), bad.get("o", o), bad.get("mass", mass))
+            assert e.value.status == (amskv.AMSKV_ERR_ORDER if "s" in bad else amskv.AMSKV_ERR_INVALID_ARG)
+        lens = amskv.amskv_attend_density(h, 0, s, qd[s], o, mass)     # and the well-formed call still goes through
+        torch.cuda.synchronize()
+        assert lens == [1, 4, 49][-len(lens):] and abs(float(mass[: len(lens)].sum()) - 49.0) < 1e-2
+    finally:
+        amskv.amskv_cache_destroy(h)
