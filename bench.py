@@ -258,8 +258,14 @@ def measure(amskv, torch, x, dev, mode, pols, budgets, layout_name, borrow, fuse
         by = (2 * tokens[s] + 2 * kv_len[l][s]) * unit                    # Q read, O written, K~ and V~ read once
         roll = 2 * (2 * moved[l][s] + 2 * copied[l][s]) * unit             # K and V: read + write what moves or is copied in
         if token_mode:
-            if moved[l][s] == 0 and copied[l][s] == tokens[s]:
+            if s + 1 == S:
+                aby = 0.0                          # the iteration after the last step never runs (reset)
+            elif moved[l][s] == 0 and copied[l][s] == tokens[s]:
                 by += 2 * copied[l][s] * unit      # the scale fits untrimmed: the attend launch writes it as it streams it
+                aby = 0.0
+            elif windows is not None:
+                # no Eq. 3 test in the window modes: the attend launch also writes the survivors to their new places
+                by += 2 * (moved[l][s] + copied[l][s]) * unit
                 aby = 0.0
             else:
                 # the iteration runs in the layer's next append call; after the last step it never runs (reset)

@@ -311,7 +311,9 @@ SegTable seg_table(const LayerState& L, ExtKV* ext, bool merge = true) {
   SegTable t;
   std::memset(&t, 0, sizeof(t));
   ext->k = ext->v = nullptr;
-  ext->wb_off = -1;
+  ext->wb_from = amskv::kNoWriteBack;
+  ext->wb_delta = 0;
+  ext->wb_head_end = 0;
   int32_t v = 0;
   int32_t ext_start = -1;
   int n = 0;
@@ -446,12 +448,15 @@ int read_theta_test(amskv_cache* c, LayerState& L, bool* below) {
 // budget while it still is c_min), and applies Algorithm 2 to the token list (cached tokens
 // followed by the new scale): the first c_cds tokens and the last (budget - c_cds) tokens stay.
 // Survivors slide toward offset 0 and what stays of the new scale is copied behind them, in one launch.
-// appended_at >= 0: the attention kernel of this step has already written the whole scale into the cache at that
-// token offset (possible whenever the scale fits the budget without trimming), so nothing is left to copy.
+// on_device != kRollNone: the attention kernel of this step has already done the device side of the iteration --
+// written the whole scale behind the cached tokens (kRollAppended: the scale fits the budget without trimming), or
+// moved the survivors and written what stays of the scale (kRollTrimmed: the outcome was known before the step:
+// no Eq. 3 test due, one owner per unit) -- so only the host's list is left to update.
 // may_defer (amskv_attend): leave the iteration to the next call on the layer; if it needs the Eq. 3 score from
 // the device, enqueue the test now, so that the later call finds the result waiting.  An iteration that is never
 // asked for (a reset comes first, as after the last step of an image) costs no device work.
-int roll_budget(amskv_cache* c, LayerState& L, hipStream_t st, int32_t appended_at = -1, bool may_defer = false) {
+enum { kRollNone = 0, kRollAppended = 1, kRollTrimmed = 2 };
+int roll_budget(amskv_cache* c, LayerState& L, hipStream_t st, int on_device = kRollNone, bool may_defer = false) {
   if (!L.roll_pending) return AMSKV_OK;
   const Segment cur = L.segs.back();
   const int32_t t_new = cur.len;
@@ -465,7 +470,7 @@ int roll_budget(amskv_cache* c, LayerState& L, hipStream_t st, int32_t appended_
     // the part amskv_attend left: same state as then; what is enqueued goes behind that step's own work
     st = L.test_stream;
     L.deferred = false;
-  } else if (may_defer && appended_at < 0) {
+  } else if (may_defer && on_device == kRollNone) {
     if (wants_test) {
       int state = kTestFails;
       int rc = start_theta_test(c, L, cur, st, &state);
@@ -553,10 +558,12 @@ int roll_budget(amskv_cache* c, LayerState& L, hipStream_t st, int32_t appended_
     if (at > L.cap) return AMSKV_ERR_ARENA_TOO_SMALL;  // cannot happen: at <= budget <= c_max
   }
 
-  const bool copied_already = appended_at >= 0 && mv.n == 0 && copies.size() == 1 && copies[0].src_first == 0 &&
-                              copies[0].len == t_new && copies[0].dst == appended_at;
-  if (appended_at >= 0 && !copied_already) return AMSKV_ERR_INVALID_ARG;  // cannot happen: the caller used the same rule
-  if (c->arena && cur.ext_k && !copied_already && (mv.n > 0 || !copies.empty())) {
+  // (cannot fail: the caller derived what the launch writes from the same rule)
+  if (on_device == kRollAppended && !(mv.n == 0 && copies.size() == 1 && copies[0].src_first == 0 && copies[0].len == t_new &&
+                                      copies[0].dst == (int32_t)n_old))
+    return AMSKV_ERR_INVALID_ARG;
+  if (on_device == kRollTrimmed && (!cache_it || n_old + t_new <= bgt)) return AMSKV_ERR_INVALID_ARG;
+  if (c->arena && cur.ext_k && on_device == kRollNone && (mv.n > 0 || !copies.empty())) {
     const int bh = c->batch * c->heads;
     const int row_bytes = c->head_dim * c->elem_bytes;
     amskv::NewRanges nr;
@@ -842,14 +849,43 @@ static int attend_step(amskv_cache* c, int32_t layer, int32_t s, const void* Q_d
     }
   }
   Segment& newest = L.segs.back();
-  if (newest.pending) ext.wb_off = newest.off;  // fused append: this launch also fills the slot
-  // token-budget mode: when the scale fits the budget in force next to what is cached, Algorithm 1 keeps all of
-  // it, untrimmed, right behind the cached tokens -- known before the step runs, so the same launch writes it there
-  int32_t appended_at = -1;
-  if (c->mode == AMSKV_MODE_TOKEN_BUDGET) {
+  if (newest.pending) {  // fused append: this launch also fills the slot
+    ext.wb_from = t.ext_start;
+    ext.wb_delta = newest.off - t.ext_start;
+  }
+  // Token modes: whenever the outcome of the step's iteration of Algorithm 1 is known before the step runs, the
+  // same launch does its device side.  The scale fits the budget in force next to what is cached: it is written,
+  // whole, right behind the cached tokens.  It overflows, no Eq. 3 test is due (the budget cannot grow any more,
+  // or there is only one) and one workgroup or wave owns each (b,h): the survivors of Algorithm 2 -- the first
+  // c_cds tokens of the list stay where they are, the last budget - c_cds slide down behind them -- are written
+  // to their new places as they pass through the kernel, cached rows and rows of the new scale alike (the cached
+  // tokens are one run from offset 0, so a token's place in the list is its offset).
+  // (Not after the last scale of the schedule: no step follows that would read the result, and left to the next
+  // call the iteration is dropped by the reset that ends the image.)
+  int on_device = kRollNone;
+  if (c->mode == AMSKV_MODE_TOKEN_BUDGET && s + 1 < c->n_scales) {
     int64_t n_old = 0;
-    for (size_t i = 0; i + 1 < L.segs.size(); ++i) n_old += L.segs[i].len;
-    if (newest.len <= L.bud.c_max && n_old + newest.len <= L.c_bgt) ext.wb_off = appended_at = (int32_t)n_old;
+    bool one_run = true;
+    for (size_t i = 0; i + 1 < L.segs.size(); ++i) {
+      one_run = one_run && L.segs[i].off == n_old;
+      n_old += L.segs[i].len;
+    }
+    const int64_t total = n_old + newest.len;
+    const int32_t bgt = L.c_bgt;
+    const bool cache_it = c->cut_oversize || newest.len <= L.bud.c_max;
+    const bool overflow = cache_it && total > bgt;
+    const bool wants_test = overflow && bgt == L.bud.c_min && L.bud.c_max > L.bud.c_min;
+    const bool one_owner = c->dtype == AMSKV_DTYPE_BF16 && (by_product ? c->tokens[s] <= 128 : amskv::attend_owns_unit(c->head_dim, c->tokens[s]));
+    if (cache_it && !overflow) {
+      ext.wb_from = t.ext_start;
+      ext.wb_delta = 0;
+      on_device = kRollAppended;
+    } else if (overflow && !wants_test && (c->cut_oversize || newest.len <= bgt) && one_owner && one_run && t.ext_start == n_old) {
+      ext.wb_head_end = L.bud.c_cds;
+      ext.wb_from = (int32_t)(total - (bgt - L.bud.c_cds));
+      ext.wb_delta = ext.wb_head_end - ext.wb_from;
+      on_device = kRollTrimmed;
+    }
   }
   const int bh = c->batch * c->heads;
   // the scale read in place, if any, is the newest one
@@ -874,7 +910,7 @@ static int attend_step(amskv_cache* c, int32_t layer, int32_t s, const void* Q_d
     newest.ext_k = newest.ext_v = nullptr;
   }
   // what is left of the iteration (anything, unless this launch wrote the whole scale to its place) waits for the next call on the layer
-  if (c->mode == AMSKV_MODE_TOKEN_BUDGET) return roll_budget(c, L, (hipStream_t)stream, appended_at, true);
+  if (c->mode == AMSKV_MODE_TOKEN_BUDGET) return roll_budget(c, L, (hipStream_t)stream, on_device, true);
   return AMSKV_OK;
 }
 

@@ -32,13 +32,29 @@ struct GroupEnds {
 
 // External (borrowed) K and V of the current scale in the caller's buffers (rows located by
 // CallerIo::kv), or null pointers.
-// wb_off >= 0 asks the attention kernel to also write the scale it streams from k/v into the
-// layer's K/V regions at that token offset (the append fused into the attention of its step).
+// The attention kernel can also write rows it streams into the layer's K/V regions (the append fused into the
+// attention of its step; in the token modes a whole iteration of Algorithm 1 -- survivors slide toward offset 0,
+// what stays of the new scale lands behind them): row j of the virtual concatenation goes to token offset
+// j + wb_delta when j >= wb_from, and to token offset j when ext_start <= j < wb_head_end.  Nothing is written with
+// wb_from >= total and wb_head_end <= ext_start (kNoWriteBack, 0).  A destination never lies above its source row,
+// and rows are streamed in ascending order by the one workgroup (or wave) that owns the unit, so a row is
+// overwritten only after that owner has fetched it; callers ask for cached rows to be moved only for launches
+// with one owner per unit (attend_owns_unit).
+constexpr int32_t kNoWriteBack = 0x7fffffff;
 struct ExtKV {
   const void* k;
   const void* v;
-  int32_t wb_off;
+  int32_t wb_from, wb_delta, wb_head_end;
 };
+__host__ __device__ inline bool writes_back(const ExtKV& e, int total, int ext_start) {
+  return e.wb_from < total || e.wb_head_end > ext_start;
+}
+// token offset row j is written to, or -1
+__host__ __device__ inline int write_back_row(const ExtKV& e, int j, int total, int ext_start) {
+  if (j >= total) return -1;
+  if (j >= e.wb_from) return j + e.wb_delta;
+  return j >= ext_start && j < e.wb_head_end ? j : -1;
+}
 
 // Where the rows of a tensor owned by the caller sit: row t of unit (b, h) starts, in bytes from
 // the tensor's base, at b*batch + h*head + t*tok (the D channels of a row are contiguous).
@@ -104,6 +120,9 @@ hipError_t launch_attend_bf16(const void* q, void* o, void* kc, void* vc, int bh
 // the per-head masses of the groups in out_dev (heads * AMSKV_MAX_SCALES floats; workspace as for launch_density).
 // Exists for t_q above the coarse-scale kernel's range only: attend_density_fused(t_q) tells.
 bool attend_density_fused(int t_q);
+// launch_attend_bf16 gives every (b,h) to one workgroup (or, on the coarse scales, one wave): the condition for
+// asking it to move cached rows (ExtKV)
+bool attend_owns_unit(int head_dim, int t_q);
 hipError_t launch_attend_density_bf16(const void* q, void* o, void* kc, void* vc, int batch, int heads, int t_q, int head_dim,
                                       int64_t cap_tokens, const SegTable& seg, const ExtKV& ext, const CallerIo& io,
                                       float softmax_scale, const GroupEnds& groups, float* partial_ws, float* out_dev,

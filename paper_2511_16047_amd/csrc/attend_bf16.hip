@@ -247,17 +247,18 @@ struct TileLoader {
     }
   }
 
-  // Fused append: copy the rows of the landed tile (first row j0) that belong to the current (external)
-  // scale from LDS into the scale's slot of the cache.  Each wave stores exactly the 1 KB blocks it fetched,
+  // Fused append / fused iteration: copy the rows of the landed tile (first row j0) that ExtKV asks for from LDS
+  // to their place in the cache (the rows of the current scale into its slot; in the token modes also cached
+  // rows that slide toward offset 0).  Each wave stores exactly the 1 KB blocks it fetched,
   // so lane i re-reads its own 16 bytes at block + 16*i and the swizzle of issue() is undone by using the same
   // chunk mapping for the destination.  The stores are ordinary vector-memory operations issued before the
   // next tile's loads; the tile waits of the caller stay valid because a vmcnt wait only counts operations
   // (loads complete in order, and outstanding stores make the wait stricter, not laxer).
   __device__ static __forceinline__ void write_back(const Stream& s, char* kb, char* vb, const char* lds_k, const char* lds_v,
-                                                    int j0, int t_kv, const SegTable& seg, int wb_off, int wave, int lane) {
+                                                    int j0, int t_kv, const SegTable& seg, const ExtKV& ext, int wave, int lane) {
     const int first = j0 + wave * kRowsPerWave;  // wave-uniform
-    if (__builtin_expect(first >= seg.ext_start && first + kRowsPerWave <= t_kv, 1)) {  // all rows of the wave's part belong to the scale
-      const long long at = (long long)(wb_off + first - seg.ext_start) * RB;
+    if (__builtin_expect(first >= ext.wb_from && first + kRowsPerWave <= t_kv, 1)) {  // all rows of the wave's part move by wb_delta
+      const long long at = (long long)(first + ext.wb_delta) * RB;
 #pragma unroll
       for (int i = 0; i < kLoadsPerWave; ++i) {
         const int blk = wave * kLoadsPerWave + i;
@@ -271,8 +272,9 @@ struct TileLoader {
     for (int i = 0; i < kLoadsPerWave; ++i) {
       const int blk = wave * kLoadsPerWave + i;
       const int j = j0 + blk * kRowsPerLoad + fresh(lane) / CPR;
-      if (j >= seg.ext_start && j < t_kv) {
-        const long long dst = (long long)(wb_off + j - seg.ext_start) * RB + lane_chunk(wave, i, lane);
+      const int to = write_back_row(ext, j, t_kv, seg.ext_start);
+      if (to >= 0) {
+        const long long dst = (long long)to * RB + lane_chunk(wave, i, lane);
         *reinterpret_cast<uint4*>(kb + dst) = *reinterpret_cast<const uint4*>(lds_k + blk * 1024 + 16 * lane);
         *reinterpret_cast<uint4*>(vb + dst) = *reinterpret_cast<const uint4*>(lds_v + blk * 1024 + 16 * lane);
       }
@@ -351,7 +353,9 @@ __device__ __forceinline__ void attend_unit(
   const char* xv = (const char*)ext_kv.v + x_unit;
   const long long x_tok = io.kv.tok;
   // fused append: the workgroup of the first query tile also fills the current scale's slot
-  const bool write_back = ext_kv.wb_off >= 0 && q_tile == 0;
+  const bool write_back = writes_back(ext_kv, seg.total, seg.ext_start) && q_tile == 0;
+  // first row that is written anywhere
+  const int wb_first = min(ext_kv.wb_from, ext_kv.wb_head_end > seg.ext_start ? seg.ext_start : kNoWriteBack);
 
   // ---- prologue.  What the first matrix instruction waits for is kept small: the wave's own Q rows and tile 0.
   // Q goes through LDS like the tiles (direct-to-LDS loads, so every wait below is an explicit count and the
@@ -423,8 +427,8 @@ __device__ __forceinline__ void attend_unit(
       else wait_vmcnt<0>();
     }
     __syncthreads();
-    if (write_back && (it + 1) * kTileKeys > seg.ext_start)
-      Loader::write_back(stream, kb, vb, lds_k + sync_off, lds_v + sync_off, it * kTileKeys, t_kv, seg, ext_kv.wb_off, wave, lane);
+    if (write_back && (it + 1) * kTileKeys > wb_first)
+      Loader::write_back(stream, kb, vb, lds_k + sync_off, lds_v + sync_off, it * kTileKeys, t_kv, seg, ext_kv, wave, lane);
     sync_off = ring_next(sync_off, kTileBytes);
     if (kSteady || it + kAhead < n_tiles) {
       Loader::issue(stream, kb, vb, xk, xv, x_tok, lds_k + fetch_off, lds_v + fetch_off, t_kv, seg, wave, lane);
@@ -799,6 +803,8 @@ hipError_t launch_density_variant(const void* q, void* o, void* kc, void* vc, in
 }  // namespace
 
 bool attend_density_fused(int t_q) { return t_q > kSmallTq; }
+
+bool attend_owns_unit(int head_dim, int t_q) { return t_q <= (head_dim == 64 ? 256 : 128); }
 
 hipError_t launch_attend_density_bf16(const void* q, void* o, void* kc, void* vc, int batch, int heads, int t_q, int head_dim,
                                       int64_t cap_tokens, const SegTable& seg, const ExtKV& ext, const CallerIo& io,

@@ -85,7 +85,7 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, D == 64 ? 4 : 2) void attend_b
   const long long x_tok = io.kv.tok;
   const char* q_unit = (const char*)q + unit_offset(io.q, bh, io.heads);
   char* o_unit = (char*)o + unit_offset(io.o, bh, io.heads);
-  const bool write_back = ext_kv.wb_off >= 0 && q_base == 0;
+  const bool write_back = writes_back(ext_kv, seg.total, seg.ext_start) && q_base == 0;
 
   bf16x8 qf[KS];
   {
@@ -138,16 +138,18 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, D == 64 ? 4 : 2) void attend_b
     if (write_back) {
       // fused append: this unit also fills the current scale's slot from the registers it just used
       const int j0 = 32 * g;
-      if (j0 + r >= seg.ext_start && j0 + r < t_kv) {
-        char* dst = kb + (long long)(ext_kv.wb_off + j0 + r - seg.ext_start) * RB + 16 * h;
+      const int k_to = write_back_row(ext_kv, j0 + r, t_kv, seg.ext_start);
+      if (k_to >= 0) {
+        char* dst = kb + (long long)k_to * RB + 16 * h;
 #pragma unroll
         for (int t = 0; t < KS; ++t) *reinterpret_cast<bf16x8*>(dst + 32 * t) = kf[t];
       }
 #pragma unroll
       for (int k = 0; k < VCH; ++k) {
         const int row = k * (64 / CPR) + lane / CPR, c = (lane % CPR) ^ (row & 7);
-        if (j0 + row >= seg.ext_start && j0 + row < t_kv)
-          *reinterpret_cast<u32x4*>(vb + (long long)(ext_kv.wb_off + j0 + row - seg.ext_start) * RB + 16 * c) =
+        const int v_to = write_back_row(ext_kv, j0 + row, t_kv, seg.ext_start);
+        if (v_to >= 0)
+          *reinterpret_cast<u32x4*>(vb + (long long)v_to * RB + 16 * c) =
               *reinterpret_cast<const u32x4*>(my_v + k * 1024 + 16 * lane);
       }
     }

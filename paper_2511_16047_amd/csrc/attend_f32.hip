@@ -64,8 +64,9 @@ __global__ __launch_bounds__(kThreads) void attend_f32_kernel(const float* __res
           kk = *reinterpret_cast<const float4*>(kb + off);
           vv = *reinterpret_cast<const float4*>(vb + off);
         }
-        if (ext && ext_kv.wb_off >= 0 && blockIdx.y == 0) {  // fused append: fill the scale's slot while streaming it
-          const long long dst = (long long)ext_kv.wb_off * D + off;
+        const int to = write_back_row(ext_kv, j, t_kv, seg.ext_start);
+        if (ext && to >= 0 && blockIdx.y == 0) {  // fused append: fill the scale's slot while streaming it
+          const long long dst = (long long)to * D + 4 * c;
           *reinterpret_cast<float4*>(kb + dst) = kk;
           *reinterpret_cast<float4*>(vb + dst) = vv;
         }
