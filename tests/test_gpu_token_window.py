@@ -103,7 +103,12 @@ def test_var_schedule(dtype, window, n_sink):
     ((2, 3, 5, 7, 11), 1, 5, 64, 40, 4),     # ragged: 121-token final scale, cut
     ((3, 1, 4, 1, 5), 2, 2, 128, 17, 9),     # head dim 128, the sinks end inside a scale
     ((1, 2, 3, 4, 6, 9, 13, 18, 24), 1, 2, 128, 300, 5),   # several query tiles per unit at head dim 128
-], ids=["ragged", "d128_sink_inside_scale", "d128_multi_tile"])
+    ((6, 3, 4, 7), 2, 3, 64, 20, 8),         # the first scale is larger than the window: sinks and tail both cut from it
+    ((5, 2, 4), 2, 3, 64, 10, 4),            # the same on the coarse-scale kernel (25 query rows)
+    ((6, 2, 5), 1, 2, 128, 20, 8),           # ... and at head dim 128
+    ((12, 14, 16), 1, 2, 64, 150, 6),        # the eight-wave kernel moves cached rows (144..256 query rows)
+], ids=["ragged", "d128_sink_inside_scale", "d128_multi_tile", "sinks_in_new_scale", "sinks_in_new_scale_coarse",
+        "sinks_in_new_scale_d128", "last_scales"])
 def test_other_schedules(case):
     sides, B, H, D, window, n_sink = case
     _run(sides, B, H, D, "bf16", window, n_sink, inp.layer_seed(8, 100 + window))
