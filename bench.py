@@ -19,8 +19,8 @@ headline fields the line carries
                    benchmark's layer mix, every layer cache-efficient ({0,1} + window 2), every layer at the
                    paper's smallest budget ({0,1} + window 1) -- with ms per step, attention ms and KV bytes
                    each: the attention-latency comparison
-  other_workloads  the other shapes the contract names (VAR-d16 stack at batch 32, Infinity-2B shape at
-                   batch 8, VAR-d30 at batch 128) and VAR-d30 at batch 512 (twice the largest batch the paper
+  other_workloads  the other shapes the contract names (VAR-d16 stack at batch 32, VAR-d24 with ragged per-layer
+                   policies at batch 64, Infinity-2B shape at batch 8, VAR-d30 at batch 128) and VAR-d30 at batch 512 (twice the largest batch the paper
                    reports; inputs and cache resident in one device's HBM), each with its own roofline object
 (skipped with --quick, or when --workload / --mode select something else than the default).
 """
@@ -562,7 +562,7 @@ def main():
         del x
         torch.cuda.empty_cache()
         others = []
-        for key, batch, st in (("var_d30", 128, 5), ("var_d30", 512, 3), ("var_d16", 0, 10), ("infinity_2b", 0, 3)):
+        for key, batch, st in (("var_d30", 128, 5), ("var_d30", 512, 3), ("var_d16", 0, 10), ("var_d24", 0, 5), ("infinity_2b", 0, 3)):
             y = Inputs(key, batch, dev)
             p = probe_policies(amskv, torch, y, dev) if key == "var_d30" else list(y.w.policies)
             r = measure(amskv, torch, y, dev, "amskv", p, None, layout_name, borrow, fuse, st, 1, n_inst=2)
