@@ -568,6 +568,17 @@ def main():
             r = measure(amskv, torch, y, dev, "amskv", p, None, layout_name, borrow, fuse, st, 1, n_inst=2)
             release(amskv, r)
             others.append(workload_record(y.w, "amskv", layout_name, borrow, fuse, r))
+            if key == "var_d24":
+                # the sweep the configuration is named for: every layer at (condensed c, window w), all twelve corners
+                sweep = []
+                for cds in (1, 2, 3):
+                    for win in (1, 2, 3, 4):
+                        q = measure(amskv, torch, y, dev, "amskv", [(cds, win, False)] * y.w.layers, None, layout_name, borrow, fuse,
+                                    3, 1, n_inst=1, graph_replay=False)
+                        release(amskv, q)
+                        sweep.append({"condensed": cds, "window": win, "ms_per_step": q["ms_per_step"], "tflops": q["tflops"],
+                                      "kv_bytes_held": q["held"], "frac_of_hbm_roof": q["roofline"]["frac"]})
+                others[-1]["policy_sweep"] = sweep
             del y, r
             torch.cuda.empty_cache()
         out["other_workloads"] = others
