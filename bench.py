@@ -263,13 +263,11 @@ def measure(amskv, torch, x, dev, mode, pols, budgets, layout_name, borrow, fuse
             elif moved[l][s] == 0 and copied[l][s] == tokens[s]:
                 by += 2 * copied[l][s] * unit      # the scale fits untrimmed: the attend launch writes it as it streams it
                 aby = 0.0
-            elif windows is not None:
-                # no Eq. 3 test in the window modes: the attend launch also writes the survivors to their new places
+            else:
+                # the attend launch also writes the survivors to their new places (bf16, one workgroup per (b,h): every
+                # step of these shapes), whichever way an Eq. 3 test decided on the device in front of it comes out
                 by += 2 * (moved[l][s] + copied[l][s]) * unit
                 aby = 0.0
-            else:
-                # the iteration runs in the layer's next append call; after the last step it never runs (reset)
-                aby = roll if s + 1 < S else 0.0
         elif fuse:
             # the attend launch streams the scale anyway: only the write of K_s, V_s is extra
             by += 2 * copied[l][s] * unit

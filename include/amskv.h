@@ -151,13 +151,16 @@ typedef struct {
  * iteration for scale s (budget test, skip, Algorithm 2's trim, copy of what stays of scale s)
  * comes after that attention.  Whenever its outcome is known before the step runs, the attention
  * launch itself performs it and the iteration is complete when amskv_attend returns: the scale
- * fits the budget untrimmed (it is written behind the cached tokens); or it overflows a budget
- * that can no longer grow, so that no Eq. 3 test is due, on a bf16 cache at a step whose (b,h)
- * each belong to one workgroup (at most 256 query tokens at head dim 64, 128 at head dim 128):
- * the kernel then writes Algorithm 2's survivors -- cached tokens that slide toward offset 0 and
- * the kept part of the new scale -- to their new places as they stream through it (a token is
- * only ever written below the place it was read from, by the workgroup that has already read
- * everything below).  Not after the last scale of the schedule, whose iteration nobody reads.
+ * fits the budget untrimmed (it is written behind the cached tokens); or it overflows, on a bf16
+ * cache at a step whose (b,h) each belong to one workgroup (at most 256 query tokens at head dim
+ * 64, 128 at head dim 128): the kernel then writes Algorithm 2's survivors -- cached tokens that
+ * slide toward offset 0 and the kept part of the new scale -- to their new places as they stream
+ * through it (a token is only ever written below the place it was read from, by the workgroup
+ * that has already read everything below).  If the iteration needs the Eq. 3 score, the
+ * similarity kernels and a one-lane kernel that compares the score with theta are enqueued in
+ * front of the attention launch, which is handed both outcomes and follows the device's word;
+ * the host reads that word (one transfer, one event) when the next call on the layer needs the
+ * list.  Not after the last scale of the schedule, whose iteration nobody reads.
  * Otherwise amskv_attend leaves the iteration to the next call that reads or changes
  * the layer's state -- amskv_append_scale, amskv_cache_settle, any query, export -- which
  * enqueues its device work on the stream amskv_attend was given; amskv_cache_reset drops an

@@ -50,6 +50,7 @@ struct LayerState {
   // iteration needs the Eq. 3 score, the test has been enqueued and its sums are on their way to the host
   bool deferred = false;
   bool test_pending = false;
+  bool device_done = false;  // the deferred iteration's device side was done by the step's attention launch
   hipEvent_t test_done = nullptr;
   hipStream_t test_stream = nullptr;
 };
@@ -275,7 +276,8 @@ void build_plan(int32_t layers, int32_t heads, int32_t head_dim, const amskv_sch
   }
   pl->ws_off = at;
   // similarity workspace: per (tensor, b, h) four partial sums, then per (layer, tensor, h) four totals
-  at = align_up(at + (2 * bh * 4 + (uint64_t)layers * 2 * heads * 4) * sizeof(float));
+  // (and one word per layer for the outcome of Algorithm 1's test when it is decided on the device)
+  at = align_up(at + (2 * bh * 4 + (uint64_t)layers * 2 * heads * 4 + (uint64_t)layers) * sizeof(float));
   // attention-density workspace: per (b, h, block of 32 query rows) one partial sum per group of keys,
   // then per head one total per group
   int32_t t_max = 0;
@@ -311,9 +313,10 @@ SegTable seg_table(const LayerState& L, ExtKV* ext, bool merge = true) {
   SegTable t;
   std::memset(&t, 0, sizeof(t));
   ext->k = ext->v = nullptr;
-  ext->wb_from = amskv::kNoWriteBack;
-  ext->wb_delta = 0;
-  ext->wb_head_end = 0;
+  ext->wb_from = ext->alt_from = amskv::kNoWriteBack;
+  ext->wb_delta = ext->alt_delta = 0;
+  ext->wb_head_end = ext->alt_head_end = 0;
+  ext->alt_if = nullptr;
   int32_t v = 0;
   int32_t ext_start = -1;
   int n = 0;
@@ -350,6 +353,13 @@ inline bool whole_scale(const amskv_cache* c, const Segment& g, int s) {
 inline float* similarity_slot(const amskv_cache* c, int layer) {
   float* partial = (float*)(c->arena + c->ws_off);
   return partial + 2 * (uint64_t)c->batch * c->heads * 4 + (uint64_t)layer * 2 * c->heads * 4;
+}
+
+// Where the device leaves the outcome of a layer's Eq. 3 test (behind the slots of all layers), and where the
+// host finds its copy (behind the sums of all layers in the pinned block).
+inline int32_t* theta_flag_dev(const amskv_cache* c, int layer) { return (int32_t*)similarity_slot(c, c->layers) + layer; }
+inline int32_t* theta_flag_host(const amskv_cache* c, int layer) {
+  return (int32_t*)(c->theta_host + (size_t)c->layers * c->heads * 4) + layer;
 }
 
 // Eq. 3 between scale s (segment cur) and the upsampled scale s-1 (segment prev), both held
@@ -418,9 +428,14 @@ int start_theta_test(amskv_cache* c, LayerState& L, const Segment& cur, hipStrea
   const int layer = (int)(&L - c->layer.data());
   int rc = similarity_launch(c, L, layer, cur, *prev, cur.scale, false, st);
   if (rc) return rc;
+  // the decision is taken on the device (so that a launch behind it can act on it) and the host reads that word
+  if (amskv::launch_theta_flag(similarity_slot(c, layer), c->heads, (double)c->batch * c->tokens[cur.scale], L.bud.theta,
+                               theta_flag_dev(c, layer), st) != hipSuccess)
+    return AMSKV_ERR_HIP;
   const size_t n = (size_t)c->heads * 4;
   if (hipMemcpyAsync(c->theta_host + layer * n, similarity_slot(c, layer), n * sizeof(float), hipMemcpyDeviceToHost,
-                     st) != hipSuccess)
+                     st) != hipSuccess ||
+      hipMemcpyAsync(theta_flag_host(c, layer), theta_flag_dev(c, layer), sizeof(int32_t), hipMemcpyDeviceToHost, st) != hipSuccess)
     return AMSKV_ERR_HIP;
   if (hipEventRecord(L.test_done, st) != hipSuccess) return AMSKV_ERR_HIP;
   L.test_stream = st;
@@ -432,13 +447,7 @@ int start_theta_test(amskv_cache* c, LayerState& L, const Segment& cur, hipStrea
 int read_theta_test(amskv_cache* c, LayerState& L, bool* below) {
   if (hipEventSynchronize(L.test_done) != hipSuccess) return AMSKV_ERR_HIP;
   const int layer = (int)(&L - c->layer.data());
-  const float* host = c->theta_host + (size_t)layer * c->heads * 4;
-  const int32_t s = L.segs.back().scale;
-  double mean = 0.0;
-  const double n_tok = (double)c->batch * c->tokens[s];
-  for (int h = 0; h < c->heads; ++h) mean += (double)(float)(host[h * 4] / n_tok);
-  mean /= c->heads;
-  *below = mean < (double)L.bud.theta;
+  *below = *theta_flag_host(c, layer) != 0;
   return AMSKV_OK;
 }
 
@@ -451,11 +460,13 @@ int read_theta_test(amskv_cache* c, LayerState& L, bool* below) {
 // on_device != kRollNone: the attention kernel of this step has already done the device side of the iteration --
 // written the whole scale behind the cached tokens (kRollAppended: the scale fits the budget without trimming), or
 // moved the survivors and written what stays of the scale (kRollTrimmed: the outcome was known before the step:
-// no Eq. 3 test due, one owner per unit) -- so only the host's list is left to update.
+// no Eq. 3 test due, one owner per unit), or done whichever of the two the Eq. 3 test, decided on the device just
+// before the launch, called for (kRollEitherWay: the host learns the outcome later, so its part is deferred and
+// waits for the test's event) -- so only the host's list is left to update.
 // may_defer (amskv_attend): leave the iteration to the next call on the layer; if it needs the Eq. 3 score from
 // the device, enqueue the test now, so that the later call finds the result waiting.  An iteration that is never
 // asked for (a reset comes first, as after the last step of an image) costs no device work.
-enum { kRollNone = 0, kRollAppended = 1, kRollTrimmed = 2 };
+enum { kRollNone = 0, kRollAppended = 1, kRollTrimmed = 2, kRollEitherWay = 3 };
 int roll_budget(amskv_cache* c, LayerState& L, hipStream_t st, int on_device = kRollNone, bool may_defer = false) {
   if (!L.roll_pending) return AMSKV_OK;
   const Segment cur = L.segs.back();
@@ -470,6 +481,13 @@ int roll_budget(amskv_cache* c, LayerState& L, hipStream_t st, int on_device = k
     // the part amskv_attend left: same state as then; what is enqueued goes behind that step's own work
     st = L.test_stream;
     L.deferred = false;
+    if (L.device_done) on_device = kRollEitherWay;
+    L.device_done = false;
+  } else if (may_defer && on_device == kRollEitherWay) {
+    L.deferred = true;  // test_pending was set by the caller, which enqueued the test in front of its launch
+    L.device_done = true;
+    L.test_stream = st;
+    return AMSKV_OK;
   } else if (may_defer && on_device == kRollNone) {
     if (wants_test) {
       int state = kTestFails;
@@ -562,7 +580,6 @@ int roll_budget(amskv_cache* c, LayerState& L, hipStream_t st, int on_device = k
   if (on_device == kRollAppended && !(mv.n == 0 && copies.size() == 1 && copies[0].src_first == 0 && copies[0].len == t_new &&
                                       copies[0].dst == (int32_t)n_old))
     return AMSKV_ERR_INVALID_ARG;
-  if (on_device == kRollTrimmed && (!cache_it || n_old + t_new <= bgt)) return AMSKV_ERR_INVALID_ARG;
   if (c->arena && cur.ext_k && on_device == kRollNone && (mv.n > 0 || !copies.empty())) {
     const int bh = c->batch * c->heads;
     const int row_bytes = c->head_dim * c->elem_bytes;
@@ -707,7 +724,7 @@ int32_t amskv_cache_create(int32_t layers, int32_t heads, int32_t head_dim,
   }
   if (c->mode == AMSKV_MODE_TOKEN_BUDGET && c->arena) {
     // where the Eq. 3 sums of each layer's test arrive, and the event that says they have
-    bool ok = hipHostMalloc((void**)&c->theta_host, (size_t)layers * heads * 4 * sizeof(float), hipHostMallocDefault) == hipSuccess;
+    bool ok = hipHostMalloc((void**)&c->theta_host, ((size_t)layers * heads * 4 + layers) * sizeof(float), hipHostMallocDefault) == hipSuccess;
     for (int l = 0; ok && l < layers; ++l)
       ok = hipEventCreateWithFlags(&c->layer[l].test_done, hipEventDisableTiming) == hipSuccess;
     if (!ok) return AMSKV_ERR_HIP;
@@ -876,15 +893,43 @@ static int attend_step(amskv_cache* c, int32_t layer, int32_t s, const void* Q_d
     const bool overflow = cache_it && total > bgt;
     const bool wants_test = overflow && bgt == L.bud.c_min && L.bud.c_max > L.bud.c_min;
     const bool one_owner = c->dtype == AMSKV_DTYPE_BF16 && (by_product ? c->tokens[s] <= 128 : amskv::attend_owns_unit(c->head_dim, c->tokens[s]));
+    // what the launch writes under budget b: nothing (the scale is larger than the budget and is not cached), the
+    // whole scale behind the cached tokens, or Algorithm 2's survivors
+    auto plan = [&](int32_t b, int32_t* from, int32_t* delta, int32_t* head_end) {
+      *from = amskv::kNoWriteBack;
+      *delta = *head_end = 0;
+      if (newest.len > b && !c->cut_oversize) return;
+      if (total <= b) {
+        *from = t.ext_start;
+        return;
+      }
+      *head_end = L.bud.c_cds;
+      *from = (int32_t)(total - (b - L.bud.c_cds));
+      *delta = *head_end - *from;
+    };
     if (cache_it && !overflow) {
       ext.wb_from = t.ext_start;
       ext.wb_delta = 0;
       on_device = kRollAppended;
-    } else if (overflow && !wants_test && (c->cut_oversize || newest.len <= bgt) && one_owner && one_run && t.ext_start == n_old) {
-      ext.wb_head_end = L.bud.c_cds;
-      ext.wb_from = (int32_t)(total - (bgt - L.bud.c_cds));
-      ext.wb_delta = ext.wb_head_end - ext.wb_from;
-      on_device = kRollTrimmed;
+    } else if (overflow && one_owner && one_run && t.ext_start == n_old) {
+      if (!wants_test) {
+        plan(bgt, &ext.wb_from, &ext.wb_delta, &ext.wb_head_end);
+        on_device = kRollTrimmed;
+      } else {
+        // the test goes in front of the launch; if it needs the device, the launch is given both outcomes
+        int state = kTestFails;
+        if (int rc = start_theta_test(c, L, newest, (hipStream_t)stream, &state)) return rc;
+        if (state == kTestEnqueued) {
+          plan(bgt, &ext.wb_from, &ext.wb_delta, &ext.wb_head_end);
+          plan(L.bud.c_max, &ext.alt_from, &ext.alt_delta, &ext.alt_head_end);
+          ext.alt_if = theta_flag_dev(c, layer);
+          L.test_pending = true;
+          on_device = kRollEitherWay;
+        } else {
+          plan(state == kTestHolds ? L.bud.c_max : bgt, &ext.wb_from, &ext.wb_delta, &ext.wb_head_end);
+          on_device = kRollTrimmed;
+        }
+      }
     }
   }
   const int bh = c->batch * c->heads;
@@ -1223,7 +1268,7 @@ int32_t amskv_cache_reset(amskv_cache* c) try {
     L.last_scale = -1;
     L.c_bgt = L.bud.c_min;
     L.roll_pending = false;
-    L.deferred = L.test_pending = false;  // an enqueued test still runs; its result is not read
+    L.deferred = L.test_pending = L.device_done = false;  // an enqueued test still runs; its result is not read
     L.sim_scale = -1;
   }
   return AMSKV_OK;

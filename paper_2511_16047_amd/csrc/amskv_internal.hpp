@@ -40,15 +40,32 @@ struct GroupEnds {
 // and rows are streamed in ascending order by the one workgroup (or wave) that owns the unit, so a row is
 // overwritten only after that owner has fetched it; callers ask for cached rows to be moved only for launches
 // with one owner per unit (attend_owns_unit).
+// When the outcome of the iteration hangs on an Eq. 3 test that is decided on the device just before the launch,
+// both outcomes are handed over: alt_if points at the device word the test leaves (non-zero: the layer is
+// cache-demanding, the budget grows) and the alt_ triple replaces the wb_ triple when it is set.
 constexpr int32_t kNoWriteBack = 0x7fffffff;
 struct ExtKV {
   const void* k;
   const void* v;
   int32_t wb_from, wb_delta, wb_head_end;
+  const int32_t* alt_if;
+  int32_t alt_from, alt_delta, alt_head_end;
 };
 __host__ __device__ inline bool writes_back(const ExtKV& e, int total, int ext_start) {
   return e.wb_from < total || e.wb_head_end > ext_start;
 }
+#if defined(__HIPCC__)
+// the write-back the launch is to perform, the device's decision applied (uniform over the launch)
+__device__ inline ExtKV chosen(ExtKV e) {
+  if (e.alt_if != nullptr && *e.alt_if != 0) {
+    e.wb_from = e.alt_from;
+    e.wb_delta = e.alt_delta;
+    e.wb_head_end = e.alt_head_end;
+  }
+  e.alt_if = nullptr;
+  return e;
+}
+#endif
 // token offset row j is written to, or -1
 __host__ __device__ inline int write_back_row(const ExtKV& e, int j, int total, int ext_start) {
   if (j >= total) return -1;
@@ -171,6 +188,8 @@ hipError_t launch_similarity_static(const ScaleRef& cur, const ScaleRef& prev, i
 hipError_t launch_density(const void* q, const void* kc, int batch, int heads, int t_q, int head_dim, int dtype,
                           int64_t cap_tokens, const SegTable& pieces, const ExtKV& ext, const CallerIo& io,
                           float softmax_scale, float* partial_ws, float* out_dev, hipStream_t st);
+// Algorithm 1's test decided on the device: *flag_dev = (mean over heads of totals_dev[h*4] / n_tok) < theta
+hipError_t launch_theta_flag(const float* totals_dev, int heads, double n_tok, float theta, int32_t* flag_dev, hipStream_t st);
 // its second stage alone: out[h][p] = mean over the batch of the sum over the query blocks of partial_ws
 hipError_t launch_density_total(const float* partial_ws, int batch, int heads, int n_qblk, int n_groups, float* out_dev,
                                 hipStream_t st);

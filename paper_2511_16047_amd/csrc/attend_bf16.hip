@@ -761,8 +761,8 @@ template <int D, int NQ, int kWaves, int kTileKeys, int kMinWavesPerSimd>
 __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_bf16_kernel(
     const __bf16* __restrict__ q, __bf16* __restrict__ o, char* __restrict__ kc, char* __restrict__ vc,
     int t_q, long long cap_tokens, SegTable seg, ExtKV ext_kv, CallerIo io, float scale_log2e, int n_bh, int n_qtiles) {
-  attend_unit<D, NQ, kWaves, kTileKeys, false>(q, o, kc, vc, t_q, cap_tokens, seg, ext_kv, io, scale_log2e, n_bh, n_qtiles,
-                                               GroupEnds{}, nullptr);
+  attend_unit<D, NQ, kWaves, kTileKeys, false>(q, o, kc, vc, t_q, cap_tokens, seg, chosen(ext_kv), io, scale_log2e, n_bh,
+                                               n_qtiles, GroupEnds{}, nullptr);
 }
 
 // The same step with the attention density of its own queries as a by-product (no second pass over Q and K).
@@ -771,8 +771,8 @@ __global__ __launch_bounds__(64 * kWaves, kMinWavesPerSimd) void attend_density_
     const __bf16* __restrict__ q, __bf16* __restrict__ o, char* __restrict__ kc, char* __restrict__ vc,
     int t_q, long long cap_tokens, SegTable seg, ExtKV ext_kv, CallerIo io, float scale_log2e, int n_bh, int n_qtiles,
     GroupEnds groups, float* __restrict__ partial) {
-  attend_unit<D, NQ, kWaves, kTileKeys, true>(q, o, kc, vc, t_q, cap_tokens, seg, ext_kv, io, scale_log2e, n_bh, n_qtiles,
-                                              groups, partial);
+  attend_unit<D, NQ, kWaves, kTileKeys, true>(q, o, kc, vc, t_q, cap_tokens, seg, chosen(ext_kv), io, scale_log2e, n_bh,
+                                              n_qtiles, groups, partial);
 }
 
 template <int D, int NQ, int kWaves, int kTileKeys, int kMinWavesPerSimd>

@@ -59,7 +59,8 @@ __device__ __forceinline__ void settle_mfma(f32x16& acc) { asm volatile("s_nop 1
 template <int D>
 __global__ __launch_bounds__(64 * kWavesPerGroup, D == 64 ? 4 : 2) void attend_bf16_small_kernel(
     const __bf16* __restrict__ q, __bf16* __restrict__ o, char* __restrict__ kc, char* __restrict__ vc,
-    int t_q, long long cap_tokens, SegTable seg, ExtKV ext_kv, CallerIo io, float scale_log2e, int n_qblk, int n_units) {
+    int t_q, long long cap_tokens, SegTable seg, ExtKV ext_in, CallerIo io, float scale_log2e, int n_qblk, int n_units) {
+  const ExtKV ext_kv = chosen(ext_in);
   constexpr int RB = D * 2;
   constexpr int CPR = D / 8;
   constexpr int KS = D / 16;

@@ -142,6 +142,19 @@ __global__ __launch_bounds__(64) void similarity_total_kernel(const float* __res
     *reinterpret_cast<float4*>(totals + ((long long)tn * heads + h) * 4) = make_float4(acc[0], acc[1], acc[2], acc[3]);
 }
 
+// Algorithm 1's test on the device: flag = (mean over heads of the mean cosine < theta), from the per-head sums the
+// kernel above left (totals[h*4] = sum of the per-token cosines of K).  The arithmetic is spelled out so that the
+// host, given the same sums, would decide the same: per head the quotient in double rounded to float, their mean
+// in double, compared with theta in double.  One lane.
+__global__ __launch_bounds__(64) void theta_flag_kernel(const float* __restrict__ totals, int heads, double n_tok, float theta,
+                                                        int32_t* __restrict__ flag) {
+  if (threadIdx.x != 0) return;
+  double mean = 0.0;
+  for (int h = 0; h < heads; ++h) mean += (double)(float)((double)totals[h * 4] / n_tok);
+  mean /= heads;
+  *flag = mean < (double)theta ? 1 : 0;
+}
+
 // Partial-sum workspace of the entry point that allocates nothing: per (tensor, b, h) four floats, for up to
 // kStaticMaxUnits = batch * heads units and both tensors (512 KB).  Every device the library runs on holds its
 // own copy for the life of the process.
@@ -196,6 +209,11 @@ hipError_t launch_similarity(const ScaleRef& cur, const ScaleRef& prev, int batc
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(similarity_total_kernel, dim3(tensors * heads), dim3(64), 0, st, (const float*)partial_ws, batch,
                      heads, out_dev);
+  return hipGetLastError();
+}
+
+hipError_t launch_theta_flag(const float* totals_dev, int heads, double n_tok, float theta, int32_t* flag_dev, hipStream_t st) {
+  hipLaunchKernelGGL(theta_flag_kernel, dim3(1), dim3(64), 0, st, totals_dev, heads, n_tok, theta, flag_dev);
   return hipGetLastError();
 }
 

@@ -31,6 +31,7 @@ hipError_t launch_similarity_static(const ScaleRef&, const ScaleRef&, int, int, 
                                     hipStream_t) { std::abort(); }
 hipError_t launch_density(const void*, const void*, int, int, int, int, int, int64_t, const SegTable&, const ExtKV&,
                           const CallerIo&, float, float*, float*, hipStream_t) { std::abort(); }
+hipError_t launch_theta_flag(const float*, int, double, float, int32_t*, hipStream_t) { std::abort(); }
 bool attend_density_fused(int) { std::abort(); }
 bool attend_owns_unit(int, int) { return true; }
 hipError_t launch_attend_density_bf16(const void*, void*, void*, void*, int, int, int, int, int64_t, const SegTable&, const ExtKV&,
