@@ -7,44 +7,11 @@
 // free or undefined behaviour in the metadata code stops a test run.
 #include <cstdio>
 #include <cstdlib>
+#include <cstring>
 #include <algorithm>
 #include <vector>
 
 #include "amskv_internal.hpp"
-
-// ---- the device side is not part of this build: the launchers and the two runtime calls the host layer
-// uses are stubs that fail loudly if the plan-only paths ever reach them
-namespace amskv {
-hipError_t launch_attend_bf16(const void*, void*, void*, void*, int, int, int, int64_t, const SegTable&, const ExtKV&,
-                              const CallerIo&, float, hipStream_t) { std::abort(); }
-hipError_t launch_attend_f32(const void*, void*, void*, void*, int, int, int, int64_t, const SegTable&, const ExtKV&,
-                             const CallerIo&, float, hipStream_t) { std::abort(); }
-hipError_t launch_append(void*, void*, const void*, const void*, int, int, int64_t, const MoveList&, int, int, int,
-                         const RowMap&, int, hipStream_t) { std::abort(); }
-hipError_t launch_roll(void*, void*, const void*, const void*, int, int, int64_t, const MoveList&, const NewRanges&,
-                       const RowMap&, int, hipStream_t) { std::abort(); }
-hipError_t launch_export(const void*, const void*, void*, void*, int, int, int64_t, const SegTable&, const ExtKV&,
-                         const RowMap&, int, hipStream_t) { std::abort(); }
-hipError_t launch_similarity(const ScaleRef&, const ScaleRef&, int, int, int, int, int, int, int, int, float*, float*,
-                             hipStream_t) { std::abort(); }
-hipError_t launch_similarity_static(const ScaleRef&, const ScaleRef&, int, int, int, int, int, int, int, int, float*,
-                                    hipStream_t) { std::abort(); }
-hipError_t launch_density(const void*, const void*, int, int, int, int, int, int64_t, const SegTable&, const ExtKV&,
-                          const CallerIo&, float, float*, float*, hipStream_t) { std::abort(); }
-hipError_t launch_theta_flag(const float*, int, double, float, int32_t*, hipStream_t) { std::abort(); }
-bool attend_density_fused(int) { std::abort(); }
-bool attend_owns_unit(int, int) { return true; }
-hipError_t launch_attend_density_bf16(const void*, void*, void*, void*, int, int, int, int, int64_t, const SegTable&, const ExtKV&,
-                                      const CallerIo&, float, const GroupEnds&, float*, float*, hipStream_t) { std::abort(); }
-}  // namespace amskv
-extern "C" hipError_t hipMemcpyAsync(void*, const void*, size_t, hipMemcpyKind, hipStream_t) { std::abort(); }
-extern "C" hipError_t hipStreamSynchronize(hipStream_t) { std::abort(); }
-extern "C" hipError_t hipHostMalloc(void**, size_t, unsigned int) { std::abort(); }
-extern "C" hipError_t hipHostFree(void*) { std::abort(); }
-extern "C" hipError_t hipEventCreateWithFlags(hipEvent_t*, unsigned) { std::abort(); }
-extern "C" hipError_t hipEventDestroy(hipEvent_t) { std::abort(); }
-extern "C" hipError_t hipEventRecord(hipEvent_t, hipStream_t) { std::abort(); }
-extern "C" hipError_t hipEventSynchronize(hipEvent_t) { std::abort(); }
 
 static int failures = 0;
 #define CHECK(cond)                                                          \
@@ -54,6 +21,139 @@ static int failures = 0;
       ++failures;                                                            \
     }                                                                        \
   } while (0)
+
+// ---- the device side is not part of this build.  On plan-only caches the launchers and runtime calls are stubs
+// that fail loudly if a host path ever reaches them.  In a dry run (g_dry) they emulate instead, on lists of token
+// ids, what the kernels would do to the cache of a one-layer cache whose arena is ordinary host memory: the
+// attention launch streams the rows its segment table names and writes back the rows its ExtKV asks for (one row
+// at a time, in stream order: a row the plan overwrites before it has been read shows up as a wrong id), the roll
+// launch moves and copies, the decision kernel answers g_outcome.  What the host layer then reports as the
+// layer's list must be what the emulated cache holds.
+static bool g_dry = false;
+static int g_outcome = 0;              // the device's answer to the Eq. 3 test
+static std::vector<int32_t> g_ids;     // token id at every cache offset, -1: never written
+static std::vector<int32_t> g_new;     // ids of the rows of the scale being appended
+static std::vector<int32_t> g_seen;    // ids the last attention launch streamed, in order
+static int g_attends = 0, g_rolls = 0, g_tests = 0;
+
+static hipError_t dry_attend(int64_t cap, const amskv::SegTable& seg, const amskv::ExtKV& ext) {
+  amskv::ExtKV e = ext;
+  if (e.alt_if != nullptr && *e.alt_if != 0) {
+    e.wb_from = e.alt_from;
+    e.wb_delta = e.alt_delta;
+    e.wb_head_end = e.alt_head_end;
+  }
+  ++g_attends;
+  g_seen.clear();
+  for (int g = 0; g < seg.n; ++g)
+    for (int i = 0; i < seg.len[g]; ++i) {
+      const int j = seg.virt_start[g] + i;
+      int32_t id = -1;
+      int64_t at = -1;
+      if (j >= seg.ext_start) {
+        CHECK(j - seg.ext_start < (int)g_new.size());
+        id = g_new[j - seg.ext_start];
+      } else {
+        at = seg.phys_off[g] + i;
+        CHECK(at >= 0 && at < cap);
+        id = g_ids[at];
+        CHECK(id >= 0);
+      }
+      g_seen.push_back(id);
+      const int to = amskv::write_back_row(e, j, seg.total, seg.ext_start);
+      if (to >= 0) {
+        CHECK(to < cap && to <= j && (at < 0 || to <= at));
+        g_ids[to] = id;
+      }
+    }
+  CHECK((int)g_seen.size() == seg.total);
+  return hipSuccess;
+}
+
+namespace amskv {
+hipError_t launch_attend_bf16(const void*, void*, void*, void*, int, int, int, int64_t cap, const SegTable& seg, const ExtKV& ext,
+                              const CallerIo&, float, hipStream_t) {
+  if (!g_dry) std::abort();
+  return dry_attend(cap, seg, ext);
+}
+hipError_t launch_attend_f32(const void*, void*, void*, void*, int, int, int, int64_t cap, const SegTable& seg, const ExtKV& ext,
+                             const CallerIo&, float, hipStream_t) {
+  if (!g_dry) std::abort();
+  CHECK(ext.alt_if == nullptr && (ext.wb_from >= seg.ext_start));   // the fp32 kernel writes rows of the new scale only
+  return dry_attend(cap, seg, ext);
+}
+hipError_t launch_append(void*, void*, const void*, const void*, int, int, int64_t, const MoveList&, int, int, int,
+                         const RowMap&, int, hipStream_t) { std::abort(); }
+hipError_t launch_roll(void*, void*, const void*, const void*, int, int, int64_t cap, const MoveList& mv, const NewRanges& nr,
+                       const RowMap&, int, hipStream_t) {
+  if (!g_dry) std::abort();
+  ++g_rolls;
+  for (int m = 0; m < mv.n; ++m) {
+    CHECK(mv.dst[m] < mv.src[m] && mv.src[m] + mv.len[m] <= cap);
+    for (int i = 0; i < mv.len[m]; ++i) g_ids[mv.dst[m] + i] = g_ids[mv.src[m] + i];
+  }
+  for (int r = 0; r < nr.n; ++r) {
+    CHECK(nr.dst[r] >= 0 && nr.dst[r] + nr.len[r] <= cap && nr.src_first[r] + nr.len[r] <= (int)g_new.size());
+    for (int i = 0; i < nr.len[r]; ++i) g_ids[nr.dst[r] + i] = g_new[nr.src_first[r] + i];
+  }
+  return hipSuccess;
+}
+hipError_t launch_export(const void*, const void*, void*, void*, int, int, int64_t, const SegTable&, const ExtKV&,
+                         const RowMap&, int, hipStream_t) { std::abort(); }
+hipError_t launch_similarity(const ScaleRef&, const ScaleRef&, int, int, int, int, int, int, int, int, float*, float*,
+                             hipStream_t) {
+  if (!g_dry) std::abort();
+  return hipSuccess;
+}
+hipError_t launch_similarity_static(const ScaleRef&, const ScaleRef&, int, int, int, int, int, int, int, int, float*,
+                                    hipStream_t) { std::abort(); }
+hipError_t launch_density(const void*, const void*, int, int, int, int, int, int64_t, const SegTable&, const ExtKV&,
+                          const CallerIo&, float, float*, float*, hipStream_t) { std::abort(); }
+hipError_t launch_theta_flag(const float*, int, double, float, int32_t* flag, hipStream_t) {
+  if (!g_dry) std::abort();
+  ++g_tests;
+  *flag = g_outcome;
+  return hipSuccess;
+}
+bool attend_density_fused(int) { std::abort(); }
+bool attend_owns_unit(int head_dim, int t_q) { return t_q <= (head_dim == 64 ? 256 : 128); }
+hipError_t launch_attend_density_bf16(const void*, void*, void*, void*, int, int, int, int, int64_t, const SegTable&, const ExtKV&,
+                                      const CallerIo&, float, const GroupEnds&, float*, float*, hipStream_t) { std::abort(); }
+}  // namespace amskv
+extern "C" hipError_t hipMemcpyAsync(void* dst, const void* src, size_t n, hipMemcpyKind, hipStream_t) {
+  if (!g_dry) std::abort();
+  std::memcpy(dst, src, n);
+  return hipSuccess;
+}
+extern "C" hipError_t hipStreamSynchronize(hipStream_t) { std::abort(); }
+extern "C" hipError_t hipHostMalloc(void** p, size_t n, unsigned int) {
+  if (!g_dry) std::abort();
+  *p = std::calloc(1, n);
+  return *p ? hipSuccess : hipErrorOutOfMemory;
+}
+extern "C" hipError_t hipHostFree(void* p) {
+  if (!g_dry) std::abort();
+  std::free(p);
+  return hipSuccess;
+}
+extern "C" hipError_t hipEventCreateWithFlags(hipEvent_t* e, unsigned) {
+  if (!g_dry) std::abort();
+  *e = reinterpret_cast<hipEvent_t>(std::malloc(1));
+  return hipSuccess;
+}
+extern "C" hipError_t hipEventDestroy(hipEvent_t e) {
+  if (!g_dry) std::abort();
+  std::free(e);
+  return hipSuccess;
+}
+extern "C" hipError_t hipEventRecord(hipEvent_t, hipStream_t) {
+  if (!g_dry) std::abort();
+  return hipSuccess;
+}
+extern "C" hipError_t hipEventSynchronize(hipEvent_t) {
+  if (!g_dry) std::abort();
+  return hipSuccess;
+}
 
 struct Sched {
   std::vector<int32_t> sides;
@@ -187,6 +287,80 @@ static void walk_token_window(const Sched& sc) {
   amskv_cache_destroy(h);
 }
 
+// Dry runs of the token modes through amskv_attend: the plan the attention launch is handed (ExtKV) must leave the
+// emulated cache exactly as the host's list says, whichever way the iteration is performed (by the launch, by a
+// roll launch of the next call, with the Eq. 3 test answered either way on the "device"), and the launch must
+// stream exactly the list as it was before the step followed by the new scale.
+static void dry_token_modes(const Sched& sc, int32_t dtype) {
+  const int n = (int)sc.sides.size();
+  std::vector<int32_t> start(n + 1, 0);
+  for (int i = 0; i < n; ++i) start[i + 1] = start[i] + sc.sides[i] * sc.sides[i];
+  struct Case { amskv_layer_budget b; int32_t mode; };
+  std::vector<Case> cases;
+  const int steps[] = {1, 5, 17, 60, 174, 274, 700};
+  for (int c_max : steps)
+    for (int c_min : steps)
+      for (int c_cds : {0, 1, 5, 30}) {
+        if (c_min > c_max || c_cds > c_min) continue;
+        cases.push_back({{c_min, c_max, c_cds, 0.5f}, AMSKV_MODE_TOKEN_BUDGET});
+        if (c_min == c_max) cases.push_back({{c_min, c_max, c_cds, 0.f}, AMSKV_MODE_TOKEN_WINDOW});
+      }
+  const int B = 1, H = 1, D = 64;
+  g_dry = true;
+  int variant = 0;
+  for (const Case& cs : cases)
+    for (int outcome = 0; outcome < 2; ++outcome, ++variant) {
+      amskv_schedule s{n, sc.sides.data(), sc.sides.data(), B, dtype};
+      amskv_policy p{1, nullptr, 0.f, AMSKV_LAYOUT_COMPACT, 0, 0, cs.mode, &cs.b};
+      uint64_t need = 0;
+      CHECK(amskv_cache_required_bytes(1, H, D, &s, &p, &need) == AMSKV_OK);
+      void* arena = std::aligned_alloc(256, (need + 255) / 256 * 256);
+      amskv_cache* h = nullptr;
+      CHECK(amskv_cache_create(1, H, D, &s, &p, arena, need, &h) == AMSKV_OK && h);
+      if (!h) {
+        std::free(arena);
+        continue;
+      }
+      g_outcome = outcome;
+      const int64_t cap = amskv_cache_capacity_tokens(h, 0);
+      g_ids.assign((size_t)std::max<int64_t>(cap, 1), -1);
+      char* fake = reinterpret_cast<char*>(arena);   // any aligned non-null address: the stubs never follow it
+      for (int step = 0; step < n; ++step) {
+        // (an iteration left over from the step before runs inside this append and copies from that step's scale)
+        CHECK(amskv_append_scale(h, 0, step, fake, fake, nullptr) == AMSKV_OK);
+        g_new.resize((size_t)(start[step + 1] - start[step]));
+        for (size_t i = 0; i < g_new.size(); ++i) g_new[i] = start[step] + (int32_t)i;
+        int32_t n_seg = 0;
+        std::vector<int32_t> scale(64), first(64), len(64);
+        std::vector<int64_t> off(64);
+        CHECK(amskv_cache_segments(h, 0, &n_seg, scale.data(), first.data(), off.data(), len.data()) == AMSKV_OK);
+        std::vector<int32_t> before;
+        for (int i = 0; i < n_seg; ++i)
+          for (int k = 0; k < len[i]; ++k) before.push_back(start[scale[i]] + first[i] + k);
+        const bool attend = (step + variant) % 4 != 0;   // now and then the step's attention never comes
+        if (attend) {
+          CHECK(amskv_attend(h, 0, step, fake, fake, nullptr) == AMSKV_OK);
+          CHECK(g_seen == before);
+        }
+        CHECK(amskv_cache_segments(h, 0, &n_seg, scale.data(), first.data(), off.data(), len.data()) == AMSKV_OK);
+        int64_t at = 0;
+        for (int i = 0; i < n_seg; ++i) {
+          if (off[i] < 0) {   // the new scale, still read in place: its iteration waits for the next append
+            CHECK(!attend && i == n_seg - 1);
+            continue;
+          }
+          CHECK(off[i] == at);   // one run from offset 0
+          for (int k = 0; k < len[i]; ++k) CHECK(g_ids[(size_t)(off[i] + k)] == start[scale[i]] + first[i] + k);
+          at += len[i];
+        }
+        CHECK(at <= amskv_cache_budget_tokens(h, 0) && at <= cap);
+      }
+      amskv_cache_destroy(h);
+      std::free(arena);
+    }
+  g_dry = false;
+}
+
 static void bad_arguments() {
   const int32_t sides[3] = {1, 2, 3};
   amskv_layer_policy pol{1, 1, 0};
@@ -216,8 +390,12 @@ int main() {
         for (int fuse : {0, 1}) walk_window(sc, layout, borrow, fuse);
     walk_budget(sc);
     walk_token_window(sc);
+    dry_token_modes(sc, AMSKV_DTYPE_BF16);
+    dry_token_modes(sc, AMSKV_DTYPE_F32);
   }
   bad_arguments();
-  std::printf("host sanitizer driver: %d check(s) failed\n", failures);
+  CHECK(g_attends > 1000 && g_rolls > 100 && g_tests > 100);   // the dry runs did reach all three kinds of launch
+  std::printf("host sanitizer driver: %d check(s) failed (%d attention launches, %d roll launches, %d tests emulated)\n", failures,
+              g_attends, g_rolls, g_tests);
   return failures ? 1 : 0;
 }
