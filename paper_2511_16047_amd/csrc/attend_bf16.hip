@@ -56,6 +56,8 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 // query-token count up to which the latency-oriented kernel of attend_bf16_small.hip is used
 constexpr int kSmallTq = 32;
@@ -731,18 +733,26 @@ __device__ __forceinline__ void attend_unit(
     const float total = run_sum[n] + __shfl_xor(run_sum[n], 32, 64);
     const float inv = 1.0f / total;
     const int row = q_base + 32 * n + r;
-    if (row < t_q) {
-      __bf16* dst = reinterpret_cast<__bf16*>(o_unit + row * io.o.tok);
+    // The lane halves hold alternate 8-byte pieces of a row (columns 8g + 4h ..); one lane swap per register
+    // pairs them up, so that every lane stores 16 bytes and the two lanes of a row 32 contiguous bytes (half as
+    // many requests to the L2 as 8-byte stores: 2.4 % of the step at the default shape).
+    __bf16* dst = reinterpret_cast<__bf16*>(o_unit + min(row, t_q - 1) * io.o.tok);
 #pragma unroll
-      for (int d = 0; d < DB; ++d)
+    for (int d = 0; d < DB; ++d)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          bf16x4 w;
+      for (int k = 0; k < 2; ++k) {
+        bf16x4 wa, wb;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) w[e] = (__bf16)(oacc[n][d][4 * g + e] * inv);
-          *reinterpret_cast<bf16x4*>(dst + 32 * d + 8 * g + 4 * h) = w;
+        for (int e = 0; e < 4; ++e) {
+          wa[e] = (__bf16)(oacc[n][d][8 * k + e] * inv);
+          wb[e] = (__bf16)(oacc[n][d][8 * k + 4 + e] * inv);
         }
-    }
+        const u32x2 a = __builtin_bit_cast(u32x2, wa), b = __builtin_bit_cast(u32x2, wb);
+        const auto s0 = __builtin_amdgcn_permlane32_swap(a[0], b[0], false, false);
+        const auto s1 = __builtin_amdgcn_permlane32_swap(a[1], b[1], false, false);
+        const u32x4 w = {s0[0], s1[0], s0[1], s1[1]};
+        if (row < t_q) *reinterpret_cast<u32x4*>(dst + 32 * d + 16 * k + 8 * h) = w;
+      }
     if constexpr (kDensity) {
       // mass of the query block on group p = sum over its valid rows of (sum of exp over the group) / (sum over all keys)
       const int n_qblk = (t_q + 31) >> 5;

@@ -209,18 +209,26 @@ __global__ __launch_bounds__(64 * kWavesPerGroup, D == 64 ? 4 : 2) void attend_b
   const float total = run_sum + __shfl_xor(run_sum, 32, 64);
   const float inv = 1.0f / total;
   const int row = q_base + r;
-  if (row < t_q) {
-    __bf16* dst = reinterpret_cast<__bf16*>(o_unit + row * io.o.tok);
+  // The lane halves hold alternate 8-byte pieces of a row (columns 8g + 4h ..); one lane swap per register pairs
+  // them up, so that every lane stores 16 bytes and the two lanes of a row 32 contiguous bytes.
+  __bf16* dst = reinterpret_cast<__bf16*>(o_unit + min(row, t_q - 1) * io.o.tok);
 #pragma unroll
-    for (int d = 0; d < DB; ++d)
+  for (int d = 0; d < DB; ++d)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        bf16x4 w;
+    for (int k = 0; k < 2; ++k) {
+      typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+      bf16x4 wa, wb;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) w[e] = (__bf16)(oacc[d][4 * g + e] * inv);
-        *reinterpret_cast<bf16x4*>(dst + 32 * d + 8 * g + 4 * h) = w;
+      for (int e = 0; e < 4; ++e) {
+        wa[e] = (__bf16)(oacc[d][8 * k + e] * inv);
+        wb[e] = (__bf16)(oacc[d][8 * k + 4 + e] * inv);
       }
-  }
+      const u32x2 a = __builtin_bit_cast(u32x2, wa), b = __builtin_bit_cast(u32x2, wb);
+      const auto s0 = __builtin_amdgcn_permlane32_swap(a[0], b[0], false, false);
+      const auto s1 = __builtin_amdgcn_permlane32_swap(a[1], b[1], false, false);
+      const u32x4 w = {s0[0], s1[0], s0[1], s1[1]};
+      if (row < t_q) *reinterpret_cast<u32x4*>(dst + 32 * d + 16 * k + 8 * h) = w;
+    }
 }
 
 }  // namespace
