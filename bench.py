@@ -27,6 +27,7 @@ headline fields the line carries
 from __future__ import annotations
 
 import argparse
+import gc
 import glob
 import json
 import os
@@ -243,10 +244,17 @@ def measure(amskv, torch, x, dev, mode, pols, budgets, layout_name, borrow, fuse
     held = sum(amskv.amskv_cache_bytes_held(cache, l, True) for l in range(L))
     held_paper = sum(amskv.amskv_cache_bytes_held(cache, l, False) for l in range(L))
 
+    # the instrumented passes create two event objects per call: keep the interpreter's collector out of the intervals
+    # (a generation-2 pass between two event records once showed up as a 30 ms "append" that launches nothing)
     timers = []
-    for _ in range(n_inst):
-        one_step(timers)
-        torch.cuda.synchronize()
+    gc.collect()
+    gc.disable()
+    try:
+        for _ in range(n_inst):
+            one_step(timers)
+            torch.cuda.synchronize()
+    finally:
+        gc.enable()
     dom_rows = 128 if D == 64 and max(tokens) > 128 else 32    # launches of the dominant kernel: T_q above this
     dom_t = dom_bytes = dom_flops = 0.0
     dom_n = 0
