@@ -167,12 +167,13 @@ typedef struct {
  * iteration nobody asked for (after the last step of an image its result is never read).
  * If amskv_attend(s) is not called at all, the next amskv_append_scale or amskv_cache_settle
  * performs the iteration.
- * An iteration that needs the Eq. 3 score does not make amskv_attend wait: the call enqueues the
- * similarity kernels, a transfer of their sums into pinned host memory (allocated by
- * amskv_cache_create) and an event, and returns.  The call that later performs the iteration
- * waits for that event alone, not for the stream; Algorithm 1 needs the decision only before the
- * next scale is appended, and by then the device has long passed the test when other layers'
- * steps were enqueued in between.
+ * Where the launch cannot perform the iteration (fp32 caches, steps with more query tokens than
+ * one workgroup holds) and the iteration needs the Eq. 3 score, amskv_attend does not wait either:
+ * it enqueues the similarity kernels behind the attention, a transfer of their sums into pinned
+ * host memory (allocated by amskv_cache_create) and an event, and returns.  The call that later
+ * performs the iteration waits for that event alone, not for the stream; Algorithm 1 needs the
+ * decision only before the next scale is appended, and by then the device has long passed the
+ * test when other layers' steps were enqueued in between.
  * K_dev/V_dev of scale s must stay valid and unchanged until the iteration has run: until the
  * work enqueued by the next amskv_append_scale / amskv_cache_settle / query on the layer has
  * finished, or until amskv_cache_reset. */
