@@ -485,3 +485,35 @@ def test_similarity_enqueue_collect_matches_the_waiting_call():
         assert nan(ck)
     finally:
         r.close()
+
+
+@pytest.mark.parametrize("flags", [dict(), dict(fuse=True), dict(layout=amskv.AMSKV_LAYOUT_PLANNED, borrow=True, fuse=True)],
+                         ids=["copy", "fuse", "planned_borrow_fuse"])
+@pytest.mark.parametrize("dtype,D", [("bf16", 64), ("bf16", 128), ("f32", 64)])
+def test_several_attend_calls_within_one_step(dtype, D, flags):
+    """A step may be attended more than once (two sets of queries against the same keys): with fuse_append the first
+    call fills the slot and the later ones read it from the cache; every call must match the oracle, the same queries
+    must give the same bits, and the cache must end up as after a single call."""
+    sides = (1, 2, 4, 7, 10, 13)
+    pols = [(1, 2, False), (0, 0, True)]
+    B, H = 2, 3
+    r = Runner(sides, sides, B, H, D, dtype, pols, **flags)
+    try:
+        for layer, pol in enumerate(pols):
+            q, k, v = _qkv(sides, sides, B, H, D, dtype, 1500 + layer)
+            q2, _, _ = _qkv(sides, sides, B, H, D, dtype, 1600 + layer)
+            want = orc.attend_all_steps([_f64(x) for x in q], [_f64(x) for x in k], [_f64(x) for x in v], r.tokens, pol, None)
+            want2 = orc.attend_all_steps([_f64(x) for x in q2], [_f64(x) for x in k], [_f64(x) for x in v], r.tokens, pol, None)
+            for s in range(len(sides)):
+                amskv.amskv_append_scale(r.h, layer, s, k[s], v[s])
+                o = [torch.full_like(q[s], float("nan")) for _ in range(3)]
+                amskv.amskv_attend(r.h, layer, s, q[s], o[0])
+                amskv.amskv_attend(r.h, layer, s, q2[s], o[1])
+                amskv.amskv_attend(r.h, layer, s, q[s], o[2])
+                torch.cuda.synchronize()
+                assert np.abs(_f64(o[0]) - want[s]).max() <= TOL[dtype]
+                assert np.abs(_f64(o[1]) - want2[s]).max() <= TOL[dtype]
+                assert np.array_equal(_bits(o[0]), _bits(o[2])), (layer, s)
+                r.check_cache(layer, s, k, v)
+    finally:
+        r.close()
