@@ -1,7 +1,7 @@
 // Inter-scale similarity (Eq. 3): scale s-1 is resized bilinearly to the grid of scale s on
 // the fly (never materialised) and compared with scale s, straight from the cache.
 // Bandwidth-bound: each token row is read with 16-byte loads by consecutive lanes.
-// Reduction order is fixed (lane tree -> workgroup tree -> strided lanes and an xor tree over batch), so the
+// Reduction order is fixed (lanes of a token -> xor tree over a wave -> waves in order -> strided lanes and an xor tree over batch), so the
 // result is deterministic from run to run.
 #include "amskv_internal.hpp"
 
@@ -108,19 +108,21 @@ __global__ __launch_bounds__(kThreads) void similarity_partial_kernel(
     }
   }
 
-  __shared__ float red[4][kThreads];
-  red[0][threadIdx.x] = acc_cos;
-  red[1][threadIdx.x] = acc_ab;
-  red[2][threadIdx.x] = acc_aa;
-  red[3][threadIdx.x] = acc_bb;
+  // workgroup sum in a fixed order: xor tree over the lanes of a wave, then the waves in ascending order
+  float acc[4] = {acc_cos, acc_ab, acc_aa, acc_bb};
+#pragma unroll
+  for (int m = 32; m > 0; m >>= 1)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[q] += __shfl_xor(acc[q], m, 64);
+  __shared__ float red[kThreads / 64][4];
+  if ((threadIdx.x & 63) == 0)
+    for (int q = 0; q < 4; ++q) red[threadIdx.x >> 6][q] = acc[q];
   __syncthreads();
-  for (int m = kThreads / 2; m > 0; m >>= 1) {
-    if (threadIdx.x < m)
-      for (int q = 0; q < 4; ++q) red[q][threadIdx.x] += red[q][threadIdx.x + m];
-    __syncthreads();
+  if (threadIdx.x < 4) {
+    float total = red[0][threadIdx.x];
+    for (int w = 1; w < kThreads / 64; ++w) total += red[w][threadIdx.x];
+    partial[((long long)blockIdx.y * gridDim.x + bh) * 4 + threadIdx.x] = total;
   }
-  if (threadIdx.x < 4)
-    partial[((long long)blockIdx.y * gridDim.x + bh) * 4 + threadIdx.x] = red[threadIdx.x][0];
 }
 
 // totals[(tensor*H + h)*4 + q] = sum over b of partial[(tensor*B*H + b*H + h)*4 + q].
