@@ -153,6 +153,33 @@ def plan_trace(amskv, w, pols, budgets, layout, borrow, fuse, windows=None):
     return kv_len, moved, copied
 
 
+def step_accounting(w, t_kv, moved, copied, s, token_mode, fuse):
+    """(attention FLOPs, algorithmic bytes of the attend call, algorithmic bytes of the append call) of one layer's step
+    s, from the tokens the step attends to (`t_kv`, its own scale included) and the tokens its bookkeeping moves inside
+    the arena or copies into it (plan_trace).  FLOPs: 4 T_q T_kv D per (b,h) -- the kept keys only.  Bytes of the
+    attention: Q read, O written, K~ and V~ read once, plus what the same launch writes into the cache."""
+    tokens, S = w.tokens, len(w.tokens)
+    unit = w.head_dim * EB * w.batch * w.heads
+    by = (2 * tokens[s] + 2 * t_kv) * unit
+    roll = 2 * (2 * moved + 2 * copied) * unit                 # K and V: read + write what moves or is copied in
+    if token_mode:
+        aby = 0.0
+        if s + 1 == S:
+            pass                                   # the iteration after the last step never runs (reset)
+        elif moved == 0 and copied == tokens[s]:
+            by += 2 * copied * unit                # the scale fits untrimmed: the attend launch writes it as it streams it
+        else:
+            # the attend launch also writes the survivors to their new places (bf16, one workgroup per (b,h): every
+            # step of these shapes), whichever way an Eq. 3 test decided on the device in front of it comes out
+            by += 2 * (moved + copied) * unit
+    elif fuse:
+        by += 2 * copied * unit                    # the attend launch streams the scale anyway: only the write of K_s, V_s is extra
+        aby = 2 * 2 * moved * unit
+    else:
+        aby = roll
+    return 4.0 * w.batch * w.heads * tokens[s] * t_kv * w.head_dim, by, aby
+
+
 def dominant_kernel_name(w, tokens):
     D = w.head_dim
     if D == 128:
@@ -240,7 +267,7 @@ def measure(amskv, torch, x, dev, mode, pols, budgets, layout_name, borrow, fuse
         forced = [(a, b, c, 2.0 if expanded[l] else -2.0) for l, (a, b, c, _) in enumerate(budgets)]
         log("layers whose budget the Eq. 3 test expanded:", [l for l in range(L) if expanded[l]])
     kv_len, moved, copied = plan_trace(amskv, w, pols, forced, layout, borrow, fuse, windows)
-    flops = sum(4.0 * B * H * tokens[s] * kv_len[l][s] * D for l in range(L) for s in range(S))
+    flops = sum(step_accounting(w, kv_len[l][s], moved[l][s], copied[l][s], s, token_mode, fuse)[0] for l in range(L) for s in range(S))
     held = sum(amskv.amskv_cache_bytes_held(cache, l, True) for l in range(L))
     held_paper = sum(amskv.amskv_cache_bytes_held(cache, l, False) for l in range(L))
 
@@ -260,29 +287,9 @@ def measure(amskv, torch, x, dev, mode, pols, budgets, layout_name, borrow, fuse
     dom_n = 0
     att_t = app_t = att_bytes = app_bytes = 0.0
     scale_rows = [[0.0, 0.0, 0.0, 0.0] for _ in range(S)]
-    unit = D * EB * B * H
     for l, s, e in timers:
         ta, tt = e[0].elapsed_time(e[1]) * 1e-3, e[1].elapsed_time(e[2]) * 1e-3
-        by = (2 * tokens[s] + 2 * kv_len[l][s]) * unit                    # Q read, O written, K~ and V~ read once
-        roll = 2 * (2 * moved[l][s] + 2 * copied[l][s]) * unit             # K and V: read + write what moves or is copied in
-        if token_mode:
-            if s + 1 == S:
-                aby = 0.0                          # the iteration after the last step never runs (reset)
-            elif moved[l][s] == 0 and copied[l][s] == tokens[s]:
-                by += 2 * copied[l][s] * unit      # the scale fits untrimmed: the attend launch writes it as it streams it
-                aby = 0.0
-            else:
-                # the attend launch also writes the survivors to their new places (bf16, one workgroup per (b,h): every
-                # step of these shapes), whichever way an Eq. 3 test decided on the device in front of it comes out
-                by += 2 * (moved[l][s] + copied[l][s]) * unit
-                aby = 0.0
-        elif fuse:
-            # the attend launch streams the scale anyway: only the write of K_s, V_s is extra
-            by += 2 * copied[l][s] * unit
-            aby = 2 * 2 * moved[l][s] * unit
-        else:
-            aby = roll
-        fl = 4.0 * B * H * tokens[s] * kv_len[l][s] * D
+        fl, by, aby = step_accounting(w, kv_len[l][s], moved[l][s], copied[l][s], s, token_mode, fuse)
         att_t += tt; app_t += ta; att_bytes += by; app_bytes += aby
         r = scale_rows[s]
         r[0] += ta; r[1] += tt; r[2] += fl; r[3] += by
