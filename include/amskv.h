@@ -159,8 +159,8 @@ typedef struct {
  * that has already read everything below).  If the iteration needs the Eq. 3 score, the
  * similarity kernels and a one-lane kernel that compares the score with theta are enqueued in
  * front of the attention launch, which is handed both outcomes and follows the device's word;
- * the host reads that word (one transfer, one event) when the next call on the layer needs the
- * list.  Not after the last scale of the schedule, whose iteration nobody reads.
+ * the host reads that word (left in pinned host memory by the same kernel, behind one event) when
+ * the next call on the layer needs the list.  Not after the last scale of the schedule, whose iteration nobody reads.
  * Otherwise amskv_attend leaves the iteration to the next call that reads or changes
  * the layer's state -- amskv_append_scale, amskv_cache_settle, any query, export -- which
  * enqueues its device work on the stream amskv_attend was given; amskv_cache_reset drops an
@@ -169,8 +169,8 @@ typedef struct {
  * performs the iteration.
  * Where the launch cannot perform the iteration (fp32 caches, steps with more query tokens than
  * one workgroup holds) and the iteration needs the Eq. 3 score, amskv_attend does not wait either:
- * it enqueues the similarity kernels behind the attention, a transfer of their sums into pinned
- * host memory (allocated by amskv_cache_create) and an event, and returns.  The call that later
+ * it enqueues the similarity kernels behind the attention -- the last of them leaves the decision
+ * in pinned host memory (allocated by amskv_cache_create) -- and an event, and returns.  The call that later
  * performs the iteration waits for that event alone, not for the stream; Algorithm 1 needs the
  * decision only before the next scale is appended, and by then the device has long passed the
  * test when other layers' steps were enqueued in between.

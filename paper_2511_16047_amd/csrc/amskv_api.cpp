@@ -69,7 +69,7 @@ struct amskv_cache {
   uint64_t dens_off = 0;  // attention-density workspace
   int32_t io_layout = AMSKV_IO_HEAD_MAJOR;
   int64_t q_tok = 0, kv_tok = 0, o_tok = 0;  // token strides in elements (token-major tensors only)
-  float* theta_host = nullptr;  // token-budget mode: pinned, [layers][heads * 4], the sums of each layer's Eq. 3 test
+  float* theta_host = nullptr;  // token-budget mode: pinned; behind [layers][heads * 4] floats, one decision word per layer
   std::vector<LayerState> layer;
 };
 
@@ -410,8 +410,8 @@ int similarity_sums(amskv_cache* c, LayerState& L, int layer, const Segment& cur
 
 // Algorithm 1's test for a cache-demanding layer: Eq. 3 (cosine form, mean over heads) of the
 // newest scale against the scale before it, compared with theta.  Either the outcome is known
-// without device work (kTestFails, kTestHolds), or the kernels, the transfer of their sums into
-// the layer's pinned slot and an event behind them are enqueued (kTestEnqueued).
+// without device work (kTestFails, kTestHolds), or the kernels -- the last of which leaves the decision
+// word in the layer's pinned slot -- and an event behind them are enqueued (kTestEnqueued).
 enum { kTestFails = 0, kTestHolds = 1, kTestEnqueued = 2 };
 int start_theta_test(amskv_cache* c, LayerState& L, const Segment& cur, hipStream_t st, int* state) {
   *state = kTestFails;
@@ -428,14 +428,10 @@ int start_theta_test(amskv_cache* c, LayerState& L, const Segment& cur, hipStrea
   const int layer = (int)(&L - c->layer.data());
   int rc = similarity_launch(c, L, layer, cur, *prev, cur.scale, false, st);
   if (rc) return rc;
-  // the decision is taken on the device (so that a launch behind it can act on it) and the host reads that word
+  // the decision is taken on the device (so that a launch behind it can act on it); the same kernel leaves the word
+  // in pinned host memory, where the host reads it behind the event
   if (amskv::launch_theta_flag(similarity_slot(c, layer), c->heads, (double)c->batch * c->tokens[cur.scale], L.bud.theta,
-                               theta_flag_dev(c, layer), st) != hipSuccess)
-    return AMSKV_ERR_HIP;
-  const size_t n = (size_t)c->heads * 4;
-  if (hipMemcpyAsync(c->theta_host + layer * n, similarity_slot(c, layer), n * sizeof(float), hipMemcpyDeviceToHost,
-                     st) != hipSuccess ||
-      hipMemcpyAsync(theta_flag_host(c, layer), theta_flag_dev(c, layer), sizeof(int32_t), hipMemcpyDeviceToHost, st) != hipSuccess)
+                               theta_flag_dev(c, layer), theta_flag_host(c, layer), st) != hipSuccess)
     return AMSKV_ERR_HIP;
   if (hipEventRecord(L.test_done, st) != hipSuccess) return AMSKV_ERR_HIP;
   L.test_stream = st;
@@ -1280,7 +1276,7 @@ void amskv_cache_destroy(amskv_cache* c) {
   if (!c) return;
   for (LayerState& L : c->layer)
     if (L.test_done) {
-      (void)hipEventSynchronize(L.test_done);  // a transfer into theta_host may still be in flight
+      (void)hipEventSynchronize(L.test_done);  // a kernel that writes into theta_host may still be in flight
       (void)hipEventDestroy(L.test_done);
     }
   if (c->theta_host) (void)hipHostFree(c->theta_host);

@@ -189,7 +189,8 @@ hipError_t launch_density(const void* q, const void* kc, int batch, int heads, i
                           int64_t cap_tokens, const SegTable& pieces, const ExtKV& ext, const CallerIo& io,
                           float softmax_scale, float* partial_ws, float* out_dev, hipStream_t st);
 // Algorithm 1's test decided on the device: *flag_dev = (mean over heads of totals_dev[h*4] / n_tok) < theta
-hipError_t launch_theta_flag(const float* totals_dev, int heads, double n_tok, float theta, int32_t* flag_dev, hipStream_t st);
+hipError_t launch_theta_flag(const float* totals_dev, int heads, double n_tok, float theta, int32_t* flag_dev,
+                             int32_t* flag_host_pinned, hipStream_t st);
 // its second stage alone: out[h][p] = mean over the batch of the sum over the query blocks of partial_ws
 hipError_t launch_density_total(const float* partial_ws, int batch, int heads, int n_qblk, int n_groups, float* out_dev,
                                 hipStream_t st);

@@ -149,12 +149,14 @@ __global__ __launch_bounds__(64) void similarity_total_kernel(const float* __res
 // host, given the same sums, would decide the same: per head the quotient in double rounded to float, their mean
 // in double, compared with theta in double.  One lane.
 __global__ __launch_bounds__(64) void theta_flag_kernel(const float* __restrict__ totals, int heads, double n_tok, float theta,
-                                                        int32_t* __restrict__ flag) {
+                                                        int32_t* __restrict__ flag, int32_t* __restrict__ flag_host) {
   if (threadIdx.x != 0) return;
   double mean = 0.0;
   for (int h = 0; h < heads; ++h) mean += (double)(float)((double)totals[h * 4] / n_tok);
   mean /= heads;
-  *flag = mean < (double)theta ? 1 : 0;
+  const int32_t word = mean < (double)theta ? 1 : 0;
+  *flag = word;       // for the launch behind this one
+  *flag_host = word;  // pinned host memory: the host reads it behind the event, no transfer
 }
 
 // Partial-sum workspace of the entry point that allocates nothing: per (tensor, b, h) four floats, for up to
@@ -214,8 +216,9 @@ hipError_t launch_similarity(const ScaleRef& cur, const ScaleRef& prev, int batc
   return hipGetLastError();
 }
 
-hipError_t launch_theta_flag(const float* totals_dev, int heads, double n_tok, float theta, int32_t* flag_dev, hipStream_t st) {
-  hipLaunchKernelGGL(theta_flag_kernel, dim3(1), dim3(64), 0, st, totals_dev, heads, n_tok, theta, flag_dev);
+hipError_t launch_theta_flag(const float* totals_dev, int heads, double n_tok, float theta, int32_t* flag_dev,
+                             int32_t* flag_host_pinned, hipStream_t st) {
+  hipLaunchKernelGGL(theta_flag_kernel, dim3(1), dim3(64), 0, st, totals_dev, heads, n_tok, theta, flag_dev, flag_host_pinned);
   return hipGetLastError();
 }
 

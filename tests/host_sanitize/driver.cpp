@@ -109,10 +109,11 @@ hipError_t launch_similarity_static(const ScaleRef&, const ScaleRef&, int, int, 
                                     hipStream_t) { std::abort(); }
 hipError_t launch_density(const void*, const void*, int, int, int, int, int, int64_t, const SegTable&, const ExtKV&,
                           const CallerIo&, float, float*, float*, hipStream_t) { std::abort(); }
-hipError_t launch_theta_flag(const float*, int, double, float, int32_t* flag, hipStream_t) {
+hipError_t launch_theta_flag(const float*, int, double, float, int32_t* flag, int32_t* flag_host, hipStream_t) {
   if (!g_dry) std::abort();
   ++g_tests;
   *flag = g_outcome;
+  *flag_host = g_outcome;
   return hipSuccess;
 }
 bool attend_density_fused(int) { std::abort(); }
