@@ -20,7 +20,7 @@ def _build(exe):
     if shutil.which("gcc") is None:
         pytest.skip("no C compiler")
     assert os.path.exists(os.path.join(PKG, "libamskv.so")), "libamskv.so is not built (python -m paper_2511_16047_amd.build)"
-    cmd = ["gcc", "-std=c11", "-O2", "-Wall", "-Wextra", "-Werror", "-D__HIP_PLATFORM_AMD__", "-I" + os.path.join(ROCM, "include"),
+    cmd = ["gcc", "-std=c11", "-O2", "-Wall", "-Wextra", "-Werror", "-D__HIP_PLATFORM_AMD__", "-isystem", os.path.join(ROCM, "include"),
            "-I" + os.path.join(ROOT, "include"), os.path.join(ROOT, "tests", "c_abi", "abi_check.c"), "-o", exe,
            "-L" + PKG, "-lamskv", "-L" + os.path.join(ROCM, "lib"), "-lamdhip64", "-lm",
            "-Wl,-rpath," + PKG, "-Wl,-rpath," + os.path.join(ROCM, "lib")]
